@@ -1,0 +1,148 @@
+"""numpy front end of the CPU oracle (oracle/fxp_ref.cpp).
+
+TEST INFRASTRUCTURE: imported by tests/, __graft_entry__.smoke() and the
+cpu_baseline leg of bench.py only.  It never imports the GPU package.
+All arrays are host numpy arrays; every function returns new arrays.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+STOCHASTIC = 0
+NEAREST = 1
+TAG_X, TAG_W, TAG_DY = 0, 1, 2
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.LIB if os.path.exists(_build.LIB) else _build.build()
+        L = ctypes.CDLL(path)
+        c = ctypes
+        vp, i32, i64, u64, u32 = c.c_void_p, c.c_int32, c.c_int64, c.c_uint64, c.c_uint32
+        L.fxp_ref_num_threads.restype = c.c_int
+        L.fxp_ref_philox4x32_10.argtypes = [vp, vp, vp]
+        L.fxp_ref_philox4x32_10.restype = None
+        L.fxp_ref_random_word.argtypes = [u64, u64, u64]
+        L.fxp_ref_random_word.restype = u32
+        L.fxp_ref_scale.argtypes = [vp, u64, vp]
+        L.fxp_ref_map.argtypes = [vp, i64, i64, i32, vp, vp, u64, u64, c.c_int, c.c_int]
+        L.fxp_ref_gemm.argtypes = [c.c_int, c.c_int, i64, i64, i64, vp, i64, vp, i64, vp, i64]
+        L.fxp_ref_unmap.argtypes = [vp, u64, i32, c.c_int, i32, c.c_int, vp]
+        L.fxp_ref_unmap_i8.argtypes = [vp, u64, i32, c.c_int, vp]
+        L.fxp_ref_linear_fwd.argtypes = [vp, vp, i64, i64, i64, vp, vp, vp, vp, vp, u64, u64, c.c_int, c.c_int]
+        L.fxp_ref_linear_bwd.argtypes = [vp, vp, vp, i32, i32, i64, i64, i64, vp, vp, vp, vp, u64, u64, c.c_int,
+                                         c.c_int]
+        _lib = L
+    return _lib
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise ValueError(f"oracle {what} failed with code {rc}")
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _ptr(a):
+    return a.ctypes.data if a is not None else None
+
+
+def num_threads():
+    return int(lib().fxp_ref_num_threads())
+
+
+def philox4x32_10(ctr, key):
+    ctr = np.ascontiguousarray(ctr, dtype=np.uint32)
+    key = np.ascontiguousarray(key, dtype=np.uint32)
+    assert ctr.shape == (4,) and key.shape == (2,)
+    out = np.empty(4, dtype=np.uint32)
+    lib().fxp_ref_philox4x32_10(_ptr(ctr), _ptr(key), _ptr(out))
+    return out
+
+
+def random_word(seed, stream_id, i):
+    return int(lib().fxp_ref_random_word(seed, stream_id, i))
+
+
+def scale(x):
+    x = _f32(x)
+    e = np.zeros(1, dtype=np.int32)
+    _check(lib().fxp_ref_scale(_ptr(x), x.size, _ptr(e)), "scale")
+    return int(e[0])
+
+
+def map(x, e_max, seed=0, stream_id=0, rounding=STOCHASTIC, bits=8, transposed=False):
+    x = _f32(x)
+    assert x.ndim == 2
+    rows, cols = x.shape
+    q = np.empty((rows, cols), dtype=np.int8)
+    qT = np.empty((cols, rows), dtype=np.int8) if transposed else None
+    _check(lib().fxp_ref_map(_ptr(x), rows, cols, int(e_max), _ptr(q), _ptr(qT), seed, stream_id, rounding, bits),
+           "map")
+    return (q, qT) if transposed else q
+
+
+def gemm(A, B, transA=False, transB=False):
+    A = np.ascontiguousarray(A, dtype=np.int8)
+    B = np.ascontiguousarray(B, dtype=np.int8)
+    M, K = (A.shape[1], A.shape[0]) if transA else A.shape
+    Kb, N = (B.shape[1], B.shape[0]) if transB else B.shape
+    assert K == Kb, "contraction lengths differ"
+    C = np.empty((M, N), dtype=np.int32)
+    _check(lib().fxp_ref_gemm(int(transA), int(transB), M, N, K, _ptr(A), A.shape[1], _ptr(B), B.shape[1], _ptr(C),
+                              N), "gemm")
+    return C
+
+
+def unmap(acc, eA, eB=None, bitsA=8, bitsB=8):
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    out = np.empty(acc.shape, dtype=np.float32)
+    _check(lib().fxp_ref_unmap(_ptr(acc), acc.size, int(eA), bitsA, int(eB) if eB is not None else 0,
+                               bitsB if eB is not None else 0, _ptr(out)), "unmap")
+    return out
+
+
+def unmap_i8(q, eA, bits=8):
+    q = np.ascontiguousarray(q, dtype=np.int8)
+    out = np.empty(q.shape, dtype=np.float32)
+    _check(lib().fxp_ref_unmap_i8(_ptr(q), q.size, int(eA), bits, _ptr(out)), "unmap_i8")
+    return out
+
+
+def linear_fwd(X, W, seed=0, step=0, rounding=STOCHASTIC, bits=8):
+    """Returns Y and the saved state dict(Xq, Wq, eX, eW)."""
+    X, W = _f32(X), _f32(W)
+    M, K = X.shape
+    Kw, N = W.shape
+    assert K == Kw
+    Y = np.empty((M, N), dtype=np.float32)
+    Xq = np.empty((M, K), dtype=np.int8)
+    Wq = np.empty((K, N), dtype=np.int8)
+    eX = np.zeros(1, dtype=np.int32)
+    eW = np.zeros(1, dtype=np.int32)
+    _check(lib().fxp_ref_linear_fwd(_ptr(X), _ptr(W), M, K, N, _ptr(Y), _ptr(Xq), _ptr(Wq), _ptr(eX), _ptr(eW), seed,
+                                    step, rounding, bits), "linear_fwd")
+    return Y, dict(Xq=Xq, Wq=Wq, eX=int(eX[0]), eW=int(eW[0]))
+
+
+def linear_bwd(dY, saved, seed=0, step=0, rounding=STOCHASTIC, bits=8, need_dX=True, need_dW=True):
+    """Returns dX, dW and dict(dYq, eG)."""
+    dY = _f32(dY)
+    M, N = dY.shape
+    K = saved["Xq"].shape[1]
+    dX = np.empty((M, K), dtype=np.float32) if need_dX else None
+    dW = np.empty((K, N), dtype=np.float32) if need_dW else None
+    dYq = np.empty((M, N), dtype=np.int8)
+    eG = np.zeros(1, dtype=np.int32)
+    _check(lib().fxp_ref_linear_bwd(_ptr(dY), _ptr(saved["Xq"]), _ptr(saved["Wq"]), saved["eX"], saved["eW"], M, K, N,
+                                    _ptr(dX), _ptr(dW), _ptr(dYq), _ptr(eG), seed, step, rounding, bits),
+           "linear_bwd")
+    return dX, dW, dict(dYq=dYq, eG=int(eG[0]))

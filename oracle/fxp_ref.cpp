@@ -1,0 +1,291 @@
+// fxp_ref — CPU ORACLE for the integer (dynamic fixed-point) linear-layer step.
+//
+// THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow, obviously
+// correct CPU implementation that the GPU library is checked against.  Only the
+// test-suite, the smoke check and the benchmark's "cpu_baseline" leg may call
+// it.  It shares no source, header, table or helper with the HIP kernels and
+// neither side includes or links the other.
+//
+// Every function follows one passage of "Is Integer Arithmetic Enough for Deep
+// Learning Training?" (arXiv 2207.08822) in the paper's own order and notation:
+//   scale  — Sec. 3.1: e_max = max(e_1..e_n), the shared per-tensor scale.
+//   map    — Sec. 3.1 + App. A.1 (Fig. 4): unpack, shift the 24-bit mantissa
+//            right by e_max-e_i, round the result stochastically to 7 bits by
+//            comparing a random number with the low 17 bits, attach the sign.
+//   gemm   — Sec. 3.3 (Fig. 2): int8 x int8 products accumulated in int32.
+//   unmap  — Sec. 3.2 (Fig. 1b): shared exponent (sum of the operand
+//            exponents, Sec. 3.3) + integer mantissa -> rounded, normalised,
+//            packed fp32.
+//   linear — App. A.2: Y = X W, dL/dW = X^T G, and dL/dX = G W^T (chain rule).
+// Random numbers: the paper only says they are generated on the fly; this
+// build fixes Philox-4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11), keyed by the
+// seed, with the tensor's stream id and the element index as the counter.
+//
+// Parity pins (tests that do not depend on this file's own formulas) exist for
+// every function: the paper's two worked examples, exact round trips, an exact
+// rational model, numpy int64 matmul, an integer round-to-nearest-even model,
+// 10^7-sample mean-error and closed-form variance tests, and, for the Philox
+// rounds, rocRAND's host-callable engine (an independent implementation of the
+// same published generator; the authors' known-answer vectors themselves are
+// not available offline).  No function is "parity unpinned".
+//
+// Build: g++ -O2 -fopenmp -shared -fPIC (see oracle/build.py).  OpenMP only
+// splits independent outer loops; results do not depend on the thread count.
+
+#include <cmath>
+#include <cstddef>
+#include <cstdint>
+#include <cstring>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+namespace {
+
+// ---- unpack (Sec. 3.1, "unpack to integer") --------------------------------
+struct Unpacked {
+    uint32_t s;  // sign bit
+    uint32_t e;  // 8-bit exponent field
+    uint32_t f;  // 23-bit fraction field
+};
+
+Unpacked unpack(float x) {
+    uint32_t b;
+    std::memcpy(&b, &x, sizeof b);
+    Unpacked u;
+    u.s = b >> 31;
+    u.e = (b >> 23) & 0xFFu;
+    u.f = b & 0x7FFFFFu;
+    return u;
+}
+
+// A sub-normal input (e == 0) has no hidden bit and weighs as much as e == 1.
+uint32_t effective_exponent(const Unpacked& u) { return u.e == 0 ? 1u : u.e; }
+
+// 24-bit mantissa: the 23 fraction bits plus the implicit hidden bit.
+uint32_t mantissa24(const Unpacked& u) { return (u.e == 0 ? 0u : 0x800000u) | u.f; }
+
+// ---- Philox-4x32-10 ---------------------------------------------------------
+void mulhilo(uint32_t a, uint32_t b, uint32_t& hi, uint32_t& lo) {
+    const uint64_t p = static_cast<uint64_t>(a) * static_cast<uint64_t>(b);
+    hi = static_cast<uint32_t>(p >> 32);
+    lo = static_cast<uint32_t>(p);
+}
+
+void philox4x32_10(const uint32_t ctr_in[4], const uint32_t key_in[2], uint32_t out[4]) {
+    const uint32_t MUL0 = 0xD2511F53u, MUL1 = 0xCD9E8D57u;   // round multipliers
+    const uint32_t WEYL0 = 0x9E3779B9u, WEYL1 = 0xBB67AE85u; // key increments
+    uint32_t c[4] = {ctr_in[0], ctr_in[1], ctr_in[2], ctr_in[3]};
+    uint32_t k[2] = {key_in[0], key_in[1]};
+    for (int round = 0; round < 10; ++round) {
+        if (round > 0) {
+            k[0] += WEYL0;
+            k[1] += WEYL1;
+        }
+        uint32_t hi0, lo0, hi1, lo1;
+        mulhilo(MUL0, c[0], hi0, lo0);
+        mulhilo(MUL1, c[2], hi1, lo1);
+        const uint32_t n0 = hi1 ^ c[1] ^ k[0];
+        const uint32_t n1 = lo1;
+        const uint32_t n2 = hi0 ^ c[3] ^ k[1];
+        const uint32_t n3 = lo0;
+        c[0] = n0; c[1] = n1; c[2] = n2; c[3] = n3;
+    }
+    out[0] = c[0]; out[1] = c[1]; out[2] = c[2]; out[3] = c[3];
+}
+
+// The 32-bit random word of element i of tensor-stream `stream_id`:
+// counter = (i/4 as 64 bits, stream_id as 64 bits), key = seed, word i mod 4.
+uint32_t random_word(uint64_t seed, uint64_t stream_id, uint64_t i) {
+    const uint64_t block = i >> 2;
+    const uint32_t ctr[4] = {static_cast<uint32_t>(block), static_cast<uint32_t>(block >> 32),
+                             static_cast<uint32_t>(stream_id), static_cast<uint32_t>(stream_id >> 32)};
+    const uint32_t key[2] = {static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32)};
+    uint32_t out[4];
+    philox4x32_10(ctr, key, out);
+    return out[i & 3u];
+}
+
+// ---- map of one element (Sec. 3.1, App. A.1) --------------------------------
+// bits = total width of the fixed-point value (sign + bits-1 magnitude bits);
+// the paper's int8 is bits = 8: 24-bit mantissa rounded to 7 bits using the
+// low 17 bits.  rounding 0 = stochastic, 1 = nearest (half up on magnitude).
+int32_t map_one(float x, int32_t e_max, uint32_t word, int rounding, int bits) {
+    const Unpacked u = unpack(x);
+    const int mag_bits = bits - 1;
+    const int cut = 24 - mag_bits;                   // number of low bits dropped
+    const uint32_t sat = (1u << mag_bits) - 1u;      // largest magnitude
+    uint32_t q1;
+    if (u.e == 255u) {
+        // not a number the format can carry: Inf saturates, NaN gives 0
+        q1 = (u.f == 0u) ? sat : 0u;
+    } else {
+        const int32_t d = e_max - static_cast<int32_t>(effective_exponent(u));
+        if (d < 0) {
+            q1 = sat;                                // above the range of this scale
+        } else {
+            const uint32_t m = mantissa24(u);
+            const uint32_t m_shift = (d >= 24) ? 0u : (m >> d);  // truncating right shift
+            const uint32_t q0 = m_shift >> cut;                  // bits kept
+            const uint32_t low = m_shift & ((1u << cut) - 1u);   // bits dropped
+            if (rounding == 0) {
+                const uint32_t r = word >> (32 - cut);           // uniform on [0, 2^cut)
+                q1 = q0 + ((r < low) ? 1u : 0u);                 // P(up) = low / 2^cut
+            } else {
+                q1 = (m_shift + (1u << (cut - 1))) >> cut;
+            }
+            if (q1 > sat) q1 = sat;
+        }
+    }
+    return u.s ? -static_cast<int32_t>(q1) : static_cast<int32_t>(q1);
+}
+
+// exponent of one unit of a mapped tensor: value = q * 2^lsb_exponent
+int32_t lsb_exponent(int32_t e_max, int bits) { return e_max - 127 - (bits - 2); }
+
+bool bad_bits(int bits) { return bits < 2 || bits > 8; }
+
+}  // namespace
+
+extern "C" {
+
+int fxp_ref_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void fxp_ref_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+    philox4x32_10(ctr, key, out);
+}
+
+uint32_t fxp_ref_random_word(uint64_t seed, uint64_t stream_id, uint64_t i) {
+    return random_word(seed, stream_id, i);
+}
+
+// Sec. 3.1: e_max = max_i e_i (sub-normals and zeros count as e = 1).
+int fxp_ref_scale(const float* x, uint64_t n, int32_t* e_max) {
+    if (!e_max || (n && !x)) return -1;
+    int32_t best = 1;
+#pragma omp parallel for reduction(max : best) schedule(static)
+    for (int64_t i = 0; i < static_cast<int64_t>(n); ++i) {
+        const int32_t e = static_cast<int32_t>(effective_exponent(unpack(x[i])));
+        if (e > best) best = e;
+    }
+    *e_max = best;
+    return 0;
+}
+
+// Sec. 3.1 + App. A.1: x[rows, cols] row-major -> q[rows, cols] (and, when qT
+// is given, the same values transposed to [cols, rows]).
+int fxp_ref_map(const float* x, int64_t rows, int64_t cols, int32_t e_max, int8_t* q, int8_t* qT,
+                uint64_t seed, uint64_t stream_id, int rounding, int bits) {
+    if (rows < 0 || cols < 0 || bad_bits(bits) || rounding < 0 || rounding > 1) return -2;
+    if (rows * cols > 0 && (!x || (!q && !qT))) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int64_t c = 0; c < cols; ++c) {
+            const uint64_t i = static_cast<uint64_t>(r) * static_cast<uint64_t>(cols) + static_cast<uint64_t>(c);
+            const uint32_t word = random_word(seed, stream_id, i);
+            const int8_t v = static_cast<int8_t>(map_one(x[i], e_max, word, rounding, bits));
+            if (q) q[i] = v;
+            if (qT) qT[c * rows + r] = v;
+        }
+    }
+    return 0;
+}
+
+// Sec. 3.3: C[M,N] = op(A)[M,K] * op(B)[K,N], int8 operands, int32 accumulation.
+// transA = 0: A is stored [M,K] (lda >= K); 1: A is stored [K,M] (lda >= M).
+// transB = 0: B is stored [K,N] (ldb >= N); 1: B is stored [N,K] (ldb >= K).
+int fxp_ref_gemm(int transA, int transB, int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda,
+                 const int8_t* B, int64_t ldb, int32_t* C, int64_t ldc) {
+    if (M < 0 || N < 0 || K < 0 || ldc < N) return -2;
+    if (M * N > 0 && !C) return -1;
+    if (M * K > 0 && !A) return -1;
+    if (N * K > 0 && !B) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i) {
+        for (int64_t j = 0; j < N; ++j) {
+            int32_t acc = 0;
+            for (int64_t k = 0; k < K; ++k) {
+                const int32_t a = transA ? A[k * lda + i] : A[i * lda + k];
+                const int32_t b = transB ? B[j * ldb + k] : B[k * ldb + j];
+                acc += a * b;
+            }
+            C[i * ldc + j] = acc;
+        }
+    }
+    return 0;
+}
+
+// Sec. 3.2 + 3.3: the real number acc * 2^E with E = lsb(eA) + lsb(eB), rounded
+// once (nearest, ties to even) to fp32.  bitsB == 0 means "no second operand"
+// (the inverse map of a mapped tensor itself).
+int fxp_ref_unmap(const int32_t* acc, uint64_t n, int32_t eA, int bitsA, int32_t eB, int bitsB, float* out) {
+    if (n && (!acc || !out)) return -1;
+    if (bad_bits(bitsA) || (bitsB != 0 && bad_bits(bitsB))) return -2;
+    const int32_t E = lsb_exponent(eA, bitsA) + (bitsB ? lsb_exponent(eB, bitsB) : 0);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < static_cast<int64_t>(n); ++i) {
+        out[i] = static_cast<float>(std::ldexp(static_cast<double>(acc[i]), E));
+    }
+    return 0;
+}
+
+int fxp_ref_unmap_i8(const int8_t* q, uint64_t n, int32_t eA, int bitsA, float* out) {
+    if (n && (!q || !out)) return -1;
+    if (bad_bits(bitsA)) return -2;
+    const int32_t E = lsb_exponent(eA, bitsA);
+    for (uint64_t i = 0; i < n; ++i) out[i] = static_cast<float>(std::ldexp(static_cast<double>(q[i]), E));
+    return 0;
+}
+
+// App. A.2, forward: Y = unmap(map(X) * map(W)).  X[M,K], W[K,N], Y[M,N].
+// Xq[M,K], Wq[K,N] and the two scales are returned for the backward pass.
+// Random streams: (step << 8) | tag with tag 0 for X and 1 for W.
+int fxp_ref_linear_fwd(const float* X, const float* W, int64_t M, int64_t K, int64_t N, float* Y, int8_t* Xq,
+                       int8_t* Wq, int32_t* eX, int32_t* eW, uint64_t seed, uint64_t step, int rounding, int bits) {
+    if (!X || !W || !Y || !Xq || !Wq || !eX || !eW) return -1;
+    int rc;
+    if ((rc = fxp_ref_scale(X, static_cast<uint64_t>(M * K), eX))) return rc;
+    if ((rc = fxp_ref_scale(W, static_cast<uint64_t>(K * N), eW))) return rc;
+    if ((rc = fxp_ref_map(X, M, K, *eX, Xq, nullptr, seed, (step << 8) | 0u, rounding, bits))) return rc;
+    if ((rc = fxp_ref_map(W, K, N, *eW, Wq, nullptr, seed, (step << 8) | 1u, rounding, bits))) return rc;
+    int32_t* acc = new int32_t[static_cast<size_t>(M * N) + 1];
+    rc = fxp_ref_gemm(0, 0, M, N, K, Xq, K, Wq, N, acc, N);
+    if (!rc) rc = fxp_ref_unmap(acc, static_cast<uint64_t>(M * N), *eX, bits, *eW, bits, Y);
+    delete[] acc;
+    return rc;
+}
+
+// App. A.2, backward: G = map(dY) once (stream tag 2); dX = unmap(G * Wq^T)
+// [M,K]; dW = unmap(Xq^T * G) [K,N].  dX or dW may be null to skip it.
+int fxp_ref_linear_bwd(const float* dY, const int8_t* Xq, const int8_t* Wq, int32_t eX, int32_t eW, int64_t M,
+                       int64_t K, int64_t N, float* dX, float* dW, int8_t* dYq, int32_t* eG, uint64_t seed,
+                       uint64_t step, int rounding, int bits) {
+    if (!dY || !Xq || !Wq || !dYq || !eG) return -1;
+    int rc;
+    if ((rc = fxp_ref_scale(dY, static_cast<uint64_t>(M * N), eG))) return rc;
+    if ((rc = fxp_ref_map(dY, M, N, *eG, dYq, nullptr, seed, (step << 8) | 2u, rounding, bits))) return rc;
+    if (dX) {
+        int32_t* acc = new int32_t[static_cast<size_t>(M * K) + 1];
+        rc = fxp_ref_gemm(0, 1, M, K, N, dYq, N, Wq, N, acc, K);
+        if (!rc) rc = fxp_ref_unmap(acc, static_cast<uint64_t>(M * K), *eG, bits, eW, bits, dX);
+        delete[] acc;
+        if (rc) return rc;
+    }
+    if (dW) {
+        int32_t* acc = new int32_t[static_cast<size_t>(K * N) + 1];
+        rc = fxp_ref_gemm(1, 0, K, N, M, Xq, K, dYq, N, acc, N);
+        if (!rc) rc = fxp_ref_unmap(acc, static_cast<uint64_t>(K * N), eX, bits, *eG, bits, dW);
+        delete[] acc;
+        if (rc) return rc;
+    }
+    return 0;
+}
+
+}  // extern "C"

@@ -1,0 +1,112 @@
+"""Seeded synthetic inputs for the integer linear-layer step.
+
+Shared by the tests, the benchmark and the smoke check; it holds no arithmetic
+of the method (no scale, mapping, GEMM or inverse mapping) — only random fp32
+tensors with the shapes and value distributions of the five benchmark
+workloads, which stand in for the ResNet / ViT layers the paper trains
+(Sec. 5, App. A.5): the paper's datasets and weights are not used.
+
+All draws come from numpy.random.Generator(PCG64(seed)) in a fixed order
+(X, then W, then dY), so a (workload, seed) pair names one set of tensors.
+"""
+from dataclasses import dataclass
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class Layer:
+    name: str
+    M: int  # rows of X and dY (batch x tokens, or batch x output pixels)
+    K: int  # input features (contraction length of the forward GEMM)
+    N: int  # output features
+
+
+# ViT-B/16 at batch 64 x 197 tokens
+_VIT_M = 64 * 197
+
+WORKLOADS = {
+    # single small linear layer
+    "c1": [Layer("linear256", 256, 256, 256)],
+    # ResNet-18 stage-2 3x3 conv as an im2col GEMM: batch 32, 128->128 channels, 28x28
+    "c2": [Layer("resnet18_conv3x3_128", 32 * 28 * 28, 128 * 9, 128)],
+    # ViT-B/16 MLP fc1
+    "c3": [Layer("vit_fc1", _VIT_M, 768, 3072)],
+    # ViT-B/16 encoder block: every linear layer
+    "c4": [Layer("vit_qkv", _VIT_M, 768, 2304), Layer("vit_proj", _VIT_M, 768, 768),
+           Layer("vit_fc1", _VIT_M, 768, 3072), Layer("vit_fc2", _VIT_M, 3072, 768)],
+    # large square stress GEMM; sigma is a parameter
+    "c5": [Layer("square8192", 8192, 8192, 8192)],
+}
+C5_SIGMAS = (1e-6, 1e-2, 1.0, 1e3)
+DEFAULT_SEED = {"c1": 0, "c2": 1, "c3": 2, "c4": 3, "c5": 4}
+
+
+def _normal(rng, shape, sigma):
+    return (rng.standard_normal(shape, dtype=np.float32) * np.float32(sigma)).astype(np.float32)
+
+
+def _laplace(rng, shape, b):
+    return rng.laplace(0.0, b, size=shape).astype(np.float32)
+
+
+def im2col_3x3(act):
+    """[B,C,H,W] -> [B*H*W, C*9] patches of a 3x3, stride 1, zero-padded-by-1
+    convolution; column order (c, kh, kw).  Input construction only."""
+    B, C, H, W = act.shape
+    p = np.zeros((B, C, H + 2, W + 2), dtype=act.dtype)
+    p[:, :, 1:-1, 1:-1] = act
+    s = p.strides
+    win = np.lib.stride_tricks.as_strided(p, shape=(B, H, W, C, 3, 3), strides=(s[0], s[2], s[3], s[1], s[2], s[3]),
+                                          writeable=False)
+    return np.ascontiguousarray(win).reshape(B * H * W, C * 9)
+
+
+def layer_tensors(workload, layer_index=0, seed=None, sigma=1.0, scale_down=1):
+    """fp32 (X[M,K], W[K,N], dY[M,N]) of one layer of a workload.
+
+    scale_down > 1 divides M (and, for c5, K and N) for reduced-size parity
+    cases; distributions are unchanged.
+    """
+    layer = WORKLOADS[workload][layer_index]
+    if seed is None:
+        seed = DEFAULT_SEED[workload]
+    rng = np.random.Generator(np.random.PCG64([seed, layer_index]))
+    M, K, N = layer.M, layer.K, layer.N
+    if workload == "c1":
+        X = _normal(rng, (M, K), 1.0)
+        W = _normal(rng, (K, N), 1.0)
+        dY = _laplace(rng, (M, N), 1e-4)
+    elif workload == "c2":
+        batch = max(1, 32 // scale_down)
+        act = np.maximum(_normal(rng, (batch, 128, 28, 28), 1.0), 0.0)  # ReLU'd N(0,1)
+        X = im2col_3x3(act)
+        M = X.shape[0]
+        W = _normal(rng, (K, N), np.sqrt(2.0 / K))                      # N(0, 2/fan_in) as a variance
+        dY = _normal(rng, (M, N), 1e-3)
+    elif workload in ("c3", "c4"):
+        M = max(1, M // scale_down)
+        X = _normal(rng, (M, K), 1.0)
+        W = _normal(rng, (K, N), 0.02)
+        dY = _laplace(rng, (M, N), 1e-5)
+        outlier = rng.random((M, N), dtype=np.float32) < np.float32(1e-3)  # 0.1 % of entries x1000
+        dY = np.where(outlier, dY * np.float32(1000.0), dY).astype(np.float32)
+    elif workload == "c5":
+        M, K, N = (max(1, v // scale_down) for v in (M, K, N))
+        X = _normal(rng, (M, K), sigma)
+        W = _normal(rng, (K, N), sigma)
+        dY = _normal(rng, (M, N), sigma)
+    else:
+        raise KeyError(workload)
+    return X, W, dY
+
+
+def ops_per_layer(layer):
+    """Integer operations (multiply and add counted separately) of the three
+    GEMMs of one forward + backward layer step."""
+    return 3 * 2 * layer.M * layer.K * layer.N
+
+
+def mapped_elements(layer):
+    """fp32 elements that go through scale + map in one layer step (X, W, dY)."""
+    return layer.M * layer.K + layer.K * layer.N + layer.M * layer.N
