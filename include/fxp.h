@@ -1,0 +1,159 @@
+/*
+ * fxp.h — C ABI of libfxp: the integer (dynamic fixed-point) linear-layer step
+ * of "Is Integer Arithmetic Enough for Deep Learning Training?" (arXiv
+ * 2207.08822) as hand-written HIP kernels for gfx950 (MI355X).
+ *
+ * Conventions that hold for every call
+ *  - Every data pointer is a DEVICE pointer unless the argument says "host".
+ *    The caller owns every buffer; the library never allocates, frees or keeps
+ *    a pointer after the call's work has run.
+ *  - All matrices are dense row-major.  X[M,K], W[K,N], Y[M,N], dY[M,N],
+ *    dX[M,K], dW[K,N] (the paper's Y = XW, App. A.2).
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls only enqueue work; they never synchronise and never read device
+ *    memory from the host, so per-tensor scales stay on the device.
+ *  - `ws` is device scratch of at least fxp_workspace_bytes(...) bytes, 256-byte
+ *    aligned, private to the call until its work has finished on `stream`.
+ *  - Return value: FXP_OK (0) or a negative fxp_status; nothing is enqueued when
+ *    an argument error is returned.  Launch failures reported by the runtime map
+ *    to FXP_ERR_LAUNCH.  No exception crosses this boundary.
+ *  - A mapped tensor is int8 values q plus ONE int32 scale e_max (the biased
+ *    fp32 exponent field of its largest magnitude, Sec. 3.1); q stands for the
+ *    real number q * 2^(e_max - 127 - (bits - 2)), i.e. q * 2^(e_max - 133) for
+ *    the paper's int8 (bits = 8: sign + 7 magnitude bits).
+ *  - Inputs must be finite.  Non-finite input is not an error (it cannot be seen
+ *    without a synchronisation): the scale then reads 255, +-Inf maps to the
+ *    largest magnitude and NaN to 0.
+ */
+#ifndef FXP_H_
+#define FXP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum fxp_status {
+    FXP_OK = 0,
+    FXP_ERR_NULL = -1,      /* a required pointer is NULL */
+    FXP_ERR_DIMS = -2,      /* negative size, leading dimension too small, or size beyond the supported range */
+    FXP_ERR_ALIGN = -3,     /* a pointer misses the alignment stated for it */
+    FXP_ERR_WORKSPACE = -4, /* ws is NULL or smaller than fxp_workspace_bytes says */
+    FXP_ERR_ROUNDING = -5,  /* unknown rounding mode */
+    FXP_ERR_BITS = -6,      /* bits outside [2, 8] */
+    FXP_ERR_LAUNCH = -7,    /* the HIP runtime refused a launch */
+    FXP_ERR_OVERFLOW = -8   /* contraction so long that int32 accumulation could overflow (> 133144) */
+} fxp_status;
+
+/* Rounding of the 24-bit shifted mantissa to bits-1 magnitude bits. */
+enum {
+    FXP_ROUND_STOCHASTIC = 0, /* App. A.1: up with probability (dropped bits) / 2^(number dropped) */
+    FXP_ROUND_NEAREST = 1     /* half up on the magnitude; for comparison runs only */
+};
+
+/* Operation selector of fxp_workspace_bytes. */
+enum { FXP_OP_SCALE = 0, FXP_OP_GEMM = 1, FXP_OP_LINEAR_FWD = 2, FXP_OP_LINEAR_BWD = 3 };
+
+/* Random-stream tags of the layer calls: stream_id = (step << 8) | tag. */
+enum { FXP_TAG_X = 0, FXP_TAG_W = 1, FXP_TAG_DY = 2 };
+
+/* Host string for a status code (static storage). */
+const char* fxp_strerror(int status);
+
+/* Library version, major * 100 + minor. */
+int fxp_version(void);
+
+/* Scratch bytes an operation needs.  FXP_OP_SCALE: M = number of elements.
+ * FXP_OP_GEMM: worst case over the operand forms of fxp_gemm / fxp_gemm_unmap.
+ * FXP_OP_LINEAR_FWD / _BWD: layer shapes M, N, K as above.  Returns 0 on bad
+ * arguments. */
+size_t fxp_workspace_bytes(int op, int64_t M, int64_t N, int64_t K);
+
+/* Scale of a tensor (Sec. 3.1: e_max = max(e_1 .. e_n)).
+ * x: n fp32 values, 4-byte aligned, any n >= 0.  e_max: one int32, receives the
+ * largest biased exponent field, counting zeros and sub-normals as 1, so the
+ * result lies in [1, 255] (n = 0 gives 1). */
+int fxp_scale(const float* x, size_t n, int32_t* e_max, void* ws, size_t ws_bytes, void* stream);
+
+/* Linear fixed-point mapping (Sec. 3.1; stochastic rounding of App. A.1, Fig. 4).
+ * x: [rows, cols] fp32.  e_max: the tensor's scale as fxp_scale wrote it (a
+ * larger value is allowed, e.g. a scale shared between shards; elements whose
+ * exponent exceeds it saturate).  q: [rows, cols] int8 or NULL.  qT: [cols,
+ * rows] int8 or NULL, the same values transposed (one rounding decision per
+ * element, shared by both copies).  At least one of q, qT is required.
+ * Per element: 24-bit mantissa (hidden bit restored) shifted right by
+ * e_max - e, cut after bits-1 magnitude bits, rounded up iff r < dropped bits,
+ * saturated to 2^(bits-1) - 1, sign attached.  r is the top (25 - bits) bits
+ * of word (i mod 4) of Philox-4x32-10 with key = seed and counter =
+ * (i / 4, stream_id), i = row * cols + col: the result does not depend on the
+ * launch geometry or on which copies are requested.
+ * Fast path: x, q, qT 16-byte aligned and cols a multiple of 4; anything else
+ * takes a slower element-wise kernel with identical results. */
+int fxp_map(const float* x, int64_t rows, int64_t cols, const int32_t* e_max, int8_t* q, int8_t* qT, uint64_t seed,
+            uint64_t stream_id, int rounding, int bits, void* stream);
+
+/* fxp_scale followed by fxp_map with the final reduction folded into the map
+ * kernel: writes *e_max and q / qT exactly as the two calls would. */
+int fxp_scale_map(const float* x, int64_t rows, int64_t cols, int32_t* e_max, int8_t* q, int8_t* qT, uint64_t seed,
+                  uint64_t stream_id, int rounding, int bits, void* ws, size_t ws_bytes, void* stream);
+
+/* Integer GEMM (Sec. 3.3, Fig. 2: int8 x int8 products, int32 accumulation).
+ * C[M,N] = op(A)[M,K] * op(B)[K,N], C overwritten.
+ * transA = 0: A stored [M,K], lda >= K.  transA = 1: A stored [K,M], lda >= M.
+ * transB = 0: B stored [K,N], ldb >= N.  transB = 1: B stored [N,K], ldb >= K.
+ * Native form is (transA, transB) = (0, 1), both operands contiguous along the
+ * contraction; other forms first transpose the operand into ws.  K <= 133144.
+ * Fast loads need A, B 16-byte aligned and lda, ldb, K multiples of 16; other
+ * shapes take a slower loader with identical results.  C 4-byte aligned. */
+int fxp_gemm(int transA, int transB, int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B,
+             int64_t ldb, int32_t* C, int64_t ldc, void* ws, size_t ws_bytes, void* stream);
+
+/* Non-linear inverse mapping (Sec. 3.2, Fig. 1b) of an integer tensor with the
+ * shared exponent of Sec. 3.3 (sum of the operand exponents):
+ * out = fp32 nearest (ties to even, gradual underflow, overflow to Inf) to
+ * acc * 2^E, E = (eA - 127 - (bitsA-2)) + (eB - 127 - (bitsB-2)); eB = NULL
+ * drops the second term.  acc and out may be the same buffer. */
+int fxp_unmap(const int32_t* acc, size_t n, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB, float* out,
+              void* stream);
+
+/* Inverse mapping of a mapped int8 tensor itself: out = q * 2^(eA - 127 - (bitsA-2)). */
+int fxp_unmap_i8(const int8_t* q, size_t n, const int32_t* eA, int bitsA, float* out, void* stream);
+
+/* fxp_gemm with the inverse mapping fused into its epilogue: C is fp32 and
+ * receives what fxp_unmap would make of the int32 result. */
+int fxp_gemm_unmap(int transA, int transB, int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda,
+                   const int8_t* B, int64_t ldb, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB, float* C,
+                   int64_t ldc, void* ws, size_t ws_bytes, void* stream);
+
+/* Mapped operands a forward call leaves for the backward call (host struct of
+ * device pointers, all caller-allocated, 16-byte aligned). */
+typedef struct fxp_saved {
+    int8_t* Xq;   /* [M,K] */
+    int8_t* XqT;  /* [K,M] */
+    int8_t* Wq;   /* [K,N] */
+    int8_t* WqT;  /* [N,K] */
+    int32_t* eX;  /* 1 */
+    int32_t* eW;  /* 1 */
+} fxp_saved;
+
+/* Forward of one integer linear layer (App. A.2: Y_hat = X_hat W_hat):
+ * scale + map X (stream tag FXP_TAG_X), scale + map W (FXP_TAG_W), int8 GEMM,
+ * inverse mapping -> Y[M,N] fp32.  Fills every member of *saved. */
+int fxp_linear_fwd(const float* X, const float* W, int64_t M, int64_t K, int64_t N, float* Y, const fxp_saved* saved,
+                   uint64_t seed, uint64_t step, int rounding, int bits, void* ws, size_t ws_bytes, void* stream);
+
+/* Backward of the same layer (App. A.2: dL/dW = X_hat^T G_hat; chain rule for
+ * dL/dX = G_hat W_hat^T): scale + map dY ONCE (FXP_TAG_DY; both GEMMs use the
+ * same rounded gradient), then dX[M,K] and dW[K,N] as fp32.  dX or dW may be
+ * NULL to skip it.  dYq [M,N], dYqT [N,M] and e_dY (1 int32) are caller-
+ * allocated outputs/scratch.  Uses saved->XqT, saved->Wq, saved->eX, saved->eW. */
+int fxp_linear_bwd(const float* dY, const fxp_saved* saved, int64_t M, int64_t K, int64_t N, float* dX, float* dW,
+                   int8_t* dYq, int8_t* dYqT, int32_t* e_dY, uint64_t seed, uint64_t step, int rounding, int bits,
+                   void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FXP_H_ */

@@ -1,0 +1,356 @@
+// Integer GEMM on the matrix cores (paper Sec. 3.3, Fig. 2: int8 x int8 products,
+// int32 accumulation) with the non-linear inverse mapping of Sec. 3.2 fused into the
+// epilogue.
+//
+// One kernel form: C[M,N] = A[M,K] * B[N,K]^T with BOTH operands contiguous along the
+// contraction (the mapping kernel emits every tensor in both orientations, so the three
+// GEMMs of a layer step all take this form).  v_mfma_i32_32x32x32_i8: a lane holds 16
+// consecutive contraction bytes of one row (A) or one column (B); integer addition is
+// order-free, so only "same bytes on both sides" matters for the contraction index.
+//
+//   * block tile BM x BN x BK through LDS, double-buffered, global loads for step k+1
+//     issued before the MFMAs of step k (register staging), one barrier per step;
+//   * LDS rows are BK bytes; 16-byte pieces are XOR-swizzled by the row so that the
+//     64-lane ds_read_b128 of a fragment (32 rows x 2 pieces) spreads over all banks;
+//   * accumulator lanes run along N: each store instruction writes 128-byte runs;
+//   * workgroups are renumbered so that each XCD (own L2) works on a compact patch of
+//     tiles instead of every 8th tile;
+//   * long-contraction / small-output shapes split K across grid.y and add int32
+//     partial sums with atomics (exact: integer addition is associative).
+// Roofline: MFMA-bound when 2MNK / (MK + NK + 4MN bytes) is above ~630 ops/B, else HBM.
+#include "fxp_internal.h"
+
+namespace fxp {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+enum { kStoreI32 = 0, kStoreF32 = 1, kAtomicI32 = 2 };
+
+constexpr int kNumXcd = 8;
+
+// Workgroup b runs on XCD b % 8.  Give XCD x the contiguous range of tile numbers
+// [start(x), start(x+1)), then walk tiles in column-major groups of `group_m` tile rows
+// so that concurrently resident tiles share A and B panels in that XCD's L2.
+__device__ inline void tile_of_block(int b, int tiles_m, int tiles_n, int group_m, int* tm, int* tn) {
+    const int total = tiles_m * tiles_n;
+    const int q = total / kNumXcd, r = total % kNumXcd;
+    const int xcd = b % kNumXcd, local = b / kNumXcd;
+    const int t = (xcd < r) ? xcd * (q + 1) + local : r * (q + 1) + (xcd - r) * q + local;
+    const int per_group = group_m * tiles_n;
+    const int g = t / per_group, in_g = t % per_group;
+    const int rows_here = min(group_m, tiles_m - g * group_m);
+    *tm = g * group_m + in_g % rows_here;
+    *tn = in_g / rows_here;
+}
+
+template <int BK>
+__device__ inline int swizzle_of_row(int row) {
+    constexpr int CPR = BK / 16;            // 16-byte pieces per LDS row
+    return (row / (16 / CPR)) % CPR;        // period 16 rows: 16 rows x 16 B = all 64 banks once
+}
+
+template <int BM, int BN, int BK, int WM, int WN, bool VEC, int MODE>
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm_nt(
+    const int8_t* __restrict__ A, int64_t lda, const int8_t* __restrict__ B, int64_t ldb, void* __restrict__ Cv,
+    int64_t ldc, int M, int N, int K, int k_per_split, const int32_t* __restrict__ eA, int bitsA,
+    const int32_t* __restrict__ eB, int bitsB, int tiles_m, int tiles_n, int group_m) {
+    constexpr int NT = (BM / WM) * (BN / WN) * 64;
+    constexpr int CPR = BK / 16;
+    constexpr int NA = BM * CPR / NT, NB = BN * CPR / NT;   // 16-byte pieces per thread per step
+    constexpr int FM = WM / 32, FN = WN / 32;               // 32x32 fragments per wave
+    static_assert(BM * CPR % NT == 0 && BN * CPR % NT == 0, "tile does not divide over the threads");
+
+    __shared__ __attribute__((aligned(16))) int8_t lds[2][(BM + BN) * BK];
+
+    int tm, tn;
+    tile_of_block(blockIdx.x, tiles_m, tiles_n, group_m, &tm, &tn);
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int kb = blockIdx.y * k_per_split;
+    const int ke = min(K, kb + k_per_split);
+    const int nk = (ke - kb + BK - 1) / BK;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm0 = (wave / (BN / WN)) * WM, wn0 = (wave % (BN / WN)) * WN;
+
+    // ---- global -> register staging ------------------------------------------------
+    const int8_t* pa[NA];
+    const int8_t* pb[NB];
+    int lds_a[NA], lds_b[NB], kc_a[NA], kc_b[NB];
+#pragma unroll
+    for (int j = 0; j < NA; ++j) {
+        const int id = tid + j * NT, row = id / CPR, c = id % CPR;
+        pa[j] = A + static_cast<int64_t>(min(m0 + row, M - 1)) * lda + c * 16;
+        lds_a[j] = row * BK + ((c ^ swizzle_of_row<BK>(row)) * 16);
+        kc_a[j] = c * 16;
+    }
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        const int id = tid + j * NT, row = id / CPR, c = id % CPR;
+        pb[j] = B + static_cast<int64_t>(min(n0 + row, N - 1)) * ldb + c * 16;
+        lds_b[j] = BM * BK + row * BK + ((c ^ swizzle_of_row<BK>(row)) * 16);
+        kc_b[j] = c * 16;
+    }
+    uint4 ra[NA], rb[NB];
+
+    auto load_piece = [&](const int8_t* p, int k_first) -> uint4 {
+        // k_first: contraction index of the piece's first byte; bytes at or beyond ke read as 0
+        if (VEC) {
+            if (k_first < ke) return *reinterpret_cast<const uint4*>(p);
+            return make_uint4(0, 0, 0, 0);
+        }
+        uint32_t w[4] = {0, 0, 0, 0};
+        for (int b = 0; b < 16; ++b)
+            if (k_first + b < ke) w[b >> 2] |= static_cast<uint32_t>(static_cast<uint8_t>(p[b])) << (8 * (b & 3));
+        return make_uint4(w[0], w[1], w[2], w[3]);
+    };
+    auto load_step = [&](int kk) {
+#pragma unroll
+        for (int j = 0; j < NA; ++j) ra[j] = load_piece(pa[j] + kk, kk + kc_a[j]);
+#pragma unroll
+        for (int j = 0; j < NB; ++j) rb[j] = load_piece(pb[j] + kk, kk + kc_b[j]);
+    };
+    auto store_step = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < NA; ++j) *reinterpret_cast<uint4*>(&lds[buf][lds_a[j]]) = ra[j];
+#pragma unroll
+        for (int j = 0; j < NB; ++j) *reinterpret_cast<uint4*>(&lds[buf][lds_b[j]]) = rb[j];
+    };
+
+    // ---- fragment addressing ---------------------------------------------------------
+    // lane l reads row (l % 32) of a fragment, contraction bytes 16 * (l / 32) .. +15 of a 32-byte step
+    const int frow = lane & 31, fhalf = lane >> 5;
+    const int fswz = swizzle_of_row<BK>(frow);     // fragment bases are multiples of 32 rows: same swizzle
+    const int a_base = (wm0 + frow) * BK, b_base = BM * BK + (wn0 + frow) * BK;
+
+    v16i acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+    if (nk > 0) {
+        load_step(kb);
+        store_step(0);
+    }
+    __syncthreads();
+    for (int it = 0; it < nk; ++it) {
+        const int buf = it & 1;
+        if (it + 1 < nk) load_step(kb + (it + 1) * BK);
+#pragma unroll
+        for (int ks = 0; ks < BK / 32; ++ks) {
+            const int piece = ((2 * ks + fhalf) ^ fswz) * 16;
+            v4i fa[FM], fb[FN];
+#pragma unroll
+            for (int i = 0; i < FM; ++i) fa[i] = *reinterpret_cast<const v4i*>(&lds[buf][a_base + i * 32 * BK + piece]);
+#pragma unroll
+            for (int j = 0; j < FN; ++j) fb[j] = *reinterpret_cast<const v4i*>(&lds[buf][b_base + j * 32 * BK + piece]);
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+        if (it + 1 < nk) store_step(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue --------------------------------------------------------------------
+    // accumulator register r of lane l is row 8 * (r / 4) + 4 * (l / 32) + r % 4, column l % 32
+    int E = 0;
+    if (MODE == kStoreF32) E = lsb_exponent(eA[0], bitsA) + (eB ? lsb_exponent(eB[0], bitsB) : 0);
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = m0 + wm0 + 32 * i + 8 * (r >> 2) + 4 * fhalf + (r & 3);
+            if (row >= M) continue;
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                const int col = n0 + wn0 + 32 * j + frow;
+                if (col >= N) continue;
+                const int64_t off = static_cast<int64_t>(row) * ldc + col;
+                if (MODE == kStoreF32)
+                    static_cast<float*>(Cv)[off] = unmap_value(acc[i][j][r], E);
+                else if (MODE == kStoreI32)
+                    static_cast<int32_t*>(Cv)[off] = acc[i][j][r];
+                else
+                    atomicAdd(static_cast<int32_t*>(Cv) + off, acc[i][j][r]);
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void k_zero_rows(int32_t* __restrict__ C, int64_t ldc, int M, int N) {
+    const int64_t total = static_cast<int64_t>(M) * N;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; i < total; i += static_cast<int64_t>(gridDim.x) * 256)
+        C[(i / N) * ldc + (i % N)] = 0;
+}
+
+__global__ __launch_bounds__(256) void k_unmap_rows(int32_t* __restrict__ C, int64_t ldc, int M, int N,
+                                                    const int32_t* __restrict__ eA, int bitsA,
+                                                    const int32_t* __restrict__ eB, int bitsB) {
+    const int E = lsb_exponent(eA[0], bitsA) + (eB ? lsb_exponent(eB[0], bitsB) : 0);
+    const int64_t total = static_cast<int64_t>(M) * N;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; i < total; i += static_cast<int64_t>(gridDim.x) * 256) {
+        int32_t* p = C + (i / N) * ldc + (i % N);
+        *reinterpret_cast<float*>(p) = unmap_value(*p, E);
+    }
+}
+
+// int8 [rows, cols] (leading dimension ld) -> [cols, rows] contiguous, 64 x 64 tiles through LDS
+__global__ __launch_bounds__(256) void k_transpose_i8(const int8_t* __restrict__ src, int64_t rows, int64_t cols,
+                                                      int64_t ld, int8_t* __restrict__ dst, int tiles_c) {
+    __shared__ int8_t t[64][65];
+    const int64_t r0 = static_cast<int64_t>(blockIdx.x / tiles_c) * 64, c0 = static_cast<int64_t>(blockIdx.x % tiles_c) * 64;
+    for (int id = threadIdx.x; id < 64 * 64; id += 256) {
+        const int r = id >> 6, c = id & 63;
+        if (r0 + r < rows && c0 + c < cols) t[r][c] = src[(r0 + r) * ld + c0 + c];
+    }
+    __syncthreads();
+    for (int id = threadIdx.x; id < 64 * 64; id += 256) {
+        const int c = id >> 6, r = id & 63;
+        if (r0 + r < rows && c0 + c < cols) dst[(c0 + c) * rows + r0 + r] = t[r][c];
+    }
+}
+
+int transpose_i8_launch(const int8_t* src, int64_t rows, int64_t cols, int64_t ld, int8_t* dst, hipStream_t s) {
+    if (rows == 0 || cols == 0) return FXP_OK;
+    const int64_t tr = (rows + 63) / 64, tc = (cols + 63) / 64;
+    if (tr * tc >= (int64_t{1} << 31)) return FXP_ERR_DIMS;
+    hipLaunchKernelGGL(k_transpose_i8, dim3(static_cast<unsigned>(tr * tc)), dim3(256), 0, s, src, rows, cols, ld, dst,
+                       static_cast<int>(tc));
+    return launch_status();
+}
+
+template <int BM, int BN, int BK, int WM, int WN>
+static int launch_cfg(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
+                      void* C, int64_t ldc, int mode, bool vec, int splits, const int32_t* eA, int bitsA,
+                      const int32_t* eB, int bitsB, hipStream_t s) {
+    constexpr int NT = (BM / WM) * (BN / WN) * 64;
+    const int tiles_m = static_cast<int>((M + BM - 1) / BM), tiles_n = static_cast<int>((N + BN - 1) / BN);
+    int k_per_split = static_cast<int>((K + splits - 1) / splits);
+    k_per_split = (k_per_split + BK - 1) / BK * BK;
+    if (k_per_split == 0) k_per_split = BK;
+    const int ny = K > 0 ? static_cast<int>((K + k_per_split - 1) / k_per_split) : 1;
+    const dim3 grid(static_cast<unsigned>(tiles_m) * tiles_n, ny), block(NT);
+    const int group_m = 8;
+#define FXP_GEMM_LAUNCH(VEC, MODE)                                                                                 \
+    hipLaunchKernelGGL((k_gemm_nt<BM, BN, BK, WM, WN, VEC, MODE>), grid, block, 0, s, A, lda, B, ldb, C, ldc,       \
+                       static_cast<int>(M), static_cast<int>(N), static_cast<int>(K), k_per_split, eA, bitsA, eB,   \
+                       bitsB, tiles_m, tiles_n, group_m)
+    if (vec) {
+        if (mode == kStoreI32) FXP_GEMM_LAUNCH(true, kStoreI32);
+        else if (mode == kStoreF32) FXP_GEMM_LAUNCH(true, kStoreF32);
+        else FXP_GEMM_LAUNCH(true, kAtomicI32);
+    } else {
+        if (mode == kStoreI32) FXP_GEMM_LAUNCH(false, kStoreI32);
+        else if (mode == kStoreF32) FXP_GEMM_LAUNCH(false, kStoreF32);
+        else FXP_GEMM_LAUNCH(false, kAtomicI32);
+    }
+#undef FXP_GEMM_LAUNCH
+    return launch_status();
+}
+
+// C = A[M,K] * B[N,K]^T.  fp32_out: C receives the inverse-mapped fp32 values (eA, eB on
+// the device), else the int32 sums.  C is overwritten in both cases.
+int gemm_nt_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
+                   void* C, int64_t ldc, bool fp32_out, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB,
+                   hipStream_t s) {
+    if (M == 0 || N == 0) return FXP_OK;
+    const bool vec = aligned(A, 16) && aligned(B, 16) && lda % 16 == 0 && ldb % 16 == 0 && K % 16 == 0;
+    const int num_cu = 256;
+    const int64_t tiles_big = ((M + 255) / 256) * ((N + 255) / 256);
+    const int64_t tiles_small = ((M + 127) / 128) * ((N + 127) / 128);
+    const bool big = tiles_big >= num_cu * 3 / 4 && K >= 256;
+    // split the contraction when the output alone cannot fill the chip and K is long
+    int splits = 1;
+    if (!big && tiles_small < num_cu && K >= 2048) {
+        splits = static_cast<int>(std::min<int64_t>((2 * num_cu + tiles_small - 1) / tiles_small, K / 512));
+        if (splits < 1) splits = 1;
+    }
+    int rc;
+    if (splits > 1) {
+        const int zg = static_cast<int>(std::min<int64_t>((M * N + 255) / 256, 2048));
+        hipLaunchKernelGGL(k_zero_rows, dim3(zg), dim3(256), 0, s, static_cast<int32_t*>(C), ldc, static_cast<int>(M),
+                           static_cast<int>(N));
+        if ((rc = launch_status())) return rc;
+        rc = launch_cfg<128, 128, 64, 64, 64>(M, N, K, A, lda, B, ldb, C, ldc, kAtomicI32, vec, splits, eA, bitsA, eB,
+                                              bitsB, s);
+        if (rc || !fp32_out) return rc;
+        hipLaunchKernelGGL(k_unmap_rows, dim3(zg), dim3(256), 0, s, static_cast<int32_t*>(C), ldc, static_cast<int>(M),
+                           static_cast<int>(N), eA, bitsA, eB, bitsB);
+        return launch_status();
+    }
+    const int mode = fp32_out ? kStoreF32 : kStoreI32;
+    if (big) return launch_cfg<256, 256, 64, 128, 128>(M, N, K, A, lda, B, ldb, C, ldc, mode, vec, 1, eA, bitsA, eB, bitsB, s);
+    return launch_cfg<128, 128, 64, 64, 64>(M, N, K, A, lda, B, ldb, C, ldc, mode, vec, 1, eA, bitsA, eB, bitsB, s);
+}
+
+static int check_gemm_args(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, int transA, const void* B,
+                           int64_t ldb, int transB, const void* C, int64_t ldc) {
+    if (M < 0 || N < 0 || K < 0) return FXP_ERR_DIMS;
+    if (M >= (int64_t{1} << 31) || N >= (int64_t{1} << 31)) return FXP_ERR_DIMS;
+    if (K > kMaxContraction) return FXP_ERR_OVERFLOW;
+    if (lda < (transA ? M : K) || ldb < (transB ? K : N) || ldc < N) return FXP_ERR_DIMS;
+    if ((M * N > 0 && !C) || (M * K > 0 && !A) || (N * K > 0 && !B)) return FXP_ERR_NULL;
+    if (!aligned(C, 4)) return FXP_ERR_ALIGN;
+    if (((M + 127) / 128) * ((N + 127) / 128) >= (int64_t{1} << 31)) return FXP_ERR_DIMS;
+    return FXP_OK;
+}
+
+static size_t gemm_ws_bytes(int transA, int transB, int64_t M, int64_t N, int64_t K) {
+    size_t b = 0;
+    if (transA) b += round_up(static_cast<size_t>(M) * static_cast<size_t>(K), 256);
+    if (!transB) b += round_up(static_cast<size_t>(N) * static_cast<size_t>(K), 256);
+    return b;
+}
+
+size_t gemm_ws_worst(int64_t M, int64_t N, int64_t K) { return gemm_ws_bytes(1, 0, M, N, K); }
+
+// Bring any operand form to the native one (transposed copies in ws), then run it.
+static int gemm_any(int transA, int transB, int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda,
+                    const int8_t* B, int64_t ldb, void* C, int64_t ldc, bool fp32_out, const int32_t* eA, int bitsA,
+                    const int32_t* eB, int bitsB, void* ws, size_t ws_bytes, hipStream_t s) {
+    if (M == 0 || N == 0) return FXP_OK;
+    const size_t need = gemm_ws_bytes(transA, transB, M, N, K);
+    if (need > 0 && (!ws || ws_bytes < need)) return FXP_ERR_WORKSPACE;
+    if (need > 0 && !aligned(ws, 256)) return FXP_ERR_ALIGN;
+    int8_t* w = static_cast<int8_t*>(ws);
+    int rc;
+    if (transA && K > 0) {
+        if ((rc = transpose_i8_launch(A, K, M, lda, w, s))) return rc;      // stored [K, M] -> [M, K]
+        A = w;
+        lda = K;
+        w += round_up(static_cast<size_t>(M) * static_cast<size_t>(K), 256);
+    }
+    if (!transB && K > 0) {
+        if ((rc = transpose_i8_launch(B, K, N, ldb, w, s))) return rc;      // stored [K, N] -> [N, K]
+        B = w;
+        ldb = K;
+    }
+    return gemm_nt_launch(M, N, K, A, lda, B, ldb, C, ldc, fp32_out, eA, bitsA, eB, bitsB, s);
+}
+
+}  // namespace fxp
+
+extern "C" int fxp_gemm(int transA, int transB, int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda,
+                        const int8_t* B, int64_t ldb, int32_t* C, int64_t ldc, void* ws, size_t ws_bytes, void* stream) {
+    int rc = fxp::check_gemm_args(M, N, K, A, lda, transA, B, ldb, transB, C, ldc);
+    if (rc) return rc;
+    return fxp::gemm_any(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, false, nullptr, 8, nullptr, 8, ws, ws_bytes,
+                         static_cast<hipStream_t>(stream));
+}
+
+extern "C" int fxp_gemm_unmap(int transA, int transB, int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda,
+                              const int8_t* B, int64_t ldb, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB,
+                              float* C, int64_t ldc, void* ws, size_t ws_bytes, void* stream) {
+    int rc = fxp::check_gemm_args(M, N, K, A, lda, transA, B, ldb, transB, C, ldc);
+    if (rc) return rc;
+    if (!eA) return FXP_ERR_NULL;
+    if (bitsA < 2 || bitsA > 8 || (eB && (bitsB < 2 || bitsB > 8))) return FXP_ERR_BITS;
+    return fxp::gemm_any(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, true, eA, bitsA, eB, bitsB, ws, ws_bytes,
+                         static_cast<hipStream_t>(stream));
+}

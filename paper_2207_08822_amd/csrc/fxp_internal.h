@@ -1,0 +1,64 @@
+// Internal declarations shared by the HIP translation units of libfxp.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/fxp.h"
+
+namespace fxp {
+
+constexpr int kMaxPartials = 1024;        // per-block maxima of the scale reduction (uint32 each)
+constexpr int kScaleThreads = 256;
+constexpr size_t kScaleWsBytes = kMaxPartials * sizeof(uint32_t);
+constexpr int64_t kMaxContraction = 133144;   // 127^2 * K < 2^31
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? FXP_OK : FXP_ERR_LAUNCH; }
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Launchers used by the layer composition (all enqueue on `s`, arguments already validated).
+int scale_partials(const float* x, size_t n, uint32_t* partials, int* n_partials, hipStream_t s);
+int scale_finish(const uint32_t* partials, int n_partials, int32_t* e_max, hipStream_t s);
+int map_launch(const float* x, int64_t rows, int64_t cols, const int32_t* e_in, const uint32_t* partials,
+               int n_partials, int32_t* e_out, int8_t* q, int8_t* qT, uint64_t seed, uint64_t stream_id, int rounding,
+               int bits, hipStream_t s);
+int gemm_nt_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
+                   void* C, int64_t ldc, bool fp32_out, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB,
+                   hipStream_t s);
+size_t gemm_ws_worst(int64_t M, int64_t N, int64_t K);
+int transpose_i8_launch(const int8_t* src, int64_t rows, int64_t cols, int64_t ld, int8_t* dst, hipStream_t s);
+
+__device__ inline uint32_t wave_max(uint32_t v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = max(v, static_cast<uint32_t>(__shfl_xor(static_cast<int>(v), off)));
+    return v;
+}
+
+// max over a block of up to 1024 threads; lds holds blockDim.x / 64 words
+__device__ inline uint32_t block_max(uint32_t v, uint32_t* lds) {
+    v = wave_max(v);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
+    if (lane == 0) lds[wave] = v;
+    __syncthreads();
+    uint32_t r = (lane < nw) ? lds[lane] : 0u;
+    r = wave_max(r);
+    __syncthreads();
+    return r;
+}
+
+// exponent of one unit of a mapped tensor
+__host__ __device__ inline int lsb_exponent(int e_max, int bits) { return e_max - 127 - (bits - 2); }
+
+// fp32 nearest (ties to even, gradual underflow, overflow to Inf) to acc * 2^E: the
+// inverse mapping of Sec. 3.2.  v_cvt_f32_i32 rounds the integer once to 24 bits; the
+// power-of-two factor is exact whenever it is a normal float (then the product is
+// normal or overflows, both as IEEE prescribes).  Outside that range one exact double
+// carries the value to a single f64->f32 rounding.
+__device__ inline float unmap_value(int acc, int E) {
+    if (E >= -126 && E <= 127) {
+        return static_cast<float>(acc) * __uint_as_float(static_cast<uint32_t>(E + 127) << 23);
+    }
+    return static_cast<float>(ldexp(static_cast<double>(acc), E));
+}
+
+}  // namespace fxp

@@ -1,0 +1,303 @@
+// Linear fixed-point mapping fp32 -> int8 (paper Sec. 3.1) with the stochastic
+// rounding of App. A.1 (Fig. 4): the 24-bit mantissa, shifted right by
+// e_max - e, is cut after bits-1 magnitude bits and rounded up iff a random
+// number is below the bits cut off.
+//
+// Kernel shape (HBM-bound by intent: 4 B read, 1 B written per copy per element;
+// the Philox rounds make VALU the close second):
+//   * one block = one 128 x 128 tile; each thread owns 4 x 4 element blocks, read
+//     as four 16-byte loads along rows (one Philox call per load);
+//   * q is written as packed dwords straight from registers (128 B per row per
+//     half-wave);
+//   * for the transposed copy the 4 x 4 block is transposed in registers, staged in
+//     LDS as [col][row] bytes and written out in 16-byte pieces along rows of qT,
+//     so both copies carry the same rounding decisions and both stores coalesce;
+//   * the final step of the scale reduction (max over <= 1024 block maxima) can be
+//     folded in, which saves a launch per tensor.
+// The random word of element i is word (i mod 4) of Philox-4x32-10 with key = seed
+// and counter = (i / 4, stream_id): nothing depends on the launch geometry.
+#include "fxp_internal.h"
+
+namespace fxp {
+
+constexpr int kTile = 128;
+constexpr int kMapThreads = 256;
+constexpr int kTStride = 33;  // dwords per staged column: 128 row bytes + 4 pad
+
+struct MapCfg {
+    int e_max;
+    int cut;        // low bits dropped: 24 - (bits - 1)
+    int rshift;     // 32 - cut: the random number is the top `cut` bits of the word
+    uint32_t sat;   // 2^(bits-1) - 1
+    uint32_t half;  // 2^(cut-1), the nearest-rounding increment
+};
+
+__device__ inline uint4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = static_cast<uint64_t>(0xD2511F53u) * c0;
+        const uint64_t p1 = static_cast<uint64_t>(0xCD9E8D57u) * c2;
+        const uint32_t n0 = static_cast<uint32_t>(p1 >> 32) ^ c1 ^ (k0 + 0x9E3779B9u * r);
+        const uint32_t n2 = static_cast<uint32_t>(p0 >> 32) ^ c3 ^ (k1 + 0xBB67AE85u * r);
+        c1 = static_cast<uint32_t>(p1);
+        c3 = static_cast<uint32_t>(p0);
+        c0 = n0;
+        c2 = n2;
+    }
+    return make_uint4(c0, c1, c2, c3);
+}
+
+// Magnitude of one element, every case: non-finite input, scale below the element.
+template <bool STOCH>
+__device__ inline uint32_t magnitude_full(uint32_t b, uint32_t word, const MapCfg& c) {
+    const uint32_t e = (b >> 23) & 0xffu, f = b & 0x7fffffu;
+    if (e == 255u) return f == 0u ? c.sat : 0u;
+    const int d = c.e_max - static_cast<int>(max(e, 1u));
+    if (d < 0) return c.sat;
+    const uint32_t m = f | (e ? 0x800000u : 0u);
+    const uint32_t mp = m >> min(d, 31);
+    const uint32_t add = STOCH ? ((~word) >> c.rshift) : c.half;
+    return min((mp + add) >> c.cut, c.sat);
+}
+
+// Same for the common case, checked by the caller: e_max in [25, 254] and no element
+// above the scale.  A sub-normal input is then shifted out whatever its hidden bit, so
+// it needs no special case.  r < low  <=>  low + (2^cut - 1 - r) carries out of the cut.
+template <bool STOCH>
+__device__ inline uint32_t magnitude_fast(uint32_t b, uint32_t word, const MapCfg& c) {
+    const uint32_t e = (b >> 23) & 0xffu;
+    const uint32_t m = (b & 0x7fffffu) | 0x800000u;
+    const uint32_t mp = m >> min(static_cast<uint32_t>(c.e_max) - e, 31u);
+    const uint32_t add = STOCH ? ((~word) >> c.rshift) : c.half;
+    return min((mp + add) >> c.cut, c.sat);
+}
+
+__device__ inline uint32_t with_sign(uint32_t mag, uint32_t b) {
+    const uint32_t sm = static_cast<uint32_t>(static_cast<int32_t>(b) >> 31);
+    return (mag ^ sm) - sm;
+}
+
+// four consecutive elements -> four int8 packed little-endian
+template <bool STOCH>
+__device__ inline uint32_t map4(const uint4 v, const uint4 w, const MapCfg& c, bool fast) {
+    uint32_t q0, q1, q2, q3;
+    if (fast) {
+        q0 = magnitude_fast<STOCH>(v.x, w.x, c);
+        q1 = magnitude_fast<STOCH>(v.y, w.y, c);
+        q2 = magnitude_fast<STOCH>(v.z, w.z, c);
+        q3 = magnitude_fast<STOCH>(v.w, w.w, c);
+    } else {
+        q0 = magnitude_full<STOCH>(v.x, w.x, c);
+        q1 = magnitude_full<STOCH>(v.y, w.y, c);
+        q2 = magnitude_full<STOCH>(v.z, w.z, c);
+        q3 = magnitude_full<STOCH>(v.w, w.w, c);
+    }
+    q0 = with_sign(q0, v.x) & 0xffu;
+    q1 = with_sign(q1, v.y) & 0xffu;
+    q2 = with_sign(q2, v.z) & 0xffu;
+    q3 = with_sign(q3, v.w);
+    return q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
+}
+
+__device__ inline uint32_t max_exponent4(const uint4 v) {
+    const uint32_t kAbs = 0x7fffffffu;
+    return max(max(v.x & kAbs, v.y & kAbs), max(v.z & kAbs, v.w & kAbs)) >> 23;
+}
+
+__device__ inline MapCfg make_cfg(int e_max, int bits) {
+    MapCfg c;
+    c.e_max = e_max;
+    c.cut = 24 - (bits - 1);
+    c.rshift = 32 - c.cut;
+    c.sat = (1u << (bits - 1)) - 1u;
+    c.half = 1u << (c.cut - 1);
+    return c;
+}
+
+// scale of the tensor: either given, or the max of the per-block maxima (and then
+// block 0 publishes it)
+__device__ inline int resolve_scale(const int32_t* e_in, const uint32_t* partials, int n_partials, int32_t* e_out,
+                                    uint32_t* red) {
+    if (partials == nullptr) return e_in[0];
+    uint32_t m = 0;
+    for (int i = threadIdx.x; i < n_partials; i += blockDim.x) m = max(m, partials[i]);
+    m = block_max(m, red);
+    const int e = max(1, static_cast<int>(m >> 23));
+    if (blockIdx.x == 0 && threadIdx.x == 0) e_out[0] = e;
+    return e;
+}
+
+template <bool STOCH>
+__global__ __launch_bounds__(kMapThreads) void k_map_tile(const uint32_t* __restrict__ x, int64_t rows, int64_t cols,
+                                                          const int32_t* __restrict__ e_in,
+                                                          const uint32_t* __restrict__ partials, int n_partials,
+                                                          int32_t* __restrict__ e_out, int8_t* __restrict__ q,
+                                                          int8_t* __restrict__ qT, uint32_t key0, uint32_t key1,
+                                                          uint32_t sid0, uint32_t sid1, int bits, int tiles_c) {
+    __shared__ uint32_t stage[kTile * kTStride];
+    __shared__ uint32_t red[kMapThreads / 64];
+    const MapCfg cfg = make_cfg(resolve_scale(e_in, partials, n_partials, e_out, red), bits);
+    const bool scale_ok = cfg.e_max >= 25 && cfg.e_max < 255;
+
+    const int tid = threadIdx.x;
+    const int64_t r0 = static_cast<int64_t>(blockIdx.x / tiles_c) * kTile;
+    const int64_t c0 = static_cast<int64_t>(blockIdx.x % tiles_c) * kTile;
+    const int cg = tid & 31;                    // group of 4 columns
+    const int64_t col = c0 + 4 * cg;
+    const bool col_ok = col < cols;             // cols is a multiple of 4: a group is all in or all out
+
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int rg = p * 8 + (tid >> 5);      // group of 4 rows
+        const int64_t row = r0 + 4 * rg;
+        uint4 v[4];
+        bool ok[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            ok[k] = col_ok && (row + k) < rows;
+            v[k] = ok[k] ? *reinterpret_cast<const uint4*>(x + (row + k) * cols + col) : make_uint4(0, 0, 0, 0);
+        }
+        uint32_t emax4 = max(max(max_exponent4(v[0]), max_exponent4(v[1])), max(max_exponent4(v[2]), max_exponent4(v[3])));
+        const bool fast = scale_ok && emax4 <= static_cast<uint32_t>(cfg.e_max);
+        uint32_t o[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint64_t blk = static_cast<uint64_t>((row + k) * cols + col) >> 2;
+            uint4 w = make_uint4(0, 0, 0, 0);
+            if (STOCH) w = philox4x32_10(static_cast<uint32_t>(blk), static_cast<uint32_t>(blk >> 32), sid0, sid1, key0, key1);
+            o[k] = map4<STOCH>(v[k], w, cfg, fast);
+            if (q != nullptr && ok[k]) *reinterpret_cast<uint32_t*>(q + (row + k) * cols + col) = o[k];
+        }
+        if (qT != nullptr) {
+            // 4 x 4 byte transpose: t[c] = column c of the block, rows in ascending byte order
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t t = ((o[0] >> (8 * c)) & 0xffu) | (((o[1] >> (8 * c)) & 0xffu) << 8) |
+                                   (((o[2] >> (8 * c)) & 0xffu) << 16) | (((o[3] >> (8 * c)) & 0xffu) << 24);
+                stage[(4 * cg + c) * kTStride + rg] = t;
+            }
+        }
+    }
+    if (qT == nullptr) return;
+    __syncthreads();
+    if ((rows & 15) == 0) {
+        // 16 rows of one column = 16 contiguous bytes of qT
+#pragma unroll
+        for (int it = 0; it < (kTile * kTile / 16) / kMapThreads; ++it) {
+            const int id = it * kMapThreads + tid;
+            const int c = id >> 3, ch = id & 7;
+            const int64_t orow = c0 + c, ocol = r0 + 16 * ch;
+            if (orow < cols && ocol < rows) {
+                const uint32_t* src = stage + c * kTStride + 4 * ch;
+                *reinterpret_cast<uint4*>(qT + orow * rows + ocol) = make_uint4(src[0], src[1], src[2], src[3]);
+            }
+        }
+    } else {
+        const uint8_t* bytes = reinterpret_cast<const uint8_t*>(stage);
+        for (int id = tid; id < kTile * kTile; id += kMapThreads) {
+            const int c = id >> 7, r = id & 127;
+            const int64_t orow = c0 + c, ocol = r0 + r;
+            if (orow < cols && ocol < rows) qT[orow * rows + ocol] = static_cast<int8_t>(bytes[c * kTStride * 4 + r]);
+        }
+    }
+}
+
+// One element per thread, any shape and alignment.
+template <bool STOCH>
+__global__ __launch_bounds__(kMapThreads) void k_map_generic(const uint32_t* __restrict__ x, int64_t rows, int64_t cols,
+                                                             const int32_t* __restrict__ e_in,
+                                                             const uint32_t* __restrict__ partials, int n_partials,
+                                                             int32_t* __restrict__ e_out, int8_t* __restrict__ q,
+                                                             int8_t* __restrict__ qT, uint32_t key0, uint32_t key1,
+                                                             uint32_t sid0, uint32_t sid1, int bits) {
+    __shared__ uint32_t red[kMapThreads / 64];
+    const MapCfg cfg = make_cfg(resolve_scale(e_in, partials, n_partials, e_out, red), bits);
+    const uint64_t n = static_cast<uint64_t>(rows) * static_cast<uint64_t>(cols);
+    for (uint64_t i = static_cast<uint64_t>(blockIdx.x) * kMapThreads + threadIdx.x; i < n;
+         i += static_cast<uint64_t>(gridDim.x) * kMapThreads) {
+        const uint32_t b = x[i];
+        uint32_t word = 0;
+        if (STOCH) {
+            const uint64_t blk = i >> 2;
+            const uint4 w = philox4x32_10(static_cast<uint32_t>(blk), static_cast<uint32_t>(blk >> 32), sid0, sid1, key0, key1);
+            const uint32_t sel = static_cast<uint32_t>(i & 3u);
+            word = sel == 0 ? w.x : sel == 1 ? w.y : sel == 2 ? w.z : w.w;
+        }
+        const int8_t v = static_cast<int8_t>(with_sign(magnitude_full<STOCH>(b, word, cfg), b));
+        if (q) q[i] = v;
+        if (qT) {
+            const uint64_t r = i / static_cast<uint64_t>(cols), c = i % static_cast<uint64_t>(cols);
+            qT[c * static_cast<uint64_t>(rows) + r] = v;
+        }
+    }
+}
+
+int map_launch(const float* x, int64_t rows, int64_t cols, const int32_t* e_in, const uint32_t* partials,
+               int n_partials, int32_t* e_out, int8_t* q, int8_t* qT, uint64_t seed, uint64_t stream_id, int rounding,
+               int bits, hipStream_t s) {
+    const uint32_t k0 = static_cast<uint32_t>(seed), k1 = static_cast<uint32_t>(seed >> 32);
+    const uint32_t s0 = static_cast<uint32_t>(stream_id), s1 = static_cast<uint32_t>(stream_id >> 32);
+    const uint32_t* xb = reinterpret_cast<const uint32_t*>(x);
+    const bool stoch = rounding == FXP_ROUND_STOCHASTIC;
+    const int64_t tiles_r = (rows + kTile - 1) / kTile, tiles_c = (cols + kTile - 1) / kTile;
+    const bool tile_path = (cols % 4 == 0) && aligned(x, 16) && (!q || aligned(q, 16)) && (!qT || aligned(qT, 16)) &&
+                           tiles_r * tiles_c > 0 && tiles_r * tiles_c < (int64_t{1} << 31) && tiles_c < (int64_t{1} << 30);
+    if (tile_path) {
+        const dim3 grid(static_cast<unsigned>(tiles_r * tiles_c)), block(kMapThreads);
+        if (stoch)
+            hipLaunchKernelGGL(k_map_tile<true>, grid, block, 0, s, xb, rows, cols, e_in, partials, n_partials, e_out, q,
+                               qT, k0, k1, s0, s1, bits, static_cast<int>(tiles_c));
+        else
+            hipLaunchKernelGGL(k_map_tile<false>, grid, block, 0, s, xb, rows, cols, e_in, partials, n_partials, e_out,
+                               q, qT, k0, k1, s0, s1, bits, static_cast<int>(tiles_c));
+    } else {
+        const uint64_t n = static_cast<uint64_t>(rows) * static_cast<uint64_t>(cols);
+        uint64_t want = (n + kMapThreads - 1) / kMapThreads;
+        const dim3 grid(static_cast<unsigned>(want < 1 ? 1 : (want > 16384 ? 16384 : want))), block(kMapThreads);
+        if (stoch)
+            hipLaunchKernelGGL(k_map_generic<true>, grid, block, 0, s, xb, rows, cols, e_in, partials, n_partials, e_out,
+                               q, qT, k0, k1, s0, s1, bits);
+        else
+            hipLaunchKernelGGL(k_map_generic<false>, grid, block, 0, s, xb, rows, cols, e_in, partials, n_partials,
+                               e_out, q, qT, k0, k1, s0, s1, bits);
+    }
+    return launch_status();
+}
+
+static int check_map_args(const float* x, int64_t rows, int64_t cols, const void* e, int8_t* q, int8_t* qT, int rounding,
+                          int bits) {
+    if (rows < 0 || cols < 0) return FXP_ERR_DIMS;
+    if (rows > 0 && cols > 0 && rows > (int64_t{1} << 62) / cols) return FXP_ERR_DIMS;
+    if (!e || (!q && !qT) || (rows * cols > 0 && !x)) return FXP_ERR_NULL;
+    if (rounding != FXP_ROUND_STOCHASTIC && rounding != FXP_ROUND_NEAREST) return FXP_ERR_ROUNDING;
+    if (bits < 2 || bits > 8) return FXP_ERR_BITS;
+    if (!aligned(x, 4) || !aligned(e, 4)) return FXP_ERR_ALIGN;
+    return FXP_OK;
+}
+
+}  // namespace fxp
+
+extern "C" int fxp_map(const float* x, int64_t rows, int64_t cols, const int32_t* e_max, int8_t* q, int8_t* qT,
+                       uint64_t seed, uint64_t stream_id, int rounding, int bits, void* stream) {
+    int rc = fxp::check_map_args(x, rows, cols, e_max, q, qT, rounding, bits);
+    if (rc) return rc;
+    if (rows * cols == 0) return FXP_OK;
+    return fxp::map_launch(x, rows, cols, e_max, nullptr, 0, nullptr, q, qT, seed, stream_id, rounding, bits,
+                           static_cast<hipStream_t>(stream));
+}
+
+extern "C" int fxp_scale_map(const float* x, int64_t rows, int64_t cols, int32_t* e_max, int8_t* q, int8_t* qT,
+                             uint64_t seed, uint64_t stream_id, int rounding, int bits, void* ws, size_t ws_bytes,
+                             void* stream) {
+    int rc = fxp::check_map_args(x, rows, cols, e_max, q, qT, rounding, bits);
+    if (rc) return rc;
+    if (!ws || ws_bytes < fxp::kScaleWsBytes) return FXP_ERR_WORKSPACE;
+    if (!fxp::aligned(ws, 4)) return FXP_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint32_t* partials = static_cast<uint32_t*>(ws);
+    int np = 0;
+    rc = fxp::scale_partials(x, static_cast<size_t>(rows * cols), partials, &np, s);
+    if (rc) return rc;
+    if (rows * cols == 0) return fxp::scale_finish(partials, np, e_max, s);
+    return fxp::map_launch(x, rows, cols, nullptr, partials, np, e_max, q, qT, seed, stream_id, rounding, bits, s);
+}

@@ -1,0 +1,228 @@
+"""Thin Python binding of libfxp (include/fxp.h): argument marshalling only.
+
+Every function takes torch CUDA tensors, allocates the outputs with torch, hands raw
+device pointers and the current torch stream to the C ABI and raises FxpError on a
+non-zero status.  All arithmetic runs in the HIP kernels; there is no CPU or PyTorch
+fallback: if libfxp.so cannot be loaded, or a tensor is not on the GPU, the call fails.
+"""
+import ctypes
+import os
+
+import torch
+
+from . import build as _build
+
+STOCHASTIC, NEAREST = 0, 1
+OP_SCALE, OP_GEMM, OP_LINEAR_FWD, OP_LINEAR_BWD = 0, 1, 2, 3
+TAG_X, TAG_W, TAG_DY = 0, 1, 2
+
+
+class FxpError(RuntimeError):
+    pass
+
+
+class _Saved(ctypes.Structure):
+    _fields_ = [("Xq", ctypes.c_void_p), ("XqT", ctypes.c_void_p), ("Wq", ctypes.c_void_p), ("WqT", ctypes.c_void_p),
+                ("eX", ctypes.c_void_p), ("eW", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    """Load libfxp.so (building it first only when no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = _build.LIB
+    if not os.path.exists(path):
+        path = _build.build()
+    L = ctypes.CDLL(path)
+    c = ctypes
+    vp, i32, i64, u64, sz, ci = c.c_void_p, c.c_int32, c.c_int64, c.c_uint64, c.c_size_t, c.c_int
+    L.fxp_strerror.restype = c.c_char_p
+    L.fxp_strerror.argtypes = [ci]
+    L.fxp_version.restype = ci
+    L.fxp_workspace_bytes.restype = sz
+    L.fxp_workspace_bytes.argtypes = [ci, i64, i64, i64]
+    L.fxp_scale.argtypes = [vp, sz, vp, vp, sz, vp]
+    L.fxp_map.argtypes = [vp, i64, i64, vp, vp, vp, u64, u64, ci, ci, vp]
+    L.fxp_scale_map.argtypes = [vp, i64, i64, vp, vp, vp, u64, u64, ci, ci, vp, sz, vp]
+    L.fxp_gemm.argtypes = [ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, i64, vp, sz, vp]
+    L.fxp_unmap.argtypes = [vp, sz, vp, ci, vp, ci, vp, vp]
+    L.fxp_unmap_i8.argtypes = [vp, sz, vp, ci, vp, vp]
+    L.fxp_gemm_unmap.argtypes = [ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, ci, vp, ci, vp, i64, vp, sz, vp]
+    L.fxp_linear_fwd.argtypes = [vp, vp, i64, i64, i64, vp, c.POINTER(_Saved), u64, u64, ci, ci, vp, sz, vp]
+    L.fxp_linear_bwd.argtypes = [vp, c.POINTER(_Saved), i64, i64, i64, vp, vp, vp, vp, vp, u64, u64, ci, ci, vp, sz, vp]
+    for name in ("fxp_scale", "fxp_map", "fxp_scale_map", "fxp_gemm", "fxp_unmap", "fxp_unmap_i8", "fxp_gemm_unmap",
+                 "fxp_linear_fwd", "fxp_linear_bwd"):
+        getattr(L, name).restype = ci
+    _lib = L
+    return L
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise FxpError(f"{what}: {lib().fxp_strerror(rc).decode()} ({rc})")
+
+
+def _dev(t, dtype, what):
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise FxpError(f"{what} must be a CUDA tensor: libfxp has no CPU path")
+    if t.dtype != dtype or not t.is_contiguous():
+        raise FxpError(f"{what} must be a contiguous {dtype} tensor")
+    return t
+
+
+def _p(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def workspace_bytes(op, M, N=0, K=0):
+    return int(lib().fxp_workspace_bytes(op, M, N, K))
+
+
+def _ws(op, M, N=0, K=0, device=None):
+    return torch.empty(max(256, workspace_bytes(op, M, N, K)), dtype=torch.uint8, device=device)
+
+
+def scale(x, ws=None):
+    """e_max of a tensor as a 1-element int32 device tensor (no synchronisation)."""
+    x = _dev(x, torch.float32, "x")
+    e = torch.empty(1, dtype=torch.int32, device=x.device)
+    ws = ws if ws is not None else _ws(OP_SCALE, x.numel(), device=x.device)
+    _check(lib().fxp_scale(_p(x), x.numel(), _p(e), _p(ws), ws.numel(), _stream()), "fxp_scale")
+    return e
+
+
+def _map_outputs(x, want_q, want_qT):
+    rows, cols = x.shape
+    q = torch.empty((rows, cols), dtype=torch.int8, device=x.device) if want_q else None
+    qT = torch.empty((cols, rows), dtype=torch.int8, device=x.device) if want_qT else None
+    return q, qT
+
+
+def map(x, e_max, seed=0, stream_id=0, rounding=STOCHASTIC, bits=8, want_q=True, want_qT=False):
+    """(q, qT) int8 tensors of x[rows, cols] under the device scale e_max."""
+    x = _dev(x, torch.float32, "x")
+    e_max = _dev(e_max, torch.int32, "e_max")
+    assert x.dim() == 2
+    q, qT = _map_outputs(x, want_q, want_qT)
+    _check(lib().fxp_map(_p(x), x.shape[0], x.shape[1], _p(e_max), _p(q), _p(qT), seed, stream_id, rounding, bits,
+                         _stream()), "fxp_map")
+    return q, qT
+
+
+def scale_map(x, seed=0, stream_id=0, rounding=STOCHASTIC, bits=8, want_q=True, want_qT=False, ws=None):
+    """(e_max, q, qT): scale and map in one call."""
+    x = _dev(x, torch.float32, "x")
+    assert x.dim() == 2
+    e = torch.empty(1, dtype=torch.int32, device=x.device)
+    q, qT = _map_outputs(x, want_q, want_qT)
+    ws = ws if ws is not None else _ws(OP_SCALE, x.numel(), device=x.device)
+    _check(lib().fxp_scale_map(_p(x), x.shape[0], x.shape[1], _p(e), _p(q), _p(qT), seed, stream_id, rounding, bits,
+                               _p(ws), ws.numel(), _stream()), "fxp_scale_map")
+    return e, q, qT
+
+
+def _gemm_dims(A, B, transA, transB):
+    M, K = (A.shape[1], A.shape[0]) if transA else A.shape
+    Kb, N = (B.shape[1], B.shape[0]) if transB else B.shape
+    if K != Kb:
+        raise FxpError("contraction lengths differ")
+    return M, N, K
+
+
+def gemm(A, B, transA=False, transB=False, ws=None):
+    """int32 C[M,N] = op(A) op(B) for int8 operands."""
+    A, B = _dev(A, torch.int8, "A"), _dev(B, torch.int8, "B")
+    M, N, K = _gemm_dims(A, B, transA, transB)
+    C = torch.empty((M, N), dtype=torch.int32, device=A.device)
+    ws = ws if ws is not None else _ws(OP_GEMM, M, N, K, device=A.device)
+    _check(lib().fxp_gemm(int(transA), int(transB), M, N, K, _p(A), A.shape[1], _p(B), B.shape[1], _p(C), N, _p(ws),
+                          ws.numel(), _stream()), "fxp_gemm")
+    return C
+
+
+def unmap(acc, eA, eB=None, bitsA=8, bitsB=8, out=None):
+    acc = _dev(acc, torch.int32, "acc")
+    out = out if out is not None else torch.empty(acc.shape, dtype=torch.float32, device=acc.device)
+    _check(lib().fxp_unmap(_p(acc), acc.numel(), _p(eA), bitsA, _p(eB), bitsB, _p(out), _stream()), "fxp_unmap")
+    return out
+
+
+def unmap_i8(q, eA, bits=8):
+    q = _dev(q, torch.int8, "q")
+    out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    _check(lib().fxp_unmap_i8(_p(q), q.numel(), _p(eA), bits, _p(out), _stream()), "fxp_unmap_i8")
+    return out
+
+
+def gemm_unmap(A, B, eA, eB, transA=False, transB=False, bitsA=8, bitsB=8, ws=None):
+    """fp32 C = unmap(op(A) op(B)) with the inverse mapping fused into the GEMM."""
+    A, B = _dev(A, torch.int8, "A"), _dev(B, torch.int8, "B")
+    M, N, K = _gemm_dims(A, B, transA, transB)
+    C = torch.empty((M, N), dtype=torch.float32, device=A.device)
+    ws = ws if ws is not None else _ws(OP_GEMM, M, N, K, device=A.device)
+    _check(lib().fxp_gemm_unmap(int(transA), int(transB), M, N, K, _p(A), A.shape[1], _p(B), B.shape[1], _p(eA), bitsA,
+                                _p(eB), bitsB, _p(C), N, _p(ws), ws.numel(), _stream()), "fxp_gemm_unmap")
+    return C
+
+
+class LayerBuffers:
+    """Caller-owned device buffers of one layer shape, allocated once and reused."""
+
+    def __init__(self, M, K, N, device="cuda"):
+        i8 = dict(dtype=torch.int8, device=device)
+        self.M, self.K, self.N = M, K, N
+        self.Xq, self.XqT = torch.empty((M, K), **i8), torch.empty((K, M), **i8)
+        self.Wq, self.WqT = torch.empty((K, N), **i8), torch.empty((N, K), **i8)
+        self.dYq, self.dYqT = torch.empty((M, N), **i8), torch.empty((N, M), **i8)
+        self.e = torch.zeros(3, dtype=torch.int32, device=device)       # eX, eW, e_dY
+        self.Y = torch.empty((M, N), dtype=torch.float32, device=device)
+        self.dX = torch.empty((M, K), dtype=torch.float32, device=device)
+        self.dW = torch.empty((K, N), dtype=torch.float32, device=device)
+        nbytes = max(workspace_bytes(OP_LINEAR_FWD, M, N, K), workspace_bytes(OP_LINEAR_BWD, M, N, K), 256)
+        self.ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        self.saved = _Saved(_p(self.Xq), _p(self.XqT), _p(self.Wq), _p(self.WqT), self.e[0:1].data_ptr(),
+                            self.e[1:2].data_ptr())
+
+    @property
+    def eX(self):
+        return self.e[0:1]
+
+    @property
+    def eW(self):
+        return self.e[1:2]
+
+    @property
+    def e_dY(self):
+        return self.e[2:3]
+
+
+def linear_fwd(X, W, buf, seed=0, step=0, rounding=STOCHASTIC, bits=8):
+    """Y = unmap(map(X) map(W)); fills buf.Xq/XqT/Wq/WqT/eX/eW and returns buf.Y."""
+    X, W = _dev(X, torch.float32, "X"), _dev(W, torch.float32, "W")
+    M, K = X.shape
+    if W.shape[0] != K or (M, K, W.shape[1]) != (buf.M, buf.K, buf.N):
+        raise FxpError("shapes do not match the layer buffers")
+    _check(lib().fxp_linear_fwd(_p(X), _p(W), M, K, buf.N, _p(buf.Y), ctypes.byref(buf.saved), seed, step, rounding,
+                                bits, _p(buf.ws), buf.ws.numel(), _stream()), "fxp_linear_fwd")
+    return buf.Y
+
+
+def linear_bwd(dY, buf, seed=0, step=0, rounding=STOCHASTIC, bits=8, need_dX=True, need_dW=True):
+    """(dX, dW) from the upstream gradient and the operands the forward call saved."""
+    dY = _dev(dY, torch.float32, "dY")
+    if tuple(dY.shape) != (buf.M, buf.N):
+        raise FxpError("shapes do not match the layer buffers")
+    dX = buf.dX if need_dX else None
+    dW = buf.dW if need_dW else None
+    _check(lib().fxp_linear_bwd(_p(dY), ctypes.byref(buf.saved), buf.M, buf.K, buf.N, _p(dX), _p(dW), _p(buf.dYq),
+                                _p(buf.dYqT), buf.e[2:3].data_ptr(), seed, step, rounding, bits, _p(buf.ws),
+                                buf.ws.numel(), _stream()), "fxp_linear_bwd")
+    return dX, dW

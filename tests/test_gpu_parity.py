@@ -1,0 +1,261 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle, element by
+element, on the same seeded inputs.  Bar: bit-exact for scales, int8 and int32;
+0 ulp for the fp32 outputs of the inverse mapping."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2207_08822_amd import synth
+from tests.gpu_util import dev, host, same_bits, say
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def fxp():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU: there is no CPU path in libfxp")
+    from paper_2207_08822_amd import fxp as binding
+    binding.lib()
+    return binding
+
+
+# --------------------------------------------------------------------------- scale
+@pytest.mark.parametrize("n", [0, 1, 3, 4, 5, 255, 1000, 4096 * 4 + 1, (1 << 20) + 3, 5_000_011])
+def test_scale_sizes(fxp, n):
+    say("scale n", n)
+    rng = np.random.default_rng(n)
+    x = (rng.standard_normal(n) * 10.0 ** rng.uniform(-20, 20)).astype(np.float32)
+    assert int(host(fxp.scale(dev(x)))[0]) == oracle.scale(x)
+    if n > 8:
+        for off in (1, 2, 3):       # pointers off the 16-byte grid
+            say("scale misaligned", n, off)
+            assert int(host(fxp.scale(dev(x)[off:]))[0]) == oracle.scale(x[off:])
+
+
+def test_scale_special_values_and_max_position(fxp):
+    say("scale specials")
+    cases = [np.zeros(100, np.float32), np.array([1e-45, -3e-39, 0], np.float32), np.array([np.inf, 1], np.float32),
+             np.array([np.nan, 1], np.float32), np.array([-3.0e38], np.float32), np.array([2.0 ** -126], np.float32)]
+    for x in cases:
+        assert int(host(fxp.scale(dev(x)))[0]) == oracle.scale(x)
+    base = np.random.default_rng(0).standard_normal(3_000_001).astype(np.float32)
+    for pos in (0, 1, 1234567, 3_000_000):
+        x = base.copy()
+        x[pos] = -70000.0
+        assert int(host(fxp.scale(dev(x)))[0]) == oracle.scale(x) == 127 + 16
+
+
+# --------------------------------------------------------------------------- map
+def check_map(fxp, x, e_max=None, seed=3, sid=(7 << 8) | 1, rounding=0, bits=8):
+    e = oracle.scale(x) if e_max is None else e_max
+    want = oracle.map(x, e, seed=seed, stream_id=sid, rounding=rounding, bits=bits)
+    xd, ed = dev(x), dev(np.array([e], np.int32))
+    q, qT = fxp.map(xd, ed, seed, sid, rounding, bits, want_q=True, want_qT=True)
+    assert np.array_equal(host(q), want)
+    assert np.array_equal(host(qT), want.T)
+    q, _ = fxp.map(xd, ed, seed, sid, rounding, bits, want_q=True, want_qT=False)
+    assert np.array_equal(host(q), want)
+    _, qT = fxp.map(xd, ed, seed, sid, rounding, bits, want_q=False, want_qT=True)
+    assert np.array_equal(host(qT), want.T)
+
+
+@pytest.mark.parametrize("shape", [(128, 128), (256, 384), (1, 4), (5, 8), (130, 132), (16, 1000), (333, 260),
+                                   (1000, 16), (48, 4096), (7, 13), (129, 3), (64, 130), (1, 1)])
+def test_map_shapes(fxp, shape):
+    say("map shape", shape)
+    rng = np.random.default_rng(shape[0] * 7919 + shape[1])
+    x = (rng.standard_normal(shape) * np.exp(rng.uniform(-8, 2, shape))).astype(np.float32)
+    check_map(fxp, x)
+
+
+@pytest.mark.parametrize("bits", [8, 7, 6, 5, 4, 2])
+@pytest.mark.parametrize("rounding", [0, 1])
+def test_map_bits_and_rounding(fxp, bits, rounding):
+    say("map bits", bits, "rounding", rounding)
+    x = np.random.default_rng(bits).standard_normal((200, 260)).astype(np.float32)
+    check_map(fxp, x, rounding=rounding, bits=bits)
+
+
+def test_map_edge_values(fxp):
+    rng = np.random.default_rng(11)
+    x = rng.standard_normal((256, 128)).astype(np.float32)
+    x[0, :8] = [np.inf, -np.inf, np.nan, 0.0, -0.0, 1e-42, -1e-40, 3.0e38]
+    x[5, 5] = 1.9999999
+    say("map non-finite, own scale")
+    check_map(fxp, x)
+    say("map non-finite, scale below")
+    check_map(fxp, x, e_max=120)
+    say("map scale above")
+    check_map(fxp, x[1:], e_max=150)
+    say("map tiny scale")
+    check_map(fxp, (x[1:] * np.float32(1e-38)).astype(np.float32))
+    check_map(fxp, (x[1:] * np.float32(1e-38)).astype(np.float32), e_max=24)
+    check_map(fxp, (x[1:] * np.float32(1e-38)).astype(np.float32), e_max=25)
+    say("map zeros")
+    check_map(fxp, np.zeros((128, 128), np.float32))
+    say("map huge seed")
+    check_map(fxp, x[1:], seed=2**64 - 1, sid=2**63 + 12345)
+
+
+def test_map_random_index_beyond_32_bits_is_keyed_by_element(fxp):
+    """Row-major element index drives the random word, independent of the tiling."""
+    say("map reshape invariance")
+    x = np.random.default_rng(5).standard_normal((512, 1024)).astype(np.float32)
+    e = dev(np.array([oracle.scale(x)], np.int32))
+    a, _ = fxp.map(dev(x), e, 9, 4)
+    b, _ = fxp.map(dev(x.reshape(2048, 256)), e, 9, 4)
+    c, _ = fxp.map(dev(x.reshape(64, 8192)), e, 9, 4)
+    assert np.array_equal(host(a).ravel(), host(b).ravel()) and np.array_equal(host(a).ravel(), host(c).ravel())
+
+
+def test_scale_map_fused_equals_two_calls(fxp):
+    for shape in [(300, 516), (64, 64), (100, 7)]:
+        say("scale_map", shape)
+        x = np.random.default_rng(shape[1]).standard_normal(shape).astype(np.float32) * 37
+        e, q, qT = fxp.scale_map(dev(x), 5, 6, want_q=True, want_qT=True)
+        eo = oracle.scale(x)
+        assert int(host(e)[0]) == eo
+        want = oracle.map(x, eo, seed=5, stream_id=6)
+        assert np.array_equal(host(q), want) and np.array_equal(host(qT), want.T)
+
+
+# --------------------------------------------------------------------------- gemm
+def rand_i8(rng, shape, lo=-127, hi=127):
+    return rng.integers(lo, hi + 1, size=shape, dtype=np.int64).astype(np.int8)
+
+
+GEMM_SHAPES = [(128, 128, 64), (256, 256, 128), (300, 200, 160), (1, 1, 16), (33, 65, 48), (129, 257, 80),
+               (512, 768, 256), (64, 64, 0), (100, 90, 50), (17, 5, 7), (128, 128, 4096), (1152, 128, 6272),
+               (1024, 2048, 512), (2100, 1800, 320)]
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+def test_gemm_all_operand_forms(fxp, M, N, K):
+    rng = np.random.default_rng(M * 31 + N * 17 + K)
+    A, B = rand_i8(rng, (M, K)), rand_i8(rng, (K, N))
+    want = oracle.gemm(A, np.ascontiguousarray(B.T), transB=True)
+    AT, BT = np.ascontiguousarray(A.T), np.ascontiguousarray(B.T)
+    for tA, tB, a, b in [(False, True, A, BT), (False, False, A, B), (True, False, AT, B), (True, True, AT, BT)]:
+        say("gemm", (M, N, K), "transA", tA, "transB", tB)
+        got = host(fxp.gemm(dev(a), dev(b), transA=tA, transB=tB))
+        assert got.dtype == np.int32 and np.array_equal(got, want)
+
+
+def test_gemm_extreme_values_longest_contraction(fxp):
+    K = 25088
+    say("gemm extremes K", K)
+    A = np.full((130, K), 127, np.int8)
+    B = np.full((70, K), -127, np.int8)
+    A[::2] = -127
+    got = host(fxp.gemm(dev(A), dev(B), transB=True))
+    want = oracle.gemm(A, B, transB=True)
+    assert np.array_equal(got, want) and abs(int(got[0, 0])) == 16129 * K
+
+
+def test_gemm_is_deterministic(fxp):
+    say("gemm determinism (split-K atomics)")
+    rng = np.random.default_rng(1)
+    A, B = dev(rand_i8(rng, (256, 8192))), dev(rand_i8(rng, (128, 8192)))
+    first = host(fxp.gemm(A, B, transB=True))
+    for _ in range(3):
+        assert np.array_equal(host(fxp.gemm(A, B, transB=True)), first)
+
+
+# --------------------------------------------------------------------------- unmap
+def test_unmap_all_exponent_ranges(fxp):
+    rng = np.random.default_rng(2)
+    special = np.array([0, 1, -1, (1 << 24) + 1, (1 << 24) + 3, -(1 << 24) - 1, (1 << 25) + 2, 2**31 - 1, -2**31,
+                        0x00FFFFFF, 3, 5], dtype=np.int64).astype(np.int32)
+    acc = np.concatenate([special, rng.integers(-2**31, 2**31, 100_003, dtype=np.int64).astype(np.int32),
+                          rng.integers(-5000, 5000, 50_000, dtype=np.int64).astype(np.int32)])
+    for eA, eB in [(133, 133), (1, 1), (1, 90), (1, 100), (10, 100), (60, 66), (70, 70), (254, 200), (254, 240),
+                   (254, 254), (127, None), (1, None), (254, None)]:
+        say("unmap", eA, eB)
+        eBd = None if eB is None else dev(np.array([eB], np.int32))
+        got = host(fxp.unmap(dev(acc), dev(np.array([eA], np.int32)), eBd))
+        assert same_bits(got, oracle.unmap(acc, eA, eB))
+    say("unmap in place, odd offset, bits")
+    a = dev(acc[1:])                      # 4-byte but not 16-byte aligned
+    e7 = dev(np.array([140], np.int32))
+    out = fxp.unmap(a, e7, e7, bitsA=5, bitsB=7, out=a.view(torch.float32))
+    assert same_bits(host(out), oracle.unmap(acc[1:], 140, 140, bitsA=5, bitsB=7))
+    q = np.arange(-128, 128).astype(np.int8)
+    assert same_bits(host(fxp.unmap_i8(dev(q), dev(np.array([3], np.int32)))), oracle.unmap_i8(q, 3))
+
+
+@pytest.mark.parametrize("M,N,K", [(300, 200, 160), (128, 128, 4096), (512, 768, 256), (1024, 1280, 64)])
+def test_gemm_unmap_fused(fxp, M, N, K):
+    rng = np.random.default_rng(M + N + K)
+    A, B = rand_i8(rng, (M, K)), rand_i8(rng, (N, K))
+    acc = oracle.gemm(A, B, transB=True)
+    for eA, eB in [(127, 120), (3, 2), (250, 250)]:
+        say("gemm_unmap", (M, N, K), eA, eB)
+        got = host(fxp.gemm_unmap(dev(A), dev(B), dev(np.array([eA], np.int32)), dev(np.array([eB], np.int32)),
+                                  transB=True))
+        assert same_bits(got, oracle.unmap(acc, eA, eB))
+
+
+# --------------------------------------------------------------------------- layer
+def layer_check_full(fxp, X, W, dY, seed, step, rounding=0, bits=8):
+    M, K = X.shape
+    N = W.shape[1]
+    buf = fxp.LayerBuffers(M, K, N)
+    Y = fxp.linear_fwd(dev(X), dev(W), buf, seed, step, rounding, bits)
+    dX, dW = fxp.linear_bwd(dev(dY), buf, seed, step, rounding, bits)
+    Yo, saved = oracle.linear_fwd(X, W, seed, step, rounding, bits)
+    dXo, dWo, aux = oracle.linear_bwd(dY, saved, seed, step, rounding, bits)
+    assert host(buf.e).tolist() == [saved["eX"], saved["eW"], aux["eG"]]
+    assert np.array_equal(host(buf.Xq), saved["Xq"]) and np.array_equal(host(buf.XqT), saved["Xq"].T)
+    assert np.array_equal(host(buf.Wq), saved["Wq"]) and np.array_equal(host(buf.WqT), saved["Wq"].T)
+    assert np.array_equal(host(buf.dYq), aux["dYq"]) and np.array_equal(host(buf.dYqT), aux["dYq"].T)
+    assert same_bits(host(Y), Yo)
+    assert same_bits(host(dX), dXo)
+    assert same_bits(host(dW), dWo)
+    return buf
+
+
+def test_layer_c1_full(fxp):
+    say("layer c1 256^3, seed 0")
+    X, W, dY = synth.layer_tensors("c1")
+    layer_check_full(fxp, X, W, dY, seed=0, step=0)
+    say("layer c1 nearest, 6 bits")
+    layer_check_full(fxp, X, W, dY, seed=0, step=3, rounding=1, bits=6)
+
+
+@pytest.mark.parametrize("workload,scale_down,sigma", [("c2", 8, 1.0), ("c3", 16, 1.0), ("c5", 16, 1e-6),
+                                                        ("c5", 16, 1e3)])
+def test_layer_reduced_workloads_full_check(fxp, workload, scale_down, sigma):
+    say("layer reduced", workload, scale_down, sigma)
+    X, W, dY = synth.layer_tensors(workload, scale_down=scale_down, sigma=sigma)
+    layer_check_full(fxp, X, W, dY, seed=1, step=2)
+
+
+def test_layer_ragged_shapes(fxp):
+    for (M, K, N) in [(100, 48, 36), (257, 130, 66), (5, 7, 3), (1, 16, 1)]:
+        say("layer ragged", (M, K, N))
+        rng = np.random.default_rng(M)
+        X = rng.standard_normal((M, K)).astype(np.float32)
+        W = (rng.standard_normal((K, N)) * 0.1).astype(np.float32)
+        dY = rng.laplace(0, 1e-3, (M, N)).astype(np.float32)
+        layer_check_full(fxp, X, W, dY, seed=4, step=1)
+
+
+def test_layer_only_one_gradient(fxp):
+    say("layer dW only / dX only")
+    X, W, dY = synth.layer_tensors("c1")
+    buf = fxp.LayerBuffers(256, 256, 256)
+    fxp.linear_fwd(dev(X), dev(W), buf, 0, 0)
+    buf.dX.fill_(7.0)
+    dX, dW = fxp.linear_bwd(dev(dY), buf, 0, 0, need_dX=False)
+    assert dX is None and float(buf.dX.min()) == 7.0
+    _, saved = oracle.linear_fwd(X, W, 0, 0)
+    _, dWo, _ = oracle.linear_bwd(dY, saved, 0, 0, need_dX=False)
+    assert same_bits(host(dW), dWo)
+
+
+def test_binding_refuses_cpu_tensors(fxp):
+    with pytest.raises(fxp.FxpError):
+        fxp.scale(torch.zeros(4))
