@@ -1,0 +1,222 @@
+#!/usr/bin/env python3
+"""Benchmark of the integer linear-layer step (scale -> map -> int8 GEMM x3 -> inverse map)
+on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2]
+
+A "step" is one forward + backward pass of every linear layer of the workload through
+fxp_linear_fwd / fxp_linear_bwd on synthetic inputs already resident in HBM.  Prints ONE
+JSON line: whole-step throughput in TOPS (3 GEMMs x 2MNK integer ops per layer), a
+`roofline` object for the kernel class that takes the most time (per-launch durations
+measured with HIP events on the launching stream, same kernels and arguments as the
+step), a `kernels` table for all classes, and `cpu_baseline`: the CPU oracle timed on a
+bounded sample of the same workload on the host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, published
+PEAK_INT8_TOPS = 5000.0      # MI355X dense int8 MFMA, published (5.0 POP/s)
+RIDGE_OPS_PER_BYTE = PEAK_INT8_TOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--sigma", type=float, default=1.0, help="c5 only")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    return ap.parse_args()
+
+
+def read_traffic(workload, kernel_class):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, or None.
+
+    File format (profiles/pmc_<workload>.txt): lines `traffic_bytes_per_launch <class> <bytes>`."""
+    path = os.path.join(ROOT, "profiles", f"pmc_{workload}.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) == 3 and parts[0] == "traffic_bytes_per_launch" and parts[1] == kernel_class:
+                    return float(parts[2])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    args = parse_args()
+    world = int(os.environ.get("WORLD_SIZE", "1"))
+    if args.gpus != 1 or world != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2207_08822_amd import fxp, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; libfxp has no CPU path", file=sys.stderr)
+        sys.exit(3)
+    fxp.lib()
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    layers = synth.WORKLOADS[args.workload]
+    host_inputs, dev_inputs, bufs = [], [], []
+    for li, layer in enumerate(layers):
+        X, W, dY = synth.layer_tensors(args.workload, li, sigma=args.sigma)
+        host_inputs.append((X, W, dY))
+        dev_inputs.append(tuple(torch.from_numpy(a).to(dev) for a in (X, W, dY)))
+        bufs.append(fxp.LayerBuffers(layer.M, layer.K, layer.N, device=dev))
+    seed = 0
+
+    def step(i):
+        for (X, W, dY), buf in zip(dev_inputs, bufs):
+            fxp.linear_fwd(X, W, buf, seed=seed, step=i)
+            fxp.linear_bwd(dY, buf, seed=seed, step=i)
+
+    # ------------------------------------------------------------------ whole step
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ops_per_step = sum(synth.ops_per_layer(l) for l in layers)
+    tops = ops_per_step / (ms_per_step * 1e-3) / 1e12
+
+    # ------------------------------------------------------------------ per-kernel durations
+    # Same kernels, same arguments as the step, launched back to back on the current
+    # stream between two HIP events (torch.cuda.Event on the current stream, which is the
+    # stream the binding hands to the library).
+    reps = max(5, min(args.steps, 50))
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps     # seconds per launch
+
+    classes = {"scale": dict(t=0.0, launches=0, bytes=0.0, ops=0.0), "map": dict(t=0.0, launches=0, bytes=0.0, ops=0.0),
+               "gemm": dict(t=0.0, launches=0, bytes=0.0, ops=0.0)}
+    gemm_rows = []
+    for layer, (X, W, dY), buf in zip(layers, dev_inputs, bufs):
+        M, K, N = layer.M, layer.K, layer.N
+        ws = torch.empty(max(256, fxp.workspace_bytes(fxp.OP_SCALE, 0)), dtype=torch.uint8, device=dev)
+        for t, e in ((X, buf.eX), (W, buf.eW), (dY, buf.e_dY)):
+            n = t.numel()
+            q = torch.empty(t.shape, dtype=torch.int8, device=dev)
+            qT = torch.empty((t.shape[1], t.shape[0]), dtype=torch.int8, device=dev)
+            lib, p = fxp.lib(), (lambda z: z.data_ptr())
+            st = torch.cuda.current_stream().cuda_stream
+            dt = timed(lambda: lib.fxp_scale(p(t), n, p(e), p(ws), ws.numel(), st))
+            c = classes["scale"]; c["t"] += dt; c["launches"] += 1; c["bytes"] += 4.0 * n
+            dt = timed(lambda: lib.fxp_map(p(t), t.shape[0], t.shape[1], p(e), p(q), p(qT), seed, 0, 0, 8, st))
+            c = classes["map"]; c["t"] += dt; c["launches"] += 1; c["bytes"] += 6.0 * n
+            del q, qT
+        gemms = [("fwd", M, N, K, buf.Xq, buf.WqT, buf.eX, buf.eW, buf.Y),
+                 ("dX", M, K, N, buf.dYq, buf.Wq, buf.e_dY, buf.eW, buf.dX),
+                 ("dW", K, N, M, buf.XqT, buf.dYqT, buf.eX, buf.e_dY, buf.dW)]
+        for name, gm, gn, gk, A, B, eA, eB, C in gemms:
+            lib, p = fxp.lib(), (lambda z: z.data_ptr())
+            st = torch.cuda.current_stream().cuda_stream
+            dt = timed(lambda: lib.fxp_gemm_unmap(0, 1, gm, gn, gk, p(A), gk, p(B), gk, p(eA), 8, p(eB), 8, p(C), gn,
+                                                  None, 0, st))
+            ops, nbytes = 2.0 * gm * gn * gk, float(gm * gk + gn * gk + 4 * gm * gn)
+            t_roof = max(ops / (PEAK_INT8_TOPS * 1e12), nbytes / (PEAK_HBM_GBS * 1e9))
+            gemm_rows.append(dict(layer=layer.name, gemm=name, M=gm, N=gn, K=gk, us=round(dt * 1e6, 2),
+                                  tops=round(ops / dt / 1e12, 1), gbs=round(nbytes / dt / 1e9, 1),
+                                  bound="mfma" if ops / nbytes > RIDGE_OPS_PER_BYTE else "hbm",
+                                  frac_of_roofline=round(t_roof / dt, 3)))
+            c = classes["gemm"]; c["t"] += dt; c["launches"] += 1; c["bytes"] += nbytes; c["ops"] += ops
+
+    dominant = max(classes, key=lambda k: classes[k]["t"])
+    c = classes[dominant]
+    avg_launch = c["t"] / c["launches"]
+    if dominant == "gemm" and c["ops"] / c["bytes"] > RIDGE_OPS_PER_BYTE:
+        achieved = c["ops"] / c["t"] / 1e12
+        roofline = dict(bound="mfma", achieved=round(achieved, 2), peak=PEAK_INT8_TOPS, unit="TOP/s",
+                        frac=round(achieved / PEAK_INT8_TOPS, 4))
+    else:
+        achieved = c["bytes"] / c["t"] / 1e9
+        roofline = dict(bound="hbm", achieved=round(achieved, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                        frac=round(achieved / PEAK_HBM_GBS, 4))
+    kernel_names = {"scale": "k_absmax_partials", "map": "k_map_tile<true>", "gemm": "k_gemm_nt"}
+    traffic = read_traffic(args.workload, dominant)
+    roofline.update(kernel=kernel_names[dominant], launches_per_step=c["launches"],
+                    avg_launch_us=round(avg_launch * 1e6, 2),
+                    algorithmic_per_launch=(c["ops"] if roofline["bound"] == "mfma" else c["bytes"]) / c["launches"],
+                    traffic=traffic)
+    kernels = {k: dict(launches_per_step=v["launches"], us_per_step=round(v["t"] * 1e6, 2),
+                       gbs=round(v["bytes"] / v["t"] / 1e9, 1),
+                       tops=(round(v["ops"] / v["t"] / 1e12, 1) if v["ops"] else None)) for k, v in classes.items()}
+
+    # ------------------------------------------------------------------ CPU oracle on a bounded sample
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        X, W, dY = host_inputs[0]
+        layer = layers[0]
+        # a few rows first to size the sample to about --cpu-seconds of CPU work
+        probe_rows = min(layer.M, 64)
+        t = time.perf_counter()
+        _, sv = oracle.linear_fwd(X[:probe_rows], W, seed=seed, step=0)
+        oracle.linear_bwd(dY[:probe_rows], sv, seed=seed, step=0)
+        per_row = (time.perf_counter() - t) / probe_rows
+        rows = int(max(probe_rows, min(layer.M, args.cpu_seconds / max(per_row, 1e-9))))
+        t = time.perf_counter()
+        _, sv = oracle.linear_fwd(X[:rows], W, seed=seed, step=0)
+        oracle.linear_bwd(dY[:rows], sv, seed=seed, step=0)
+        dt = time.perf_counter() - t
+        sample_ops = 3 * 2.0 * rows * layer.K * layer.N
+        cpu = dict(value=round(sample_ops / dt / 1e12, 6), unit="TOPS", cores=oracle.num_threads(), kind="oracle",
+                   seconds=round(dt, 2),
+                   sample=f"layer {layer.name}: first {rows} of {layer.M} rows of X and dY, full W; fwd+bwd")
+
+    out = {
+        "metric": "int8 fixed-point layer fwd+bwd TOPS",
+        "value": round(tops, 3),
+        "unit": "TOPS",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int8",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: " + ", ".join(f"{l.name} M={l.M} K={l.K} N={l.N}" for l in layers)
+                   + (f", sigma={args.sigma}" if args.workload == "c5" else ""),
+                   "pass": "scale+map X,W,dY (int8, both orientations) + 3 int8 GEMMs with fused inverse map",
+                   "rounding": "stochastic (Philox-4x32-10)", "bits": 8},
+        "map_gbs": kernels["map"]["gbs"],
+        "roofline": roofline,
+        "kernels": kernels,
+        "gemms": gemm_rows,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
