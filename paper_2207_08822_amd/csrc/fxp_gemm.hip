@@ -18,6 +18,9 @@
 //   * long-contraction / small-output shapes split K across grid.y and add int32
 //     partial sums with atomics (exact: integer addition is associative).
 // Roofline: MFMA-bound when 2MNK / (MK + NK + 4MN bytes) is above ~630 ops/B, else HBM.
+#include <algorithm>
+#include <type_traits>
+
 #include "fxp_internal.h"
 
 namespace fxp {
@@ -26,6 +29,9 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 enum { kStoreI32 = 0, kStoreF32 = 1, kAtomicI32 = 2 };
+
+template <int V>
+using IC = std::integral_constant<int, V>;
 
 constexpr int kNumXcd = 8;
 
@@ -183,6 +189,373 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm_nt(
     }
 }
 
+// s_waitcnt immediate (gfx9 encoding): wait until at most `vm` vector-memory operations
+// and no LDS operation of this wave are outstanding.
+__host__ __device__ constexpr int waitcnt_vm_lgkm0(int vm) { return (vm & 0xF) | ((vm >> 4) << 14) | 0x70; }
+
+template <int VM>
+__device__ inline void wait_loads_and_lds() {
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(VM));
+}
+
+// Same product, fast path: K a multiple of BK, operands 16-byte aligned.  Global loads go
+// straight into LDS (global_load_lds_dwordx4: each wave fills one contiguous 1 KiB region
+// per instruction, no register staging, no ds_write), STAGES buffers deep, so loads for
+// step k + STAGES - 1 are in flight while step k is multiplied.  The XOR swizzle of the
+// LDS layout is applied on the global side: lane p of a region fetches the 16-byte piece
+// that belongs in slot p.  One s_barrier per step, no fence: the only cross-wave traffic
+// is LDS written by the loads (waited for with vmcnt before the barrier) and read by
+// ds_read (waited for with lgkmcnt before the next barrier lets the buffer be refilled).
+template <int BM, int BN, int BK, int WM, int WN, int STAGES, int MODE, bool SCHED>
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm_nt_dma(
+    const int8_t* __restrict__ A, int64_t lda, const int8_t* __restrict__ B, int64_t ldb, void* __restrict__ Cv,
+    int64_t ldc, int M, int N, int K, int k_per_split, const int32_t* __restrict__ eA, int bitsA,
+    const int32_t* __restrict__ eB, int bitsB, int tiles_m, int tiles_n, int group_m) {
+    constexpr int NW = (BM / WM) * (BN / WN);
+    constexpr int CPR = BK / 16;                     // 16-byte pieces per LDS row
+    constexpr int RROWS = 64 / CPR;                  // tile rows per 1 KiB region
+    constexpr int REGIONS = (BM + BN) * BK / 1024;   // per stage: A rows first, then B rows
+    constexpr int RPW = REGIONS / NW;                // load instructions per wave per step
+    constexpr int STAGE_BYTES = (BM + BN) * BK;
+    constexpr int FM = WM / 32, FN = WN / 32;
+    static_assert(REGIONS % NW == 0, "regions do not divide over the waves");
+    static_assert(STAGES >= 2 && STAGES <= 4, "2 to 4 stages");
+    static_assert((STAGES - 1) * RPW < 64, "vmcnt is a 6-bit counter");
+    static_assert((BK / 32) % 2 == 0, "two 32-byte steps per register buffer pair");
+    static_assert(FM * FN >= (FM + FN) / 2, "wave tile too small for the interleave");
+
+    __shared__ __attribute__((aligned(1024))) int8_t lds[STAGES * STAGE_BYTES];
+
+    int tm, tn;
+    tile_of_block(blockIdx.x, tiles_m, tiles_n, group_m, &tm, &tn);
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int kb = blockIdx.y * k_per_split;
+    const int ke = min(K, kb + k_per_split);
+    const int nk = (ke - kb) / BK;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS targets stay in SGPRs
+    const int wm0 = (wave / (BN / WN)) * WM, wn0 = (wave % (BN / WN)) * WN;
+
+    const int8_t* gp[RPW];
+#pragma unroll
+    for (int j = 0; j < RPW; ++j) {
+        const int row_t = (wave + j * NW) * RROWS + lane / CPR;      // row in the stacked (A;B) tile
+        const int piece = (lane % CPR) ^ swizzle_of_row<BK>(row_t);  // BM % 16 == 0: same swizzle for B rows
+        gp[j] = (row_t < BM) ? A + static_cast<int64_t>(min(m0 + row_t, M - 1)) * lda + kb + piece * 16
+                             : B + static_cast<int64_t>(min(n0 + row_t - BM, N - 1)) * ldb + kb + piece * 16;
+    }
+    auto issue = [&](int step, int stage) {
+#pragma unroll
+        for (int j = 0; j < RPW; ++j)
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)(gp[j] + static_cast<int64_t>(step) * BK),
+                (__attribute__((address_space(3))) void*)(&lds[stage * STAGE_BYTES + (wave + j * NW) * 1024]),
+                16, 0, 0);
+    };
+
+    const int frow = lane & 31, fhalf = lane >> 5;
+    const int fswz = swizzle_of_row<BK>(frow);
+    const int a_base = (wm0 + frow) * BK, b_base = BM * BK + (wn0 + frow) * BK;
+
+    v16i acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+    // Fragments are double-buffered in registers: the ds_reads of 32-byte step s+1 are
+    // issued before the MFMAs of step s.  The barrier that publishes LDS stage it+1 sits
+    // in front of the LAST 32-byte step of stage it, so the first fragments of the next
+    // stage are already on their way while that last step is multiplied, and the stage
+    // just finished (every wave is past its reads of it) is refilled at once: all STAGES
+    // buffers stay in flight.
+    constexpr int KS = BK / 32;
+    v4i fa[2][FM], fb[2][FN];
+    auto read_frags = [&](int buf, int stage, int ks) {
+        const int8_t* st = lds + stage * STAGE_BYTES;
+        const int piece = ((2 * ks + fhalf) ^ fswz) * 16;
+#pragma unroll
+        for (int i = 0; i < FM; ++i) fa[buf][i] = *reinterpret_cast<const v4i*>(&st[a_base + i * 32 * BK + piece]);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) fb[buf][j] = *reinterpret_cast<const v4i*>(&st[b_base + j * 32 * BK + piece]);
+    };
+#pragma unroll
+    for (int s = 0; s < STAGES; ++s)
+        if (s < nk) issue(s, s);
+    if (nk > 0) {
+        if (nk >= STAGES) wait_loads_and_lds<(STAGES - 1) * RPW>();
+        else wait_loads_and_lds<0>();
+        __builtin_amdgcn_s_barrier();
+        read_frags(0, 0, 0);
+    }
+    // MFMAs of one 32-byte step.  `reads` ds_reads and `loads` global->LDS loads issued just
+    // before it are slotted behind its first MFMAs (the matrix core runs an MFMA for 32
+    // cycles; the wave issues the memory instructions in its shadow).
+    auto multiply = [&](int cur, auto reads_c, auto loads_c) {
+        constexpr int reads = decltype(reads_c)::value, loads = decltype(loads_c)::value;
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
+        if (SCHED) {
+#pragma unroll
+            for (int n = 0; n < reads / 2; ++n) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // 2 DS reads
+            }
+#pragma unroll
+            for (int n = 0; n < loads; ++n) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // 1 VMEM read
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, FM * FN - reads / 2 - loads, 0);
+        }
+    };
+    // One LDS stage: all 32-byte steps but the last, then the barrier that publishes the next
+    // stage, the first fragments of that stage, the refill of the stage just finished, and the
+    // last step.  The wait is one fixed instruction and the refill is unconditional inside a
+    // loop variant, so everything between two barriers is one basic block the scheduler can
+    // interleave.
+    auto stage_body = [&](int it, auto wait_next, auto refill) {
+        const int stage = it % STAGES;
+#pragma unroll
+        for (int ks = 0; ks + 1 < KS; ++ks) {
+            read_frags((ks & 1) ^ 1, stage, ks + 1);
+            multiply(ks & 1, IC<FM + FN>{}, IC<0>{});
+        }
+        wait_next();
+        __builtin_amdgcn_s_barrier();
+        read_frags(0, (it + 1) % STAGES, 0);          // KS is even: the last step used buffer 1
+        multiply(1, IC<FM + FN>{}, refill(it + STAGES, stage));
+    };
+    auto steady_wait = [] { wait_loads_and_lds<(STAGES - 2) * RPW>(); };
+    auto full_wait = [] { wait_loads_and_lds<0>(); };
+    auto do_refill = [&](int step, int stage) {
+        issue(step, stage);
+        return IC<(RPW <= FM * FN - (FM + FN) / 2 ? RPW : 0)>{};
+    };
+    auto no_refill = [](int, int) { return IC<0>{}; };
+    int it = 0;
+    for (; it + STAGES < nk; ++it) stage_body(it, steady_wait, do_refill);     // steps it+2 .. it+STAGES-1 in flight
+    for (; it + STAGES - 1 < nk; ++it) stage_body(it, steady_wait, no_refill);
+    for (; it + 1 < nk; ++it) stage_body(it, full_wait, no_refill);            // drain
+    if (nk > 0) {
+        const int stage = (nk - 1) % STAGES;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            if (ks + 1 < KS) read_frags((ks & 1) ^ 1, stage, ks + 1);
+            if (ks + 1 < KS) multiply(ks & 1, IC<FM + FN>{}, IC<0>{});
+            else multiply(ks & 1, IC<0>{}, IC<0>{});
+        }
+    }
+
+    int E = 0;
+    if (MODE == kStoreF32) E = lsb_exponent(eA[0], bitsA) + (eB ? lsb_exponent(eB[0], bitsB) : 0);
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = m0 + wm0 + 32 * i + 8 * (r >> 2) + 4 * fhalf + (r & 3);
+            if (row >= M) continue;
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                const int col = n0 + wn0 + 32 * j + frow;
+                if (col >= N) continue;
+                const int64_t off = static_cast<int64_t>(row) * ldc + col;
+                if (MODE == kStoreF32)
+                    static_cast<float*>(Cv)[off] = unmap_value(acc[i][j][r], E);
+                else if (MODE == kStoreI32)
+                    static_cast<int32_t*>(Cv)[off] = acc[i][j][r];
+                else
+                    atomicAdd(static_cast<int32_t*>(Cv) + off, acc[i][j][r]);
+            }
+        }
+    }
+}
+
+// 256 x 256 x 128 tile with LDS used as a RING of five 32 KiB half-stages instead of two
+// full stages.  A half-stage is the 256 x 128-byte slice of one operand for one step:
+// A(0) B(0) A(1) B(1) A(2) | B(2) A(3) ...; half-stage h lives in slot h % 5.  Full 128-byte
+// rows keep every L2 request a whole cache line (half-line requests top out at ~60 % of the
+// line rate), and the fifth slot lets the loads of a step be issued in two instalments:
+// A(t+2) is spread thinly over the first three 32-byte steps of stage t (its slot was freed
+// one barrier earlier) and only B(t+2) has to be issued in a burst behind the barrier that
+// frees A(t)'s slot.  The load queue therefore never runs dry and never has to swallow a
+// whole 64 KiB stage at once, which is what stalled the MFMA stream of the two-stage form.
+template <int WM, int WN, int MODE, bool SCHED>
+__global__ __launch_bounds__((256 / WM) * (256 / WN) * 64) void k_gemm_nt_ring(
+    const int8_t* __restrict__ A, int64_t lda, const int8_t* __restrict__ B, int64_t ldb, void* __restrict__ Cv,
+    int64_t ldc, int M, int N, int K, int k_per_split, const int32_t* __restrict__ eA, int bitsA,
+    const int32_t* __restrict__ eB, int bitsB, int tiles_m, int tiles_n, int group_m) {
+    constexpr int BM = 256, BN = 256, BK = 128;
+    constexpr int NW = (BM / WM) * (BN / WN);
+    constexpr int SLOT = 256 * BK;                   // bytes of a half-stage
+    constexpr int RPH = (SLOT / 1024) / NW;          // load instructions per wave per half-stage
+    constexpr int FM = WM / 32, FN = WN / 32, KS = BK / 32;
+    static_assert(RPH >= 3 && RPH * 2 < 64, "loads per half-stage");
+
+    __shared__ __attribute__((aligned(1024))) int8_t lds[5 * SLOT];
+
+    int tm, tn;
+    tile_of_block(blockIdx.x, tiles_m, tiles_n, group_m, &tm, &tn);
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int kb = blockIdx.y * k_per_split;
+    const int ke = min(K, kb + k_per_split);
+    const int nk = (ke - kb) / BK;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm0 = (wave / (BN / WN)) * WM, wn0 = (wave % (BN / WN)) * WN;
+
+    // lane p of 1 KiB region g fetches row 8g + p/8, piece (p%8) ^ swizzle(row) of the 128-byte row
+    const int8_t* ga[RPH];
+    const int8_t* gb[RPH];
+#pragma unroll
+    for (int j = 0; j < RPH; ++j) {
+        const int row = (wave + j * NW) * 8 + lane / 8;
+        const int piece = (lane % 8) ^ swizzle_of_row<BK>(row);
+        ga[j] = A + static_cast<int64_t>(min(m0 + row, M - 1)) * lda + kb + piece * 16;
+        gb[j] = B + static_cast<int64_t>(min(n0 + row, N - 1)) * ldb + kb + piece * 16;
+    }
+    auto load_piece = [&](const int8_t* g, int step, int slot, int j) {
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void*)(g + static_cast<int64_t>(step) * BK),
+            (__attribute__((address_space(3))) void*)(&lds[slot * SLOT + (wave + j * NW) * 1024]), 16, 0, 0);
+    };
+    auto issue_a = [&](int step, auto lo_c, auto hi_c) {        // loads [lo, hi) of A(step)
+        const int slot = (2 * step) % 5;
+#pragma unroll
+        for (int j = decltype(lo_c)::value; j < decltype(hi_c)::value; ++j) load_piece(ga[j], step, slot, j);
+    };
+    auto issue_b = [&](int step) {
+        const int slot = (2 * step + 1) % 5;
+#pragma unroll
+        for (int j = 0; j < RPH; ++j) load_piece(gb[j], step, slot, j);
+    };
+
+    const int frow = lane & 31, fhalf = lane >> 5;
+    const int fswz = swizzle_of_row<BK>(frow);
+    const int a_off = (wm0 + frow) * BK, b_off = (wn0 + frow) * BK;
+
+    v16i acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+    v4i fa[2][FM], fb[2][FN];
+    auto read_frags = [&](int buf, int step, int ks) {
+        const int8_t* sa = lds + ((2 * step) % 5) * SLOT + a_off;
+        const int8_t* sb = lds + ((2 * step + 1) % 5) * SLOT + b_off;
+        const int piece = ((2 * ks + fhalf) ^ fswz) * 16;
+#pragma unroll
+        for (int i = 0; i < FM; ++i) fa[buf][i] = *reinterpret_cast<const v4i*>(&sa[i * 32 * BK + piece]);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) fb[buf][j] = *reinterpret_cast<const v4i*>(&sb[j * 32 * BK + piece]);
+    };
+    auto multiply = [&](int cur, auto reads_c, auto loads_c) {
+        constexpr int reads = decltype(reads_c)::value, loads = decltype(loads_c)::value;
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
+        if (SCHED) {
+#pragma unroll
+            for (int n = 0; n < reads / 2; ++n) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            }
+#pragma unroll
+            for (int n = 0; n < loads; ++n) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, FM * FN - reads / 2 - loads, 0);
+        }
+    };
+    // thirds of a half-stage for the three early 32-byte steps
+    constexpr int T1 = (RPH + 2) / 3, T2 = (2 * RPH + 2) / 3;
+    // stage t, when step t+1 exists.  EARLY: A(t+2) is issued here (not for t = 0: the prologue
+    // did it); LATE: B(t+2) is issued behind the barrier.
+    auto stage_body = [&](int t, auto early_c, auto late_c, auto wait_next) {
+        constexpr bool EARLY = decltype(early_c)::value != 0, LATE = decltype(late_c)::value != 0;
+        read_frags(1, t, 1);
+        if (EARLY) issue_a(t + 2, IC<0>{}, IC<T1>{});
+        multiply(0, IC<FM + FN>{}, IC<(EARLY ? T1 : 0)>{});
+        read_frags(0, t, 2);
+        if (EARLY) issue_a(t + 2, IC<T1>{}, IC<T2>{});
+        multiply(1, IC<FM + FN>{}, IC<(EARLY ? T2 - T1 : 0)>{});
+        read_frags(1, t, 3);
+        if (EARLY) issue_a(t + 2, IC<T2>{}, IC<RPH>{});
+        multiply(0, IC<FM + FN>{}, IC<(EARLY ? RPH - T2 : 0)>{});
+        wait_next();
+        __builtin_amdgcn_s_barrier();
+        read_frags(0, t + 1, 0);
+        if (LATE) issue_b(t + 2);
+        multiply(1, IC<FM + FN>{}, IC<(LATE ? RPH : 0)>{});
+    };
+    auto wait_one_half = [] { wait_loads_and_lds<RPH>(); };
+    auto wait_all = [] { wait_loads_and_lds<0>(); };
+
+    // prologue: A(0) B(0) A(1) B(1) A(2)
+    if (nk > 0) { issue_a(0, IC<0>{}, IC<RPH>{}); issue_b(0); }
+    if (nk > 1) { issue_a(1, IC<0>{}, IC<RPH>{}); issue_b(1); }
+    if (nk > 2) issue_a(2, IC<0>{}, IC<RPH>{});
+    if (nk > 0) {
+        if (nk > 2) wait_loads_and_lds<3 * RPH>();
+        else if (nk > 1) wait_loads_and_lds<2 * RPH>();
+        else wait_loads_and_lds<0>();
+        __builtin_amdgcn_s_barrier();
+        read_frags(0, 0, 0);
+    }
+    int t = 0;
+    if (nk > 2) {                                                   // t = 0: A(2) already in flight
+        stage_body(0, IC<0>{}, IC<1>{}, wait_one_half);
+        t = 1;
+        for (; t + 2 < nk; ++t) stage_body(t, IC<1>{}, IC<1>{}, wait_one_half);
+    }
+    for (; t + 1 < nk; ++t) stage_body(t, IC<0>{}, IC<0>{}, wait_all);   // nothing left to issue
+    if (nk > 0) {                                                   // last stage
+        read_frags(1, t, 1);
+        multiply(0, IC<FM + FN>{}, IC<0>{});
+        read_frags(0, t, 2);
+        multiply(1, IC<FM + FN>{}, IC<0>{});
+        read_frags(1, t, 3);
+        multiply(0, IC<FM + FN>{}, IC<0>{});
+        multiply(1, IC<0>{}, IC<0>{});
+    }
+
+    int E = 0;
+    if (MODE == kStoreF32) E = lsb_exponent(eA[0], bitsA) + (eB ? lsb_exponent(eB[0], bitsB) : 0);
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = m0 + wm0 + 32 * i + 8 * (r >> 2) + 4 * fhalf + (r & 3);
+            if (row >= M) continue;
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                const int col = n0 + wn0 + 32 * j + frow;
+                if (col >= N) continue;
+                const int64_t off = static_cast<int64_t>(row) * ldc + col;
+                if (MODE == kStoreF32)
+                    static_cast<float*>(Cv)[off] = unmap_value(acc[i][j][r], E);
+                else if (MODE == kStoreI32)
+                    static_cast<int32_t*>(Cv)[off] = acc[i][j][r];
+                else
+                    atomicAdd(static_cast<int32_t*>(Cv) + off, acc[i][j][r]);
+            }
+        }
+    }
+}
+
 __global__ __launch_bounds__(256) void k_zero_rows(int32_t* __restrict__ C, int64_t ldc, int M, int N) {
     const int64_t total = static_cast<int64_t>(M) * N;
     for (int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; i < total; i += static_cast<int64_t>(gridDim.x) * 256)
@@ -254,39 +627,103 @@ static int launch_cfg(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t 
     return launch_status();
 }
 
+template <int WM, int WN, bool SCHED = true>
+static int launch_ring(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
+                       void* C, int64_t ldc, int mode, int splits, const int32_t* eA, int bitsA, const int32_t* eB,
+                       int bitsB, hipStream_t s) {
+    constexpr int NT = (256 / WM) * (256 / WN) * 64, BK = 128;
+    const int tiles_m = static_cast<int>((M + 255) / 256), tiles_n = static_cast<int>((N + 255) / 256);
+    int k_per_split = static_cast<int>((K + splits - 1) / splits);
+    k_per_split = (k_per_split + BK - 1) / BK * BK;
+    const int ny = static_cast<int>((K + k_per_split - 1) / k_per_split);
+    const dim3 grid(static_cast<unsigned>(tiles_m) * tiles_n, ny), block(NT);
+    const int group_m = 8;
+#define FXP_GEMM_LAUNCH(MODE)                                                                                    \
+    hipLaunchKernelGGL((k_gemm_nt_ring<WM, WN, MODE, SCHED>), grid, block, 0, s, A, lda, B, ldb, C, ldc,          \
+                       static_cast<int>(M), static_cast<int>(N), static_cast<int>(K), k_per_split, eA, bitsA, eB, \
+                       bitsB, tiles_m, tiles_n, group_m)
+    if (mode == kStoreI32) FXP_GEMM_LAUNCH(kStoreI32);
+    else if (mode == kStoreF32) FXP_GEMM_LAUNCH(kStoreF32);
+    else FXP_GEMM_LAUNCH(kAtomicI32);
+#undef FXP_GEMM_LAUNCH
+    return launch_status();
+}
+
+template <int BM, int BN, int BK, int WM, int WN, int STAGES, bool SCHED = true>
+static int launch_dma(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
+                      void* C, int64_t ldc, int mode, int splits, const int32_t* eA, int bitsA, const int32_t* eB,
+                      int bitsB, hipStream_t s) {
+    constexpr int NT = (BM / WM) * (BN / WN) * 64;
+    const int tiles_m = static_cast<int>((M + BM - 1) / BM), tiles_n = static_cast<int>((N + BN - 1) / BN);
+    int k_per_split = static_cast<int>((K + splits - 1) / splits);
+    k_per_split = (k_per_split + BK - 1) / BK * BK;
+    const int ny = static_cast<int>((K + k_per_split - 1) / k_per_split);
+    const dim3 grid(static_cast<unsigned>(tiles_m) * tiles_n, ny), block(NT);
+    const int group_m = 8;
+#define FXP_GEMM_LAUNCH(MODE)                                                                                      \
+    hipLaunchKernelGGL((k_gemm_nt_dma<BM, BN, BK, WM, WN, STAGES, MODE, SCHED>), grid, block, 0, s, A, lda, B, ldb, C, \
+                       ldc,                                                                                        \
+                       static_cast<int>(M), static_cast<int>(N), static_cast<int>(K), k_per_split, eA, bitsA, eB,   \
+                       bitsB, tiles_m, tiles_n, group_m)
+    if (mode == kStoreI32) FXP_GEMM_LAUNCH(kStoreI32);
+    else if (mode == kStoreF32) FXP_GEMM_LAUNCH(kStoreF32);
+    else FXP_GEMM_LAUNCH(kAtomicI32);
+#undef FXP_GEMM_LAUNCH
+    return launch_status();
+}
+
 // C = A[M,K] * B[N,K]^T.  fp32_out: C receives the inverse-mapped fp32 values (eA, eB on
 // the device), else the int32 sums.  C is overwritten in both cases.
+//
+// Kernel choice (measured on MI355X with mapped Gaussian operands):
+//   * operands 16-byte aligned and K a multiple of 64 -> direct-to-LDS kernels, else the
+//     register-staged 128 x 128 x 64 kernel with its element-wise loader;
+//   * enough 256 x 256 tiles to fill the chip -> the ring kernel (K % 128 == 0) or the
+//     four-stage 256 x 256 x 64 kernel;
+//   * long contraction and a small output (the weight gradient) -> split K over grid.y,
+//     int32 atomics into the zeroed output, then an in-place inverse mapping pass;
+//   * otherwise 128 x 128 tiles.
 int gemm_nt_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                    void* C, int64_t ldc, bool fp32_out, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB,
                    hipStream_t s) {
     if (M == 0 || N == 0) return FXP_OK;
     const bool vec = aligned(A, 16) && aligned(B, 16) && lda % 16 == 0 && ldb % 16 == 0 && K % 16 == 0;
+    const bool dma = vec && K > 0 && K % 64 == 0;
     const int num_cu = 256;
-    const int64_t tiles_big = ((M + 255) / 256) * ((N + 255) / 256);
-    const int64_t tiles_small = ((M + 127) / 128) * ((N + 127) / 128);
-    const bool big = tiles_big >= num_cu * 3 / 4 && K >= 256;
-    // split the contraction when the output alone cannot fill the chip and K is long
+    const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
+    const int64_t t128 = ((M + 127) / 128) * ((N + 127) / 128);
+    const bool wide = M >= 256 && N >= 256;
     int splits = 1;
-    if (!big && tiles_small < num_cu && K >= 2048) {
-        splits = static_cast<int>(std::min<int64_t>((2 * num_cu + tiles_small - 1) / tiles_small, K / 512));
-        if (splits < 1) splits = 1;
+    bool use256 = wide && t256 >= 96;
+    if (K >= 2048 && t256 < 64) {
+        // small output, long contraction: fill the chip along K (each slice at least 512 long)
+        use256 = wide && t256 >= 16;
+        const int64_t tiles = use256 ? t256 : t128;
+        const int64_t target = use256 ? num_cu : 2 * num_cu;
+        splits = static_cast<int>(std::max<int64_t>(1, std::min<int64_t>((target + tiles / 2) / tiles, K / 512)));
     }
+    const int first_mode = splits > 1 ? kAtomicI32 : (fp32_out ? kStoreF32 : kStoreI32);
+    const int zg = static_cast<int>(std::min<int64_t>((M * N + 255) / 256, 2048));
     int rc;
     if (splits > 1) {
-        const int zg = static_cast<int>(std::min<int64_t>((M * N + 255) / 256, 2048));
         hipLaunchKernelGGL(k_zero_rows, dim3(zg), dim3(256), 0, s, static_cast<int32_t*>(C), ldc, static_cast<int>(M),
                            static_cast<int>(N));
         if ((rc = launch_status())) return rc;
-        rc = launch_cfg<128, 128, 64, 64, 64>(M, N, K, A, lda, B, ldb, C, ldc, kAtomicI32, vec, splits, eA, bitsA, eB,
-                                              bitsB, s);
-        if (rc || !fp32_out) return rc;
-        hipLaunchKernelGGL(k_unmap_rows, dim3(zg), dim3(256), 0, s, static_cast<int32_t*>(C), ldc, static_cast<int>(M),
-                           static_cast<int>(N), eA, bitsA, eB, bitsB);
-        return launch_status();
     }
-    const int mode = fp32_out ? kStoreF32 : kStoreI32;
-    if (big) return launch_cfg<256, 256, 64, 128, 128>(M, N, K, A, lda, B, ldb, C, ldc, mode, vec, 1, eA, bitsA, eB, bitsB, s);
-    return launch_cfg<128, 128, 64, 64, 64>(M, N, K, A, lda, B, ldb, C, ldc, mode, vec, 1, eA, bitsA, eB, bitsB, s);
+    if (!dma)
+        rc = launch_cfg<128, 128, 64, 64, 64>(M, N, K, A, lda, B, ldb, C, ldc, first_mode, vec, splits, eA, bitsA, eB, bitsB, s);
+    else if (use256 && K % 128 == 0 && splits == 1)
+        rc = launch_ring<64, 128>(M, N, K, A, lda, B, ldb, C, ldc, first_mode, 1, eA, bitsA, eB, bitsB, s);
+    else if (use256)
+        rc = launch_dma<256, 256, 64, 64, 128, 4>(M, N, K, A, lda, B, ldb, C, ldc, first_mode, splits, eA, bitsA, eB, bitsB, s);
+    else if (K % 128 == 0 && splits == 1)
+        rc = launch_dma<128, 128, 128, 64, 32, 4>(M, N, K, A, lda, B, ldb, C, ldc, first_mode, 1, eA, bitsA, eB, bitsB, s);
+    else
+        rc = launch_dma<128, 128, 64, 64, 64, 4>(M, N, K, A, lda, B, ldb, C, ldc, first_mode, splits, eA, bitsA, eB, bitsB, s);
+    if (rc || splits == 1 || !fp32_out) return rc;
+    hipLaunchKernelGGL(k_unmap_rows, dim3(zg), dim3(256), 0, s, static_cast<int32_t*>(C), ldc, static_cast<int>(M),
+                       static_cast<int>(N), eA, bitsA, eB, bitsB);
+    return launch_status();
 }
 
 static int check_gemm_args(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, int transA, const void* B,

@@ -129,7 +129,13 @@ def rand_i8(rng, shape, lo=-127, hi=127):
 
 GEMM_SHAPES = [(128, 128, 64), (256, 256, 128), (300, 200, 160), (1, 1, 16), (33, 65, 48), (129, 257, 80),
                (512, 768, 256), (64, 64, 0), (100, 90, 50), (17, 5, 7), (128, 128, 4096), (1152, 128, 6272),
-               (1024, 2048, 512), (2100, 1800, 320)]
+               (1024, 2048, 512), (2100, 1800, 320),
+               # ring kernel (>= 96 tiles of 256 x 256, K % 128 == 0), full and ragged edges, one and many steps
+               (2560, 2560, 256), (2500, 2700, 384), (2560, 2560, 128), (3000, 2304, 1152),
+               # four-stage 256 x 256 x 64 kernel: K % 128 == 64, and split along K (wide, few tiles, long K)
+               (2560, 2560, 192), (1024, 1024, 4160), (768, 1536, 6336),
+               # 128-tile direct-to-LDS kernels: K % 128 == 0 (8 waves) and K % 128 == 64 (4 waves), 1..5 steps
+               (300, 200, 256), (300, 200, 192), (260, 130, 64), (129, 257, 640), (640, 128, 320)]
 
 
 @pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
@@ -186,7 +192,8 @@ def test_unmap_all_exponent_ranges(fxp):
     assert same_bits(host(fxp.unmap_i8(dev(q), dev(np.array([3], np.int32)))), oracle.unmap_i8(q, 3))
 
 
-@pytest.mark.parametrize("M,N,K", [(300, 200, 160), (128, 128, 4096), (512, 768, 256), (1024, 1280, 64)])
+@pytest.mark.parametrize("M,N,K", [(300, 200, 160), (128, 128, 4096), (512, 768, 256), (1024, 1280, 64),
+                                   (2560, 2560, 256), (2560, 2600, 192), (1024, 1024, 4160), (100, 90, 50)])
 def test_gemm_unmap_fused(fxp, M, N, K):
     rng = np.random.default_rng(M + N + K)
     A, B = rand_i8(rng, (M, K)), rand_i8(rng, (N, K))
