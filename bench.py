@@ -35,6 +35,8 @@ def parse_args():
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--sigma", type=float, default=1.0, help="c5 only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a 256 MiB elementwise copy (for scaling rocprofv3 byte counters)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
 
@@ -42,8 +44,8 @@ def parse_args():
 def read_traffic(workload, kernel_class):
     """HBM bytes per launch from the committed rocprofv3 --pmc summary, or None.
 
-    File format (profiles/pmc_<workload>.txt): lines `traffic_bytes_per_launch <class> <bytes>`."""
-    path = os.path.join(ROOT, "profiles", f"pmc_{workload}.txt")
+    File format (profiles/layer_step_<workload>.txt): lines `traffic_bytes_per_launch <row> <bytes>`."""
+    path = os.path.join(ROOT, "profiles", f"layer_step_{workload}.txt")
     try:
         with open(path) as f:
             for line in f:
@@ -116,9 +118,15 @@ def main():
         e1.synchronize()
         return e0.elapsed_time(e1) * 1e-3 / reps     # seconds per launch
 
-    classes = {"scale": dict(t=0.0, launches=0, bytes=0.0, ops=0.0), "map": dict(t=0.0, launches=0, bytes=0.0, ops=0.0),
-               "gemm": dict(t=0.0, launches=0, bytes=0.0, ops=0.0)}
+    rows = {}   # kernel row -> totals over one step
+
+    def add(row, kernel, dt, nbytes, ops=0.0):
+        r = rows.setdefault(row, dict(kernel=kernel, t=0.0, launches=0, bytes=0.0, ops=0.0))
+        r["t"] += dt; r["launches"] += 1; r["bytes"] += nbytes; r["ops"] += ops
+
     gemm_rows = []
+    lib, p = fxp.lib(), (lambda z: z.data_ptr())
+    st = torch.cuda.current_stream().cuda_stream
     for layer, (X, W, dY), buf in zip(layers, dev_inputs, bufs):
         M, K, N = layer.M, layer.K, layer.N
         ws = torch.empty(max(256, fxp.workspace_bytes(fxp.OP_SCALE, 0)), dtype=torch.uint8, device=dev)
@@ -126,19 +134,16 @@ def main():
             n = t.numel()
             q = torch.empty(t.shape, dtype=torch.int8, device=dev)
             qT = torch.empty((t.shape[1], t.shape[0]), dtype=torch.int8, device=dev)
-            lib, p = fxp.lib(), (lambda z: z.data_ptr())
-            st = torch.cuda.current_stream().cuda_stream
-            dt = timed(lambda: lib.fxp_scale(p(t), n, p(e), p(ws), ws.numel(), st))
-            c = classes["scale"]; c["t"] += dt; c["launches"] += 1; c["bytes"] += 4.0 * n
-            dt = timed(lambda: lib.fxp_map(p(t), t.shape[0], t.shape[1], p(e), p(q), p(qT), seed, 0, 0, 8, st))
-            c = classes["map"]; c["t"] += dt; c["launches"] += 1; c["bytes"] += 6.0 * n
+            # scale: 4 B read per element (k_absmax_partials; the finishing block is negligible)
+            add("scale", "k_absmax_partials", timed(lambda: lib.fxp_scale(p(t), n, p(e), p(ws), ws.numel(), st)), 4.0 * n)
+            # map: 4 B read + 1 B written per copy (both orientations) per element
+            add("map", "k_map_tile<true>",
+                timed(lambda: lib.fxp_map(p(t), t.shape[0], t.shape[1], p(e), p(q), p(qT), seed, 0, 0, 8, st)), 6.0 * n)
             del q, qT
         gemms = [("fwd", M, N, K, buf.Xq, buf.WqT, buf.eX, buf.eW, buf.Y),
                  ("dX", M, K, N, buf.dYq, buf.Wq, buf.e_dY, buf.eW, buf.dX),
                  ("dW", K, N, M, buf.XqT, buf.dYqT, buf.eX, buf.e_dY, buf.dW)]
         for name, gm, gn, gk, A, B, eA, eB, C in gemms:
-            lib, p = fxp.lib(), (lambda z: z.data_ptr())
-            st = torch.cuda.current_stream().cuda_stream
             dt = timed(lambda: lib.fxp_gemm_unmap(0, 1, gm, gn, gk, p(A), gk, p(B), gk, p(eA), 8, p(eB), 8, p(C), gn,
                                                   None, 0, st))
             ops, nbytes = 2.0 * gm * gn * gk, float(gm * gk + gn * gk + 4 * gm * gn)
@@ -147,12 +152,12 @@ def main():
                                   tops=round(ops / dt / 1e12, 1), gbs=round(nbytes / dt / 1e9, 1),
                                   bound="mfma" if ops / nbytes > RIDGE_OPS_PER_BYTE else "hbm",
                                   frac_of_roofline=round(t_roof / dt, 3)))
-            c = classes["gemm"]; c["t"] += dt; c["launches"] += 1; c["bytes"] += nbytes; c["ops"] += ops
+            add("gemm_" + name, "k_gemm_nt*", dt, nbytes, ops)
 
-    dominant = max(classes, key=lambda k: classes[k]["t"])
-    c = classes[dominant]
+    dominant = max(rows, key=lambda k: rows[k]["t"])
+    c = rows[dominant]
     avg_launch = c["t"] / c["launches"]
-    if dominant == "gemm" and c["ops"] / c["bytes"] > RIDGE_OPS_PER_BYTE:
+    if c["ops"] and c["ops"] / c["bytes"] > RIDGE_OPS_PER_BYTE:
         achieved = c["ops"] / c["t"] / 1e12
         roofline = dict(bound="mfma", achieved=round(achieved, 2), peak=PEAK_INT8_TOPS, unit="TOP/s",
                         frac=round(achieved / PEAK_INT8_TOPS, 4))
@@ -160,15 +165,21 @@ def main():
         achieved = c["bytes"] / c["t"] / 1e9
         roofline = dict(bound="hbm", achieved=round(achieved, 1), peak=PEAK_HBM_GBS, unit="GB/s",
                         frac=round(achieved / PEAK_HBM_GBS, 4))
-    kernel_names = {"scale": "k_absmax_partials", "map": "k_map_tile<true>", "gemm": "k_gemm_nt"}
-    traffic = read_traffic(args.workload, dominant)
-    roofline.update(kernel=kernel_names[dominant], launches_per_step=c["launches"],
+    roofline.update(kernel=c["kernel"], row=dominant, launches_per_step=c["launches"],
                     avg_launch_us=round(avg_launch * 1e6, 2),
                     algorithmic_per_launch=(c["ops"] if roofline["bound"] == "mfma" else c["bytes"]) / c["launches"],
-                    traffic=traffic)
-    kernels = {k: dict(launches_per_step=v["launches"], us_per_step=round(v["t"] * 1e6, 2),
+                    traffic=read_traffic(args.workload, dominant))
+    kernels = {k: dict(kernel=v["kernel"], launches_per_step=v["launches"], us_per_step=round(v["t"] * 1e6, 2),
                        gbs=round(v["bytes"] / v["t"] / 1e9, 1),
-                       tops=(round(v["ops"] / v["t"] / 1e12, 1) if v["ops"] else None)) for k, v in classes.items()}
+                       tops=(round(v["ops"] / v["t"] / 1e12, 1) if v["ops"] else None)) for k, v in rows.items()}
+
+    if args.copy_calibration:
+        # a plain elementwise copy of known size for scaling the FETCH_SIZE / WRITE_SIZE counters
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)      # 256 MiB read, 256 MiB written
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
 
     # ------------------------------------------------------------------ CPU oracle on a bounded sample
     cpu = None

@@ -56,5 +56,18 @@ def build(force=True):
     return LIB
 
 
+def build_ceilings():
+    """Standalone hardware-ceiling microbenchmark (not part of libfxp.so)."""
+    src = os.path.join(HERE, "ceilings", "fxp_ceilings.hip")
+    exe = os.path.join(HERE, "ceilings", "fxp_ceilings")
+    res = subprocess.run([HIPCC, *[f for f in FLAGS if f != "-fPIC"], src, "-o", exe], capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed on fxp_ceilings.hip:\n" + res.stderr)
+    return exe
+
+
 if __name__ == "__main__":
-    print(build(force="--if-stale" not in sys.argv))
+    if "--ceilings" in sys.argv:
+        print(build_ceilings())
+    else:
+        print(build(force="--if-stale" not in sys.argv))

@@ -1,0 +1,170 @@
+// fxp_ceilings — what one MI355X actually delivers on the three resources the
+// integer layer step is bound by, measured with the simplest kernels that can saturate
+// them.  The benchmark's roofline fractions use the published peaks; these numbers say
+// how much of a published peak is reachable at all on a given box.
+//   1. HBM: streaming read (16-byte loads) and copy, buffers inside and beyond the
+//      256 MB Infinity Cache.
+//   2. int8 MFMA: v_mfma_i32_32x32x32_i8 from registers only, eight independent
+//      accumulators per wave, two waves per SIMD.
+//   3. L2 -> LDS: global_load_lds_dwordx4 in the GEMM loader's pattern (rows 8 KiB
+//      apart, 64- or 128-byte pieces per row), L2-resident panels.
+// Build: python -m paper_2207_08822_amd.build --ceilings ; run: paper_2207_08822_amd/ceilings/fxp_ceilings
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdio>
+
+#define CK(x)                                                                        \
+    do {                                                                             \
+        hipError_t err_ = (x);                                                       \
+        if (err_ != hipSuccess) {                                                    \
+            printf("HIP error %s at line %d\n", hipGetErrorString(err_), __LINE__);  \
+            return 1;                                                                \
+        }                                                                            \
+    } while (0)
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+__global__ __launch_bounds__(256) void k_read(const uint4* __restrict__ x, size_t nvec, uint32_t* out) {
+    size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;
+    const size_t stride = static_cast<size_t>(gridDim.x) * 256;
+    uint32_t m = 0;
+    for (; i + 3 * stride < nvec; i += 4 * stride) {
+        const uint4 a = x[i], b = x[i + stride], c = x[i + 2 * stride], d = x[i + 3 * stride];
+        m = max(m, max(max(a.x, a.y), max(a.z, a.w)));
+        m = max(m, max(max(b.x, b.y), max(b.z, b.w)));
+        m = max(m, max(max(c.x, c.y), max(c.z, c.w)));
+        m = max(m, max(max(d.x, d.y), max(d.z, d.w)));
+    }
+    for (; i < nvec; i += stride) {
+        const uint4 a = x[i];
+        m = max(m, max(max(a.x, a.y), max(a.z, a.w)));
+    }
+    if (m == 0x12345678u) out[0] = m;
+}
+
+__global__ __launch_bounds__(256) void k_copy(const uint4* __restrict__ x, uint4* __restrict__ y, size_t nvec) {
+    const size_t stride = static_cast<size_t>(gridDim.x) * 256;
+    for (size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x; i < nvec; i += stride) y[i] = x[i];
+}
+
+__global__ __launch_bounds__(256) void k_mfma(int* out, int iters, int seed) {
+    const v4i a = {seed + static_cast<int>(threadIdx.x), seed * 3, seed * 5, seed * 7};
+    const v4i b = {seed * 11, seed * 13, static_cast<int>(threadIdx.x), seed};
+    v16i acc[8];
+    for (int n = 0; n < 8; ++n)
+        for (int r = 0; r < 16; ++r) acc[n][r] = 0;
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int n = 0; n < 8; ++n) acc[n] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[n], 0, 0, 0);
+    }
+    int s = 0;
+    for (int n = 0; n < 8; ++n)
+        for (int r = 0; r < 16; ++r) s += acc[n][r];
+    if (s == 0x7fffffff) out[0] = s;
+}
+
+// every block walks a panel of `rows` rows x K bytes (row stride ld), BK bytes per row per step;
+// blocks of one XCD share panels so that L2 serves most requests
+template <int BK>
+__global__ __launch_bounds__(256) void k_panel(const char* __restrict__ x, size_t ld, int K, int rows, int npanels,
+                                               int reps, uint32_t* out) {
+    __shared__ __attribute__((aligned(1024))) char lds[8 * 4096];
+    constexpr int CPR = BK / 16, RROWS = 64 / CPR;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const char* panel = x + static_cast<size_t>((blockIdx.x / 8) % npanels) * rows * ld;
+    const int nreg = rows / RROWS, r_in = lane / CPR, piece = lane % CPR;
+    int slot = 0;
+    for (int rep = 0; rep < reps; ++rep)
+        for (int k = 0; k < K; k += BK)
+            for (int g = wave; g < nreg; g += 4) {
+                const char* p = panel + static_cast<size_t>(g * RROWS + r_in) * ld + k + piece * 16;
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p,
+                                                 (__attribute__((address_space(3))) void*)(lds + (slot % 8) * 4096 + wave * 1024),
+                                                 16, 0, 0);
+                ++slot;
+            }
+    __builtin_amdgcn_s_waitcnt(0x0070);
+    __syncthreads();
+    if (lds[threadIdx.x] == 0x7f && reps < 0) out[0] = 1;
+}
+
+int main() {
+    hipDeviceProp_t prop;
+    CK(hipGetDeviceProperties(&prop, 0));
+    printf("device: %d CUs, %d kHz, L2 %d bytes, LDS per block %zu bytes\n", prop.multiProcessorCount, prop.clockRate,
+           prop.l2CacheSize, prop.sharedMemPerBlock);
+    hipEvent_t e0, e1;
+    CK(hipEventCreate(&e0));
+    CK(hipEventCreate(&e1));
+    float ms;
+    uint32_t* out;
+    CK(hipMalloc(&out, 4096));
+
+    for (size_t mb : {64, 256, 1024, 4096}) {
+        const size_t bytes = mb << 20, nvec = bytes / 16;
+        uint4 *x, *y;
+        CK(hipMalloc(&x, bytes));
+        CK(hipMalloc(&y, bytes));
+        CK(hipMemset(x, 1, bytes));
+        CK(hipMemset(y, 0, bytes));
+        k_read<<<16384, 256>>>(x, nvec, out);
+        CK(hipDeviceSynchronize());
+        CK(hipEventRecord(e0));
+        for (int r = 0; r < 10; ++r) k_read<<<16384, 256>>>(x, nvec, out);
+        CK(hipEventRecord(e1));
+        CK(hipEventSynchronize(e1));
+        CK(hipEventElapsedTime(&ms, e0, e1));
+        printf("hbm read  %5zu MiB: %7.1f GB/s\n", mb, bytes * 10.0 / (ms * 1e-3) / 1e9);
+        const int grid = static_cast<int>(nvec / 256 > 262144 ? 262144 : nvec / 256);
+        k_copy<<<grid, 256>>>(x, y, nvec);
+        CK(hipDeviceSynchronize());
+        CK(hipEventRecord(e0));
+        for (int r = 0; r < 10; ++r) k_copy<<<grid, 256>>>(x, y, nvec);
+        CK(hipEventRecord(e1));
+        CK(hipEventSynchronize(e1));
+        CK(hipEventElapsedTime(&ms, e0, e1));
+        printf("hbm copy  %5zu MiB: %7.1f GB/s (read + write)\n", mb, 2.0 * bytes * 10 / (ms * 1e-3) / 1e9);
+        CK(hipFree(x));
+        CK(hipFree(y));
+    }
+
+    const int iters = 20000;
+    k_mfma<<<512, 256>>>(reinterpret_cast<int*>(out), 100, 1);
+    CK(hipDeviceSynchronize());
+    CK(hipEventRecord(e0));
+    for (int r = 0; r < 20; ++r) k_mfma<<<512, 256>>>(reinterpret_cast<int*>(out), iters, 1);
+    CK(hipEventRecord(e1));
+    CK(hipEventSynchronize(e1));
+    CK(hipEventElapsedTime(&ms, e0, e1));
+    printf("int8 mfma 32x32x32 from registers, 2 waves/SIMD, %.0f ms: %7.1f TOP/s\n", ms,
+           20.0 * 512 * 4 * iters * 8 * 65536.0 / (ms * 1e-3) / 1e12);
+
+    {
+        const size_t ld = 8192;
+        const int K = 8192, rows = 512, npanels = 4, reps = 4;
+        char* x;
+        CK(hipMalloc(&x, static_cast<size_t>(npanels) * rows * ld));
+        CK(hipMemset(x, 1, static_cast<size_t>(npanels) * rows * ld));
+        const double bytes = 256.0 * rows * K * reps;
+        k_panel<128><<<256, 256>>>(x, ld, K, rows, npanels, 1, out);
+        CK(hipDeviceSynchronize());
+        CK(hipEventRecord(e0));
+        k_panel<128><<<256, 256>>>(x, ld, K, rows, npanels, reps, out);
+        CK(hipEventRecord(e1));
+        CK(hipEventSynchronize(e1));
+        CK(hipEventElapsedTime(&ms, e0, e1));
+        printf("L2 -> LDS, 128-byte row pieces: %6.2f TB/s (%5.1f GB/s per CU)\n", bytes / (ms * 1e-3) / 1e12,
+               bytes / (ms * 1e-3) / 1e9 / 256);
+        CK(hipEventRecord(e0));
+        k_panel<64><<<256, 256>>>(x, ld, K, rows, npanels, reps, out);
+        CK(hipEventRecord(e1));
+        CK(hipEventSynchronize(e1));
+        CK(hipEventElapsedTime(&ms, e0, e1));
+        printf("L2 -> LDS,  64-byte row pieces: %6.2f TB/s (%5.1f GB/s per CU)\n", bytes / (ms * 1e-3) / 1e12,
+               bytes / (ms * 1e-3) / 1e9 / 256);
+        CK(hipFree(x));
+    }
+    return 0;
+}
