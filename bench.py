@@ -144,8 +144,10 @@ def main():
                  ("dX", M, K, N, buf.dYq, buf.Wq, buf.e_dY, buf.eW, buf.dX),
                  ("dW", K, N, M, buf.XqT, buf.dYqT, buf.eX, buf.e_dY, buf.dW)]
         for name, gm, gn, gk, A, B, eA, eB, C in gemms:
+            gws = torch.empty(max(256, fxp.workspace_bytes(fxp.OP_GEMM, gm, gn, gk)), dtype=torch.uint8, device=dev)
             dt = timed(lambda: lib.fxp_gemm_unmap(0, 1, gm, gn, gk, p(A), gk, p(B), gk, p(eA), 8, p(eB), 8, p(C), gn,
-                                                  None, 0, st))
+                                                  p(gws), gws.numel(), st))
+            del gws
             ops, nbytes = 2.0 * gm * gn * gk, float(gm * gk + gn * gk + 4 * gm * gn)
             t_roof = max(ops / (PEAK_INT8_TOPS * 1e12), nbytes / (PEAK_HBM_GBS * 1e9))
             gemm_rows.append(dict(layer=layer.name, gemm=name, M=gm, N=gn, K=gk, us=round(dt * 1e6, 2),

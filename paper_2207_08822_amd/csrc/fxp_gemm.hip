@@ -60,7 +60,7 @@ template <int BM, int BN, int BK, int WM, int WN, bool VEC, int MODE>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm_nt(
     const int8_t* __restrict__ A, int64_t lda, const int8_t* __restrict__ B, int64_t ldb, void* __restrict__ Cv,
     int64_t ldc, int M, int N, int K, int k_per_split, const int32_t* __restrict__ eA, int bitsA,
-    const int32_t* __restrict__ eB, int bitsB, int tiles_m, int tiles_n, int group_m) {
+    const int32_t* __restrict__ eB, int bitsB, int tiles_m, int tiles_n, int group_m, int64_t split_stride) {
     constexpr int NT = (BM / WM) * (BN / WN) * 64;
     constexpr int CPR = BK / 16;
     constexpr int NA = BM * CPR / NT, NB = BN * CPR / NT;   // 16-byte pieces per thread per step
@@ -73,6 +73,8 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm_nt(
     tile_of_block(blockIdx.x, tiles_m, tiles_n, group_m, &tm, &tn);
     const int m0 = tm * BM, n0 = tn * BN;
     const int kb = blockIdx.y * k_per_split;
+    // split-K into a workspace: slice y owns its own M x N int32 matrix (split_stride elements apart)
+    Cv = static_cast<int32_t*>(Cv) + static_cast<int64_t>(blockIdx.y) * split_stride;
     const int ke = min(K, kb + k_per_split);
     const int nk = (ke - kb + BK - 1) / BK;
 
@@ -210,7 +212,7 @@ template <int BM, int BN, int BK, int WM, int WN, int STAGES, int MODE, bool SCH
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm_nt_dma(
     const int8_t* __restrict__ A, int64_t lda, const int8_t* __restrict__ B, int64_t ldb, void* __restrict__ Cv,
     int64_t ldc, int M, int N, int K, int k_per_split, const int32_t* __restrict__ eA, int bitsA,
-    const int32_t* __restrict__ eB, int bitsB, int tiles_m, int tiles_n, int group_m) {
+    const int32_t* __restrict__ eB, int bitsB, int tiles_m, int tiles_n, int group_m, int64_t split_stride) {
     constexpr int NW = (BM / WM) * (BN / WN);
     constexpr int CPR = BK / 16;                     // 16-byte pieces per LDS row
     constexpr int RROWS = 64 / CPR;                  // tile rows per 1 KiB region
@@ -230,6 +232,8 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm_nt_dma(
     tile_of_block(blockIdx.x, tiles_m, tiles_n, group_m, &tm, &tn);
     const int m0 = tm * BM, n0 = tn * BN;
     const int kb = blockIdx.y * k_per_split;
+    // split-K into a workspace: slice y owns its own M x N int32 matrix (split_stride elements apart)
+    Cv = static_cast<int32_t*>(Cv) + static_cast<int64_t>(blockIdx.y) * split_stride;
     const int ke = min(K, kb + k_per_split);
     const int nk = (ke - kb) / BK;
 
@@ -390,7 +394,7 @@ template <int WM, int WN, int MODE, bool SCHED>
 __global__ __launch_bounds__((256 / WM) * (256 / WN) * 64) void k_gemm_nt_ring(
     const int8_t* __restrict__ A, int64_t lda, const int8_t* __restrict__ B, int64_t ldb, void* __restrict__ Cv,
     int64_t ldc, int M, int N, int K, int k_per_split, const int32_t* __restrict__ eA, int bitsA,
-    const int32_t* __restrict__ eB, int bitsB, int tiles_m, int tiles_n, int group_m) {
+    const int32_t* __restrict__ eB, int bitsB, int tiles_m, int tiles_n, int group_m, int64_t split_stride) {
     constexpr int BM = 256, BN = 256, BK = 128;
     constexpr int NW = (BM / WM) * (BN / WN);
     constexpr int SLOT = 256 * BK;                   // bytes of a half-stage
@@ -404,6 +408,8 @@ __global__ __launch_bounds__((256 / WM) * (256 / WN) * 64) void k_gemm_nt_ring(
     tile_of_block(blockIdx.x, tiles_m, tiles_n, group_m, &tm, &tn);
     const int m0 = tm * BM, n0 = tn * BN;
     const int kb = blockIdx.y * k_per_split;
+    // split-K into a workspace: slice y owns its own M x N int32 matrix (split_stride elements apart)
+    Cv = static_cast<int32_t*>(Cv) + static_cast<int64_t>(blockIdx.y) * split_stride;
     const int ke = min(K, kb + k_per_split);
     const int nk = (ke - kb) / BK;
 
@@ -556,21 +562,52 @@ __global__ __launch_bounds__((256 / WM) * (256 / WN) * 64) void k_gemm_nt_ring(
     }
 }
 
-__global__ __launch_bounds__(256) void k_zero_rows(int32_t* __restrict__ C, int64_t ldc, int M, int N) {
-    const int64_t total = static_cast<int64_t>(M) * N;
-    for (int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; i < total; i += static_cast<int64_t>(gridDim.x) * 256)
-        C[(i / N) * ldc + (i % N)] = 0;
+// split-K helpers over an M x N int32 / fp32 matrix with leading dimension ldc; grid.y walks
+// rows when ldc != N, otherwise the matrix is one flat run (16-byte accesses when aligned)
+__global__ __launch_bounds__(256) void k_zero_rows(int32_t* __restrict__ C, int64_t ldc, int rows, int cols) {
+    for (int r = blockIdx.y; r < rows; r += gridDim.y) {
+        int32_t* row = C + static_cast<int64_t>(r) * ldc;
+        const bool vec = (reinterpret_cast<uintptr_t>(row) & 15u) == 0;
+        const int nvec = vec ? cols >> 2 : 0;
+        for (int i = blockIdx.x * 256 + threadIdx.x; i < nvec; i += gridDim.x * 256)
+            reinterpret_cast<int4*>(row)[i] = make_int4(0, 0, 0, 0);
+        for (int i = (nvec << 2) + blockIdx.x * 256 + threadIdx.x; i < cols; i += gridDim.x * 256) row[i] = 0;
+    }
 }
 
-__global__ __launch_bounds__(256) void k_unmap_rows(int32_t* __restrict__ C, int64_t ldc, int M, int N,
+__global__ __launch_bounds__(256) void k_unmap_rows(int32_t* __restrict__ C, int64_t ldc, int rows, int cols,
                                                     const int32_t* __restrict__ eA, int bitsA,
                                                     const int32_t* __restrict__ eB, int bitsB) {
     const int E = lsb_exponent(eA[0], bitsA) + (eB ? lsb_exponent(eB[0], bitsB) : 0);
-    const int64_t total = static_cast<int64_t>(M) * N;
-    for (int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; i < total; i += static_cast<int64_t>(gridDim.x) * 256) {
-        int32_t* p = C + (i / N) * ldc + (i % N);
-        *reinterpret_cast<float*>(p) = unmap_value(*p, E);
+    for (int r = blockIdx.y; r < rows; r += gridDim.y) {
+        int32_t* row = C + static_cast<int64_t>(r) * ldc;
+        const bool vec = (reinterpret_cast<uintptr_t>(row) & 15u) == 0;
+        const int nvec = vec ? cols >> 2 : 0;
+        for (int i = blockIdx.x * 256 + threadIdx.x; i < nvec; i += gridDim.x * 256) {
+            const int4 a = reinterpret_cast<const int4*>(row)[i];
+            float4 o;
+            o.x = unmap_value(a.x, E);
+            o.y = unmap_value(a.y, E);
+            o.z = unmap_value(a.z, E);
+            o.w = unmap_value(a.w, E);
+            reinterpret_cast<float4*>(row)[i] = o;
+        }
+        for (int i = (nvec << 2) + blockIdx.x * 256 + threadIdx.x; i < cols; i += gridDim.x * 256)
+            reinterpret_cast<float*>(row)[i] = unmap_value(row[i], E);
     }
+}
+
+// launch shape of the two helpers: a dense matrix is treated as one long row
+static void rows_launch_shape(int64_t M, int64_t N, int64_t ldc, int* rows, int* cols, dim3* grid) {
+    if (ldc == N && M * N < (int64_t{1} << 31)) {
+        *rows = 1;
+        *cols = static_cast<int>(M * N);
+    } else {
+        *rows = static_cast<int>(M);
+        *cols = static_cast<int>(N);
+    }
+    const int gx = std::max(1, std::min(1024, (*cols / 4 + 255) / 256));
+    *grid = dim3(gx, std::max(1, std::min(*rows, 65535)));
 }
 
 // int8 [rows, cols] (leading dimension ld) -> [cols, rows] contiguous, 64 x 64 tiles through LDS
@@ -601,19 +638,20 @@ int transpose_i8_launch(const int8_t* src, int64_t rows, int64_t cols, int64_t l
 template <int BM, int BN, int BK, int WM, int WN>
 static int launch_cfg(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                       void* C, int64_t ldc, int mode, bool vec, int splits, const int32_t* eA, int bitsA,
-                      const int32_t* eB, int bitsB, hipStream_t s) {
+                      const int32_t* eB, int bitsB, hipStream_t s, int64_t split_stride = 0, int* slices = nullptr) {
     constexpr int NT = (BM / WM) * (BN / WN) * 64;
     const int tiles_m = static_cast<int>((M + BM - 1) / BM), tiles_n = static_cast<int>((N + BN - 1) / BN);
     int k_per_split = static_cast<int>((K + splits - 1) / splits);
     k_per_split = (k_per_split + BK - 1) / BK * BK;
     if (k_per_split == 0) k_per_split = BK;
     const int ny = K > 0 ? static_cast<int>((K + k_per_split - 1) / k_per_split) : 1;
+    if (slices) *slices = ny;
     const dim3 grid(static_cast<unsigned>(tiles_m) * tiles_n, ny), block(NT);
     const int group_m = 8;
 #define FXP_GEMM_LAUNCH(VEC, MODE)                                                                                 \
     hipLaunchKernelGGL((k_gemm_nt<BM, BN, BK, WM, WN, VEC, MODE>), grid, block, 0, s, A, lda, B, ldb, C, ldc,       \
                        static_cast<int>(M), static_cast<int>(N), static_cast<int>(K), k_per_split, eA, bitsA, eB,   \
-                       bitsB, tiles_m, tiles_n, group_m)
+                       bitsB, tiles_m, tiles_n, group_m, split_stride)
     if (vec) {
         if (mode == kStoreI32) FXP_GEMM_LAUNCH(true, kStoreI32);
         else if (mode == kStoreF32) FXP_GEMM_LAUNCH(true, kStoreF32);
@@ -630,18 +668,19 @@ static int launch_cfg(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t 
 template <int WM, int WN, bool SCHED = true>
 static int launch_ring(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                        void* C, int64_t ldc, int mode, int splits, const int32_t* eA, int bitsA, const int32_t* eB,
-                       int bitsB, hipStream_t s) {
+                       int bitsB, hipStream_t s, int64_t split_stride = 0, int* slices = nullptr) {
     constexpr int NT = (256 / WM) * (256 / WN) * 64, BK = 128;
     const int tiles_m = static_cast<int>((M + 255) / 256), tiles_n = static_cast<int>((N + 255) / 256);
     int k_per_split = static_cast<int>((K + splits - 1) / splits);
     k_per_split = (k_per_split + BK - 1) / BK * BK;
     const int ny = static_cast<int>((K + k_per_split - 1) / k_per_split);
+    if (slices) *slices = ny;
     const dim3 grid(static_cast<unsigned>(tiles_m) * tiles_n, ny), block(NT);
     const int group_m = 8;
 #define FXP_GEMM_LAUNCH(MODE)                                                                                    \
     hipLaunchKernelGGL((k_gemm_nt_ring<WM, WN, MODE, SCHED>), grid, block, 0, s, A, lda, B, ldb, C, ldc,          \
                        static_cast<int>(M), static_cast<int>(N), static_cast<int>(K), k_per_split, eA, bitsA, eB, \
-                       bitsB, tiles_m, tiles_n, group_m)
+                       bitsB, tiles_m, tiles_n, group_m, split_stride)
     if (mode == kStoreI32) FXP_GEMM_LAUNCH(kStoreI32);
     else if (mode == kStoreF32) FXP_GEMM_LAUNCH(kStoreF32);
     else FXP_GEMM_LAUNCH(kAtomicI32);
@@ -652,24 +691,90 @@ static int launch_ring(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t
 template <int BM, int BN, int BK, int WM, int WN, int STAGES, bool SCHED = true>
 static int launch_dma(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                       void* C, int64_t ldc, int mode, int splits, const int32_t* eA, int bitsA, const int32_t* eB,
-                      int bitsB, hipStream_t s) {
+                      int bitsB, hipStream_t s, int64_t split_stride = 0, int* slices = nullptr) {
     constexpr int NT = (BM / WM) * (BN / WN) * 64;
     const int tiles_m = static_cast<int>((M + BM - 1) / BM), tiles_n = static_cast<int>((N + BN - 1) / BN);
     int k_per_split = static_cast<int>((K + splits - 1) / splits);
     k_per_split = (k_per_split + BK - 1) / BK * BK;
     const int ny = static_cast<int>((K + k_per_split - 1) / k_per_split);
+    if (slices) *slices = ny;
     const dim3 grid(static_cast<unsigned>(tiles_m) * tiles_n, ny), block(NT);
     const int group_m = 8;
 #define FXP_GEMM_LAUNCH(MODE)                                                                                      \
     hipLaunchKernelGGL((k_gemm_nt_dma<BM, BN, BK, WM, WN, STAGES, MODE, SCHED>), grid, block, 0, s, A, lda, B, ldb, C, \
                        ldc,                                                                                        \
                        static_cast<int>(M), static_cast<int>(N), static_cast<int>(K), k_per_split, eA, bitsA, eB,   \
-                       bitsB, tiles_m, tiles_n, group_m)
+                       bitsB, tiles_m, tiles_n, group_m, split_stride)
     if (mode == kStoreI32) FXP_GEMM_LAUNCH(kStoreI32);
     else if (mode == kStoreF32) FXP_GEMM_LAUNCH(kStoreF32);
     else FXP_GEMM_LAUNCH(kAtomicI32);
 #undef FXP_GEMM_LAUNCH
     return launch_status();
+}
+
+// sum of the split-K slices (int32, exact in any order) -> int32 or inverse-mapped fp32
+__global__ __launch_bounds__(256) void k_splitk_reduce(const int32_t* __restrict__ parts, int splits, int64_t stride,
+                                                       int M, int N, void* __restrict__ Cv, int64_t ldc, int fp32_out,
+                                                       const int32_t* __restrict__ eA, int bitsA,
+                                                       const int32_t* __restrict__ eB, int bitsB) {
+    int E = 0;
+    if (fp32_out) E = lsb_exponent(eA[0], bitsA) + (eB ? lsb_exponent(eB[0], bitsB) : 0);
+    const int nvec = N >> 2;                      // the slices are dense M x N: rows start 16-byte aligned when N % 4 == 0
+    const bool vec = (N & 3) == 0 && (ldc & 3) == 0 && (reinterpret_cast<uintptr_t>(Cv) & 15u) == 0;
+    for (int r = blockIdx.y; r < M; r += gridDim.y) {
+        const int32_t* prow = parts + static_cast<int64_t>(r) * N;
+        int32_t* crow = static_cast<int32_t*>(Cv) + static_cast<int64_t>(r) * ldc;
+        if (vec) {
+            for (int i = blockIdx.x * 256 + threadIdx.x; i < nvec; i += gridDim.x * 256) {
+                int4 acc = make_int4(0, 0, 0, 0);
+                for (int sidx = 0; sidx < splits; ++sidx) {
+                    const int4 v = reinterpret_cast<const int4*>(prow + sidx * stride)[i];
+                    acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+                }
+                if (fp32_out) {
+                    float4 o;
+                    o.x = unmap_value(acc.x, E); o.y = unmap_value(acc.y, E);
+                    o.z = unmap_value(acc.z, E); o.w = unmap_value(acc.w, E);
+                    reinterpret_cast<float4*>(crow)[i] = o;
+                } else {
+                    reinterpret_cast<int4*>(crow)[i] = acc;
+                }
+            }
+        } else {
+            for (int i = blockIdx.x * 256 + threadIdx.x; i < N; i += gridDim.x * 256) {
+                int acc = 0;
+                for (int sidx = 0; sidx < splits; ++sidx) acc += prow[sidx * stride + i];
+                if (fp32_out) reinterpret_cast<float*>(crow)[i] = unmap_value(acc, E);
+                else crow[i] = acc;
+            }
+        }
+    }
+}
+
+// How a product is cut up.  Depends on the shape only, so that workspace sizing and launch agree.
+struct GemmPlan {
+    bool use256;   // 256 x 256 tiles, else 128 x 128
+    int splits;    // slices of the contraction (grid.y)
+};
+
+static GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K) {
+    const int num_cu = 256;
+    const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
+    const int64_t t128 = ((M + 127) / 128) * ((N + 127) / 128);
+    const bool wide = M >= 256 && N >= 256;
+    GemmPlan p{wide && t256 >= 96, 1};
+    if (K >= 2048 && t256 < 64) {
+        // small output, long contraction (a weight gradient): fill the chip along K, slices of 1024 or more
+        p.use256 = wide && t256 >= 16;
+        const int64_t tiles = p.use256 ? t256 : t128;
+        p.splits = static_cast<int>(std::max<int64_t>(1, std::min<int64_t>((num_cu + tiles / 2) / tiles, K / 1024)));
+    }
+    return p;
+}
+
+size_t gemm_split_ws_bytes(int64_t M, int64_t N, int64_t K) {
+    const GemmPlan p = plan_gemm(M, N, K);
+    return p.splits > 1 ? round_up(static_cast<size_t>(p.splits) * M * N * sizeof(int32_t), 256) : 0;
 }
 
 // C = A[M,K] * B[N,K]^T.  fp32_out: C receives the inverse-mapped fp32 values (eA, eB on
@@ -679,50 +784,54 @@ static int launch_dma(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t 
 //   * operands 16-byte aligned and K a multiple of 64 -> direct-to-LDS kernels, else the
 //     register-staged 128 x 128 x 64 kernel with its element-wise loader;
 //   * enough 256 x 256 tiles to fill the chip -> the ring kernel (K % 128 == 0) or the
-//     four-stage 256 x 256 x 64 kernel;
-//   * long contraction and a small output (the weight gradient) -> split K over grid.y,
-//     int32 atomics into the zeroed output, then an in-place inverse mapping pass;
-//   * otherwise 128 x 128 tiles.
+//     four-stage 256 x 256 x 64 kernel; otherwise 128 x 128 tiles;
+//   * long contraction and a small output (the weight gradient) -> split K over grid.y.
+//     With workspace every slice stores its own int32 matrix and one pass sums the slices
+//     and applies the inverse mapping; without it the slices add into the zeroed output
+//     with int32 atomics (device-scope atomics are served at the memory side on this
+//     multi-die part, about 4x slower) and a pass converts in place.  Both are exact.
 int gemm_nt_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                    void* C, int64_t ldc, bool fp32_out, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB,
-                   hipStream_t s) {
+                   void* ws, size_t ws_bytes, hipStream_t s) {
     if (M == 0 || N == 0) return FXP_OK;
     const bool vec = aligned(A, 16) && aligned(B, 16) && lda % 16 == 0 && ldb % 16 == 0 && K % 16 == 0;
     const bool dma = vec && K > 0 && K % 64 == 0;
-    const int num_cu = 256;
-    const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
-    const int64_t t128 = ((M + 127) / 128) * ((N + 127) / 128);
-    const bool wide = M >= 256 && N >= 256;
-    int splits = 1;
-    bool use256 = wide && t256 >= 96;
-    if (K >= 2048 && t256 < 64) {
-        // small output, long contraction: fill the chip along K (each slice at least 512 long)
-        use256 = wide && t256 >= 16;
-        const int64_t tiles = use256 ? t256 : t128;
-        const int64_t target = use256 ? num_cu : 2 * num_cu;
-        splits = static_cast<int>(std::max<int64_t>(1, std::min<int64_t>((target + tiles / 2) / tiles, K / 512)));
-    }
-    const int first_mode = splits > 1 ? kAtomicI32 : (fp32_out ? kStoreF32 : kStoreI32);
-    const int zg = static_cast<int>(std::min<int64_t>((M * N + 255) / 256, 2048));
-    int rc;
-    if (splits > 1) {
-        hipLaunchKernelGGL(k_zero_rows, dim3(zg), dim3(256), 0, s, static_cast<int32_t*>(C), ldc, static_cast<int>(M),
-                           static_cast<int>(N));
+    const GemmPlan plan = plan_gemm(M, N, K);
+    const int splits = plan.splits;
+    const bool use256 = plan.use256;
+    const bool to_ws = splits > 1 && ws != nullptr && aligned(ws, 16) && ws_bytes >= gemm_split_ws_bytes(M, N, K);
+    const int first_mode = splits > 1 ? (to_ws ? kStoreI32 : kAtomicI32) : (fp32_out ? kStoreF32 : kStoreI32);
+    void* dst = to_ws ? ws : C;
+    const int64_t dst_ld = to_ws ? N : ldc;
+    const int64_t split_stride = to_ws ? M * N : 0;
+    int hr, hc;
+    dim3 hgrid;
+    rows_launch_shape(M, N, ldc, &hr, &hc, &hgrid);
+    int rc, slices = 1;   // the launchers round a slice up to whole K steps, so fewer slices than planned may run
+    if (splits > 1 && !to_ws) {
+        hipLaunchKernelGGL(k_zero_rows, hgrid, dim3(256), 0, s, static_cast<int32_t*>(C), ldc, hr, hc);
         if ((rc = launch_status())) return rc;
     }
     if (!dma)
-        rc = launch_cfg<128, 128, 64, 64, 64>(M, N, K, A, lda, B, ldb, C, ldc, first_mode, vec, splits, eA, bitsA, eB, bitsB, s);
+        rc = launch_cfg<128, 128, 64, 64, 64>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, vec, splits, eA, bitsA, eB, bitsB, s, split_stride, &slices);
     else if (use256 && K % 128 == 0 && splits == 1)
-        rc = launch_ring<64, 128>(M, N, K, A, lda, B, ldb, C, ldc, first_mode, 1, eA, bitsA, eB, bitsB, s);
+        rc = launch_ring<64, 128>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, 1, eA, bitsA, eB, bitsB, s);
     else if (use256)
-        rc = launch_dma<256, 256, 64, 64, 128, 4>(M, N, K, A, lda, B, ldb, C, ldc, first_mode, splits, eA, bitsA, eB, bitsB, s);
-    else if (K % 128 == 0 && splits == 1)
-        rc = launch_dma<128, 128, 128, 64, 32, 4>(M, N, K, A, lda, B, ldb, C, ldc, first_mode, 1, eA, bitsA, eB, bitsB, s);
+        rc = launch_dma<256, 256, 64, 64, 128, 4>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, splits, eA, bitsA, eB, bitsB, s, split_stride, &slices);
+    else if (K % 128 == 0)
+        rc = launch_dma<128, 128, 128, 64, 32, 4>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, splits, eA, bitsA, eB, bitsB, s, split_stride, &slices);
     else
-        rc = launch_dma<128, 128, 64, 64, 64, 4>(M, N, K, A, lda, B, ldb, C, ldc, first_mode, splits, eA, bitsA, eB, bitsB, s);
-    if (rc || splits == 1 || !fp32_out) return rc;
-    hipLaunchKernelGGL(k_unmap_rows, dim3(zg), dim3(256), 0, s, static_cast<int32_t*>(C), ldc, static_cast<int>(M),
-                       static_cast<int>(N), eA, bitsA, eB, bitsB);
+        rc = launch_dma<128, 128, 64, 64, 64, 4>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, splits, eA, bitsA, eB, bitsB, s, split_stride, &slices);
+    if (rc || splits == 1) return rc;
+    if (to_ws) {
+        const dim3 rgrid(std::max(1, std::min(64, static_cast<int>((N / 4 + 255) / 256))),
+                         static_cast<unsigned>(std::min<int64_t>(M, 65535)));
+        hipLaunchKernelGGL(k_splitk_reduce, rgrid, dim3(256), 0, s, static_cast<const int32_t*>(ws), slices, M * N,
+                           static_cast<int>(M), static_cast<int>(N), C, ldc, fp32_out ? 1 : 0, eA, bitsA, eB, bitsB);
+        return launch_status();
+    }
+    if (!fp32_out) return rc;
+    hipLaunchKernelGGL(k_unmap_rows, hgrid, dim3(256), 0, s, static_cast<int32_t*>(C), ldc, hr, hc, eA, bitsA, eB, bitsB);
     return launch_status();
 }
 
@@ -745,7 +854,7 @@ static size_t gemm_ws_bytes(int transA, int transB, int64_t M, int64_t N, int64_
     return b;
 }
 
-size_t gemm_ws_worst(int64_t M, int64_t N, int64_t K) { return gemm_ws_bytes(1, 0, M, N, K); }
+size_t gemm_ws_worst(int64_t M, int64_t N, int64_t K) { return gemm_ws_bytes(1, 0, M, N, K) + gemm_split_ws_bytes(M, N, K); }
 
 // Bring any operand form to the native one (transposed copies in ws), then run it.
 static int gemm_any(int transA, int transB, int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda,
@@ -754,7 +863,7 @@ static int gemm_any(int transA, int transB, int64_t M, int64_t N, int64_t K, con
     if (M == 0 || N == 0) return FXP_OK;
     const size_t need = gemm_ws_bytes(transA, transB, M, N, K);
     if (need > 0 && (!ws || ws_bytes < need)) return FXP_ERR_WORKSPACE;
-    if (need > 0 && !aligned(ws, 256)) return FXP_ERR_ALIGN;
+    if (ws && !aligned(ws, 256)) return FXP_ERR_ALIGN;
     int8_t* w = static_cast<int8_t*>(ws);
     int rc;
     if (transA && K > 0) {
@@ -767,8 +876,12 @@ static int gemm_any(int transA, int transB, int64_t M, int64_t N, int64_t K, con
         if ((rc = transpose_i8_launch(B, K, N, ldb, w, s))) return rc;      // stored [K, N] -> [N, K]
         B = w;
         ldb = K;
+        w += round_up(static_cast<size_t>(N) * static_cast<size_t>(K), 256);
     }
-    return gemm_nt_launch(M, N, K, A, lda, B, ldb, C, ldc, fp32_out, eA, bitsA, eB, bitsB, s);
+    // what is left of the workspace serves the split-K slices (atomics are used if it is too small)
+    const size_t used = static_cast<size_t>(w - static_cast<int8_t*>(ws));
+    return gemm_nt_launch(M, N, K, A, lda, B, ldb, C, ldc, fp32_out, eA, bitsA, eB, bitsB, ws ? w : nullptr,
+                          ws_bytes > used ? ws_bytes - used : 0, s);
 }
 
 }  // namespace fxp

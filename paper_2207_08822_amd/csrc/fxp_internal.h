@@ -24,7 +24,8 @@ int map_launch(const float* x, int64_t rows, int64_t cols, const int32_t* e_in, 
                int bits, hipStream_t s);
 int gemm_nt_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                    void* C, int64_t ldc, bool fp32_out, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB,
-                   hipStream_t s);
+                   void* ws, size_t ws_bytes, hipStream_t s);
+size_t gemm_split_ws_bytes(int64_t M, int64_t N, int64_t K);
 size_t gemm_ws_worst(int64_t M, int64_t N, int64_t K);
 int transpose_i8_launch(const int8_t* src, int64_t rows, int64_t cols, int64_t ld, int8_t* dst, hipStream_t s);
 

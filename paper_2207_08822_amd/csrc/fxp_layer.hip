@@ -6,6 +6,8 @@
 // Every GEMM takes the native operand form because the mapping wrote both copies:
 //   Y  = Xq  [M,K] x WqT [N,K]^T      dX = dYq [M,N] x Wq [K,N]^T
 //   dW = XqT [K,M] x dYqT[N,M]^T
+#include <algorithm>
+
 #include "fxp_internal.h"
 
 namespace fxp {
@@ -53,8 +55,11 @@ extern "C" size_t fxp_workspace_bytes(int op, int64_t M, int64_t N, int64_t K) {
     switch (op) {
         case FXP_OP_SCALE: return fxp::kScaleWsBytes;
         case FXP_OP_GEMM: return fxp::gemm_ws_worst(M, N, K) + 256;
-        case FXP_OP_LINEAR_FWD: return 2 * fxp::round_up(fxp::kScaleWsBytes, 256);
-        case FXP_OP_LINEAR_BWD: return fxp::round_up(fxp::kScaleWsBytes, 256);
+        case FXP_OP_LINEAR_FWD:
+            return 2 * fxp::round_up(fxp::kScaleWsBytes, 256) + fxp::gemm_split_ws_bytes(M, N, K);
+        case FXP_OP_LINEAR_BWD:   // the two gradient GEMMs run one after the other and share the slice area
+            return fxp::round_up(fxp::kScaleWsBytes, 256) +
+                   std::max(fxp::gemm_split_ws_bytes(M, K, N), fxp::gemm_split_ws_bytes(K, N, M));
         default: return 0;
     }
 }
@@ -77,7 +82,9 @@ extern "C" int fxp_linear_fwd(const float* X, const float* W, int64_t M, int64_t
         return rc;
     if ((rc = scale_and_map(W, K, N, saved->eW, saved->Wq, saved->WqT, seed, (step << 8) | FXP_TAG_W, rounding, bits, pW, s)))
         return rc;
-    return gemm_nt_launch(M, N, K, saved->Xq, K, saved->WqT, K, Y, N, true, saved->eX, bits, saved->eW, bits, s);
+    uint8_t* rest = static_cast<uint8_t*>(ws) + 2 * round_up(kScaleWsBytes, 256);
+    return gemm_nt_launch(M, N, K, saved->Xq, K, saved->WqT, K, Y, N, true, saved->eX, bits, saved->eW, bits, rest,
+                          ws_bytes - 2 * round_up(kScaleWsBytes, 256), s);
 }
 
 extern "C" int fxp_linear_bwd(const float* dY, const fxp_saved* saved, int64_t M, int64_t K, int64_t N, float* dX,
@@ -94,7 +101,13 @@ extern "C" int fxp_linear_bwd(const float* dY, const fxp_saved* saved, int64_t M
     if ((rc = scale_and_map(dY, M, N, e_dY, dYq, dYqT, seed, (step << 8) | FXP_TAG_DY, rounding, bits,
                             static_cast<uint32_t*>(ws), s)))
         return rc;
-    if (dX && (rc = gemm_nt_launch(M, K, N, dYq, N, saved->Wq, N, dX, K, true, e_dY, bits, saved->eW, bits, s))) return rc;
-    if (dW && (rc = gemm_nt_launch(K, N, M, saved->XqT, M, dYqT, M, dW, N, true, saved->eX, bits, e_dY, bits, s))) return rc;
+    uint8_t* rest = static_cast<uint8_t*>(ws) + round_up(kScaleWsBytes, 256);
+    const size_t rest_bytes = ws_bytes - round_up(kScaleWsBytes, 256);
+    if (dX && (rc = gemm_nt_launch(M, K, N, dYq, N, saved->Wq, N, dX, K, true, e_dY, bits, saved->eW, bits, rest,
+                                   rest_bytes, s)))
+        return rc;
+    if (dW && (rc = gemm_nt_launch(K, N, M, saved->XqT, M, dYqT, M, dW, N, true, saved->eX, bits, e_dY, bits, rest,
+                                   rest_bytes, s)))
+        return rc;
     return FXP_OK;
 }

@@ -161,13 +161,25 @@ def test_gemm_extreme_values_longest_contraction(fxp):
     assert np.array_equal(got, want) and abs(int(got[0, 0])) == 16129 * K
 
 
-def test_gemm_is_deterministic(fxp):
-    say("gemm determinism (split-K atomics)")
+def test_gemm_split_k_both_ways_and_deterministic(fxp):
+    """Long contraction, small output: slices of K go to the workspace and are summed by a
+    second pass; with no room for the slices they add into the output with int32 atomics."""
     rng = np.random.default_rng(1)
-    A, B = dev(rand_i8(rng, (256, 8192))), dev(rand_i8(rng, (128, 8192)))
-    first = host(fxp.gemm(A, B, transB=True))
-    for _ in range(3):
-        assert np.array_equal(host(fxp.gemm(A, B, transB=True)), first)
+    for (M, N, K) in [(256, 128, 8192), (512, 768, 6208)]:
+        Ah, Bh = rand_i8(rng, (M, K)), rand_i8(rng, (N, K))
+        want = oracle.gemm(Ah, Bh, transB=True)
+        A, B = dev(Ah), dev(Bh)
+        say("gemm split-K through workspace", (M, N, K))
+        assert fxp.workspace_bytes(fxp.OP_GEMM, M, N, K) >= 2 * M * N * 4
+        for _ in range(3):
+            assert np.array_equal(host(fxp.gemm(A, B, transB=True)), want)
+        say("gemm split-K through atomics", (M, N, K))
+        tiny = torch.empty(256, dtype=torch.uint8, device="cuda")
+        for _ in range(3):
+            assert np.array_equal(host(fxp.gemm(A, B, transB=True, ws=tiny)), want)
+        e = dev(np.array([120, 131], np.int32))
+        got = host(fxp.gemm_unmap(A, B, e[0:1], e[1:2], transB=True, ws=tiny))
+        assert same_bits(got, oracle.unmap(want, 120, 131))
 
 
 # --------------------------------------------------------------------------- unmap
