@@ -30,6 +30,7 @@ struct MapCfg {
     int rshift;     // 32 - cut: the random number is the top `cut` bits of the word
     uint32_t sat;   // 2^(bits-1) - 1
     uint32_t half;  // 2^(cut-1), the nearest-rounding increment
+    uint32_t low_mask;  // 2^cut - 1
 };
 
 __device__ inline uint4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1) {
@@ -60,16 +61,18 @@ __device__ inline uint32_t magnitude_full(uint32_t b, uint32_t word, const MapCf
     return min((mp + add) >> c.cut, c.sat);
 }
 
-// Same for the common case, checked by the caller: e_max in [25, 254] and no element
-// above the scale.  A sub-normal input is then shifted out whatever its hidden bit, so
-// it needs no special case.  r < low  <=>  low + (2^cut - 1 - r) carries out of the cut.
+// Same for the common case: e_max in [25, 254], no element above the scale, no result above
+// the largest magnitude.  A sub-normal input is then shifted out whatever its hidden bit, so it
+// needs no special case.  r < low  <=>  low + (2^cut - 1 - r) carries out of the cut.  The caller
+// ORs `d` (negative = element above the scale) and the result (bit bits-1 set = needs the
+// saturating path) over its elements and redoes the block with magnitude_full if either fires.
 template <bool STOCH>
-__device__ inline uint32_t magnitude_fast(uint32_t b, uint32_t word, const MapCfg& c) {
-    const uint32_t e = (b >> 23) & 0xffu;
-    const uint32_t m = (b & 0x7fffffu) | 0x800000u;
-    const uint32_t mp = m >> min(static_cast<uint32_t>(c.e_max) - e, 31u);
-    const uint32_t add = STOCH ? ((~word) >> c.rshift) : c.half;
-    return min((mp + add) >> c.cut, c.sat);
+__device__ inline uint32_t magnitude_fast(uint32_t b, uint32_t word, const MapCfg& c, uint32_t& d_or) {
+    const uint32_t d = static_cast<uint32_t>(c.e_max) - ((b >> 23) & 0xffu);
+    d_or |= d;
+    const uint32_t mp = ((b & 0x7fffffu) | 0x800000u) >> min(d, 31u);
+    const uint32_t add = STOCH ? ((word >> c.rshift) ^ c.low_mask) : c.half;
+    return (mp + add) >> c.cut;
 }
 
 __device__ inline uint32_t with_sign(uint32_t mag, uint32_t b) {
@@ -77,31 +80,12 @@ __device__ inline uint32_t with_sign(uint32_t mag, uint32_t b) {
     return (mag ^ sm) - sm;
 }
 
-// four consecutive elements -> four int8 packed little-endian
-template <bool STOCH>
-__device__ inline uint32_t map4(const uint4 v, const uint4 w, const MapCfg& c, bool fast) {
-    uint32_t q0, q1, q2, q3;
-    if (fast) {
-        q0 = magnitude_fast<STOCH>(v.x, w.x, c);
-        q1 = magnitude_fast<STOCH>(v.y, w.y, c);
-        q2 = magnitude_fast<STOCH>(v.z, w.z, c);
-        q3 = magnitude_fast<STOCH>(v.w, w.w, c);
-    } else {
-        q0 = magnitude_full<STOCH>(v.x, w.x, c);
-        q1 = magnitude_full<STOCH>(v.y, w.y, c);
-        q2 = magnitude_full<STOCH>(v.z, w.z, c);
-        q3 = magnitude_full<STOCH>(v.w, w.w, c);
-    }
+__device__ inline uint32_t pack4(uint32_t q0, uint32_t q1, uint32_t q2, uint32_t q3, const uint4 v) {
     q0 = with_sign(q0, v.x) & 0xffu;
     q1 = with_sign(q1, v.y) & 0xffu;
     q2 = with_sign(q2, v.z) & 0xffu;
     q3 = with_sign(q3, v.w);
     return q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
-}
-
-__device__ inline uint32_t max_exponent4(const uint4 v) {
-    const uint32_t kAbs = 0x7fffffffu;
-    return max(max(v.x & kAbs, v.y & kAbs), max(v.z & kAbs, v.w & kAbs)) >> 23;
 }
 
 __device__ inline MapCfg make_cfg(int e_max, int bits) {
@@ -111,6 +95,7 @@ __device__ inline MapCfg make_cfg(int e_max, int bits) {
     c.rshift = 32 - c.cut;
     c.sat = (1u << (bits - 1)) - 1u;
     c.half = 1u << (c.cut - 1);
+    c.low_mask = (1u << c.cut) - 1u;
     return c;
 }
 
@@ -127,6 +112,114 @@ __device__ inline int resolve_scale(const int32_t* e_in, const uint32_t* partial
     return e;
 }
 
+// One 128 x 128 tile.  EDGE = the tile sticks out of the tensor: loads are clamped to valid
+// addresses and stores are predicated; interior tiles carry no bounds code at all.  All
+// per-thread addressing is a 32-bit element offset from the tile's (wave-uniform) origin.
+template <bool STOCH, bool EDGE>
+__device__ inline void map_tile_body(const uint32_t* __restrict__ x, int64_t rows, int64_t cols, const MapCfg& cfg,
+                                     int8_t* __restrict__ q, int8_t* __restrict__ qT, uint32_t key0, uint32_t key1,
+                                     uint32_t sid0, uint32_t sid1, int64_t r0, int64_t c0, uint32_t* stage) {
+    const int tid = threadIdx.x;
+    const int cg = tid & 31;                      // group of 4 columns
+    const uint32_t ucols = static_cast<uint32_t>(cols);
+    const int64_t origin = r0 * cols + c0;        // element index of the tile's first element (multiple of 4)
+    const uint32_t* xt = x + origin;
+    int8_t* qt = q ? q + origin : nullptr;
+    const uint64_t blk0 = static_cast<uint64_t>(origin) >> 2;
+    const int rows_here = EDGE ? static_cast<int>(min<int64_t>(kTile, rows - r0)) : kTile;
+    const int cols_here = EDGE ? static_cast<int>(min<int64_t>(kTile, cols - c0)) : kTile;
+    const bool col_ok = !EDGE || 4 * cg < cols_here;
+    const uint32_t col_ld = EDGE ? static_cast<uint32_t>(min(4 * cg, cols_here - 4)) : 4 * cg;
+    const bool scale_ok = cfg.e_max >= 25 && cfg.e_max < 255;
+    const uint32_t over_bit = cfg.sat + 1u;       // a fast-path result with this bit set needs saturation
+
+    // Four passes of 32 rows.  The loads of pass p+1 are issued before the arithmetic of pass
+    // p, so a block keeps the memory pipe busy while it runs its Philox rounds.
+    auto load_pass = [&](int p, uint4 (&v)[4]) {
+        const int lrow = 4 * (p * 8 + (tid >> 5));
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int rr = EDGE ? min(lrow + k, rows_here - 1) : lrow + k;
+            v[k] = *reinterpret_cast<const uint4*>(xt + static_cast<uint32_t>(rr) * ucols + col_ld);
+        }
+    };
+    uint4 cur[4], nxt[4];
+    load_pass(0, cur);
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int rg = p * 8 + (tid >> 5);        // group of 4 rows
+        const int lrow = 4 * rg;
+        if (p < 3) load_pass(p + 1, nxt);
+        auto words_of = [&](int k) {
+            const uint32_t off = static_cast<uint32_t>(lrow + k) * ucols + 4 * cg;   // element offset in the tile
+            const uint64_t blk = blk0 + (off >> 2);
+            return STOCH ? philox4x32_10(static_cast<uint32_t>(blk), static_cast<uint32_t>(blk >> 32), sid0, sid1, key0, key1)
+                         : make_uint4(0, 0, 0, 0);
+        };
+        uint32_t o[4];
+        uint32_t d_or = 0, q_or = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint4 w = words_of(k);
+            const uint32_t m0 = magnitude_fast<STOCH>(cur[k].x, w.x, cfg, d_or);
+            const uint32_t m1 = magnitude_fast<STOCH>(cur[k].y, w.y, cfg, d_or);
+            const uint32_t m2 = magnitude_fast<STOCH>(cur[k].z, w.z, cfg, d_or);
+            const uint32_t m3 = magnitude_fast<STOCH>(cur[k].w, w.w, cfg, d_or);
+            q_or |= m0 | m1 | m2 | m3;
+            o[k] = pack4(m0, m1, m2, m3, cur[k]);
+        }
+        if (!scale_ok || (d_or & 0x80000000u) || (q_or & over_bit)) {
+            // rare: an element above the scale, a saturating result, a non-finite input or a tiny
+            // scale somewhere in this 4 x 4 block: redo it with the complete per-element path
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint4 w = words_of(k);
+                o[k] = pack4(magnitude_full<STOCH>(cur[k].x, w.x, cfg), magnitude_full<STOCH>(cur[k].y, w.y, cfg),
+                             magnitude_full<STOCH>(cur[k].z, w.z, cfg), magnitude_full<STOCH>(cur[k].w, w.w, cfg), cur[k]);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (qt != nullptr && col_ok && (!EDGE || lrow + k < rows_here))
+                *reinterpret_cast<uint32_t*>(qt + static_cast<uint32_t>(lrow + k) * ucols + 4 * cg) = o[k];
+        if (qT != nullptr) {
+            // 4 x 4 byte transpose: t[c] = column c of the block, rows in ascending byte order
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t t = ((o[0] >> (8 * c)) & 0xffu) | (((o[1] >> (8 * c)) & 0xffu) << 8) |
+                                   (((o[2] >> (8 * c)) & 0xffu) << 16) | (((o[3] >> (8 * c)) & 0xffu) << 24);
+                stage[(4 * cg + c) * kTStride + rg] = t;
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) cur[k] = nxt[k];
+    }
+    if (qT == nullptr) return;
+    __syncthreads();
+    int8_t* qTt = qT + c0 * rows + r0;             // element [c0][r0] of the transposed copy
+    const uint32_t urows = static_cast<uint32_t>(rows);
+    if ((rows & 15) == 0) {
+        // 16 rows of one column = 16 contiguous bytes of qT
+#pragma unroll
+        for (int it = 0; it < (kTile * kTile / 16) / kMapThreads; ++it) {
+            const int id = it * kMapThreads + tid;
+            const int c = id >> 3, ch = id & 7;
+            if (!EDGE || (c < cols_here && 16 * ch < rows_here)) {
+                const uint32_t* src = stage + c * kTStride + 4 * ch;
+                *reinterpret_cast<uint4*>(qTt + static_cast<uint64_t>(c) * urows + 16 * ch) =
+                    make_uint4(src[0], src[1], src[2], src[3]);
+            }
+        }
+    } else {
+        const uint8_t* bytes = reinterpret_cast<const uint8_t*>(stage);
+        for (int id = tid; id < kTile * kTile; id += kMapThreads) {
+            const int c = id >> 7, r = id & 127;
+            if (c < cols_here && r < rows_here)
+                qTt[static_cast<uint64_t>(c) * urows + r] = static_cast<int8_t>(bytes[c * kTStride * 4 + r]);
+        }
+    }
+}
+
 template <bool STOCH>
 __global__ __launch_bounds__(kMapThreads) void k_map_tile(const uint32_t* __restrict__ x, int64_t rows, int64_t cols,
                                                           const int32_t* __restrict__ e_in,
@@ -137,69 +230,12 @@ __global__ __launch_bounds__(kMapThreads) void k_map_tile(const uint32_t* __rest
     __shared__ uint32_t stage[kTile * kTStride];
     __shared__ uint32_t red[kMapThreads / 64];
     const MapCfg cfg = make_cfg(resolve_scale(e_in, partials, n_partials, e_out, red), bits);
-    const bool scale_ok = cfg.e_max >= 25 && cfg.e_max < 255;
-
-    const int tid = threadIdx.x;
     const int64_t r0 = static_cast<int64_t>(blockIdx.x / tiles_c) * kTile;
     const int64_t c0 = static_cast<int64_t>(blockIdx.x % tiles_c) * kTile;
-    const int cg = tid & 31;                    // group of 4 columns
-    const int64_t col = c0 + 4 * cg;
-    const bool col_ok = col < cols;             // cols is a multiple of 4: a group is all in or all out
-
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        const int rg = p * 8 + (tid >> 5);      // group of 4 rows
-        const int64_t row = r0 + 4 * rg;
-        uint4 v[4];
-        bool ok[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            ok[k] = col_ok && (row + k) < rows;
-            v[k] = ok[k] ? *reinterpret_cast<const uint4*>(x + (row + k) * cols + col) : make_uint4(0, 0, 0, 0);
-        }
-        uint32_t emax4 = max(max(max_exponent4(v[0]), max_exponent4(v[1])), max(max_exponent4(v[2]), max_exponent4(v[3])));
-        const bool fast = scale_ok && emax4 <= static_cast<uint32_t>(cfg.e_max);
-        uint32_t o[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const uint64_t blk = static_cast<uint64_t>((row + k) * cols + col) >> 2;
-            uint4 w = make_uint4(0, 0, 0, 0);
-            if (STOCH) w = philox4x32_10(static_cast<uint32_t>(blk), static_cast<uint32_t>(blk >> 32), sid0, sid1, key0, key1);
-            o[k] = map4<STOCH>(v[k], w, cfg, fast);
-            if (q != nullptr && ok[k]) *reinterpret_cast<uint32_t*>(q + (row + k) * cols + col) = o[k];
-        }
-        if (qT != nullptr) {
-            // 4 x 4 byte transpose: t[c] = column c of the block, rows in ascending byte order
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const uint32_t t = ((o[0] >> (8 * c)) & 0xffu) | (((o[1] >> (8 * c)) & 0xffu) << 8) |
-                                   (((o[2] >> (8 * c)) & 0xffu) << 16) | (((o[3] >> (8 * c)) & 0xffu) << 24);
-                stage[(4 * cg + c) * kTStride + rg] = t;
-            }
-        }
-    }
-    if (qT == nullptr) return;
-    __syncthreads();
-    if ((rows & 15) == 0) {
-        // 16 rows of one column = 16 contiguous bytes of qT
-#pragma unroll
-        for (int it = 0; it < (kTile * kTile / 16) / kMapThreads; ++it) {
-            const int id = it * kMapThreads + tid;
-            const int c = id >> 3, ch = id & 7;
-            const int64_t orow = c0 + c, ocol = r0 + 16 * ch;
-            if (orow < cols && ocol < rows) {
-                const uint32_t* src = stage + c * kTStride + 4 * ch;
-                *reinterpret_cast<uint4*>(qT + orow * rows + ocol) = make_uint4(src[0], src[1], src[2], src[3]);
-            }
-        }
-    } else {
-        const uint8_t* bytes = reinterpret_cast<const uint8_t*>(stage);
-        for (int id = tid; id < kTile * kTile; id += kMapThreads) {
-            const int c = id >> 7, r = id & 127;
-            const int64_t orow = c0 + c, ocol = r0 + r;
-            if (orow < cols && ocol < rows) qT[orow * rows + ocol] = static_cast<int8_t>(bytes[c * kTStride * 4 + r]);
-        }
-    }
+    if (r0 + kTile <= rows && c0 + kTile <= cols)
+        map_tile_body<STOCH, false>(x, rows, cols, cfg, q, qT, key0, key1, sid0, sid1, r0, c0, stage);
+    else
+        map_tile_body<STOCH, true>(x, rows, cols, cfg, q, qT, key0, key1, sid0, sid1, r0, c0, stage);
 }
 
 // One element per thread, any shape and alignment.
@@ -241,7 +277,7 @@ int map_launch(const float* x, int64_t rows, int64_t cols, const int32_t* e_in, 
     const bool stoch = rounding == FXP_ROUND_STOCHASTIC;
     const int64_t tiles_r = (rows + kTile - 1) / kTile, tiles_c = (cols + kTile - 1) / kTile;
     const bool tile_path = (cols % 4 == 0) && aligned(x, 16) && (!q || aligned(q, 16)) && (!qT || aligned(qT, 16)) &&
-                           tiles_r * tiles_c > 0 && tiles_r * tiles_c < (int64_t{1} << 31) && tiles_c < (int64_t{1} << 30);
+                           tiles_r * tiles_c > 0 && tiles_r * tiles_c < (int64_t{1} << 31) && cols < (int64_t{1} << 24);   // 32-bit offsets inside a tile
     if (tile_path) {
         const dim3 grid(static_cast<unsigned>(tiles_r * tiles_c)), block(kMapThreads);
         if (stoch)
