@@ -38,6 +38,12 @@ def lib():
         L.fxp_ref_linear_fwd.argtypes = [vp, vp, i64, i64, i64, vp, vp, vp, vp, vp, u64, u64, c.c_int, c.c_int]
         L.fxp_ref_linear_bwd.argtypes = [vp, vp, vp, i32, i32, i64, i64, i64, vp, vp, vp, vp, u64, u64, c.c_int,
                                          c.c_int]
+        cd = [i64] * 9       # N, H, W, C, Cout, KH, KW, stride, pad
+        L.fxp_ref_conv2d_fwd_acc.argtypes = [vp, i64, i64, i64, i64, vp, i64, i64, i64, i64, i64, vp]
+        L.fxp_ref_conv2d_bwd_input_acc.argtypes = [vp, vp] + cd + [vp]
+        L.fxp_ref_conv2d_bwd_weight_acc.argtypes = [vp, vp] + cd + [vp]
+        L.fxp_ref_conv2d_fwd.argtypes = [vp, vp] + cd + [vp, vp, vp, vp, vp, u64, u64, c.c_int, c.c_int]
+        L.fxp_ref_conv2d_bwd.argtypes = [vp, vp, vp, i32, i32] + cd + [vp, vp, vp, vp, u64, u64, c.c_int, c.c_int]
         _lib = L
     return _lib
 
@@ -145,4 +151,75 @@ def linear_bwd(dY, saved, seed=0, step=0, rounding=STOCHASTIC, bits=8, need_dX=T
     _check(lib().fxp_ref_linear_bwd(_ptr(dY), _ptr(saved["Xq"]), _ptr(saved["Wq"]), saved["eX"], saved["eW"], M, K, N,
                                     _ptr(dX), _ptr(dW), _ptr(dYq), _ptr(eG), seed, step, rounding, bits),
            "linear_bwd")
+    return dX, dW, dict(dYq=dYq, eG=int(eG[0]))
+
+
+# ---- convolution, channels-last: X[N,H,W,C], W[Cout,KH,KW,C], Y / dY [N,Ho,Wo,Cout] ----------------
+def conv_out_hw(H, W, KH, KW, stride, pad):
+    return (H + 2 * pad - KH) // stride + 1, (W + 2 * pad - KW) // stride + 1
+
+
+def _i8(a):
+    return np.ascontiguousarray(a, dtype=np.int8)
+
+
+def conv2d_fwd_acc(Xq, Wq, stride=1, pad=0):
+    Xq, Wq = _i8(Xq), _i8(Wq)
+    N, H, W, C = Xq.shape
+    Cout, KH, KW, C2 = Wq.shape
+    assert C == C2
+    Ho, Wo = conv_out_hw(H, W, KH, KW, stride, pad)
+    acc = np.empty((N, Ho, Wo, Cout), dtype=np.int32)
+    _check(lib().fxp_ref_conv2d_fwd_acc(_ptr(Xq), N, H, W, C, _ptr(Wq), Cout, KH, KW, stride, pad, _ptr(acc)),
+           "conv2d_fwd_acc")
+    return acc
+
+
+def conv2d_bwd_input_acc(Gq, Wq, x_shape, stride=1, pad=0):
+    Gq, Wq = _i8(Gq), _i8(Wq)
+    N, H, W, C = x_shape
+    Cout, KH, KW, _ = Wq.shape
+    acc = np.empty((N, H, W, C), dtype=np.int32)
+    _check(lib().fxp_ref_conv2d_bwd_input_acc(_ptr(Gq), _ptr(Wq), N, H, W, C, Cout, KH, KW, stride, pad, _ptr(acc)),
+           "conv2d_bwd_input_acc")
+    return acc
+
+
+def conv2d_bwd_weight_acc(Xq, Gq, w_shape, stride=1, pad=0):
+    Xq, Gq = _i8(Xq), _i8(Gq)
+    N, H, W, C = Xq.shape
+    Cout, KH, KW, _ = w_shape
+    acc = np.empty((Cout, KH, KW, C), dtype=np.int32)
+    _check(lib().fxp_ref_conv2d_bwd_weight_acc(_ptr(Xq), _ptr(Gq), N, H, W, C, Cout, KH, KW, stride, pad, _ptr(acc)),
+           "conv2d_bwd_weight_acc")
+    return acc
+
+
+def conv2d_fwd(X, Wt, stride=1, pad=0, seed=0, step=0, rounding=STOCHASTIC, bits=8):
+    """Returns Y[N,Ho,Wo,Cout] and the saved state dict(Xq, Wq, eX, eW, stride, pad)."""
+    X, Wt = _f32(X), _f32(Wt)
+    N, H, W, C = X.shape
+    Cout, KH, KW, _ = Wt.shape
+    Ho, Wo = conv_out_hw(H, W, KH, KW, stride, pad)
+    Y = np.empty((N, Ho, Wo, Cout), dtype=np.float32)
+    Xq = np.empty(X.shape, dtype=np.int8)
+    Wq = np.empty(Wt.shape, dtype=np.int8)
+    eX, eW = np.zeros(1, np.int32), np.zeros(1, np.int32)
+    _check(lib().fxp_ref_conv2d_fwd(_ptr(X), _ptr(Wt), N, H, W, C, Cout, KH, KW, stride, pad, _ptr(Y), _ptr(Xq), _ptr(Wq),
+                                    _ptr(eX), _ptr(eW), seed, step, rounding, bits), "conv2d_fwd")
+    return Y, dict(Xq=Xq, Wq=Wq, eX=int(eX[0]), eW=int(eW[0]), stride=stride, pad=pad)
+
+
+def conv2d_bwd(dY, saved, seed=0, step=0, rounding=STOCHASTIC, bits=8, need_dX=True, need_dW=True):
+    dY = _f32(dY)
+    Xq, Wq = saved["Xq"], saved["Wq"]
+    N, H, W, C = Xq.shape
+    Cout, KH, KW, _ = Wq.shape
+    dX = np.empty(Xq.shape, dtype=np.float32) if need_dX else None
+    dW = np.empty(Wq.shape, dtype=np.float32) if need_dW else None
+    dYq = np.empty(dY.shape, dtype=np.int8)
+    eG = np.zeros(1, np.int32)
+    _check(lib().fxp_ref_conv2d_bwd(_ptr(dY), _ptr(Xq), _ptr(Wq), saved["eX"], saved["eW"], N, H, W, C, Cout, KH, KW,
+                                    saved["stride"], saved["pad"], _ptr(dX), _ptr(dW), _ptr(dYq), _ptr(eG), seed, step,
+                                    rounding, bits), "conv2d_bwd")
     return dX, dW, dict(dYq=dYq, eG=int(eG[0]))

@@ -17,6 +17,7 @@
 //            exponents, Sec. 3.3) + integer mantissa -> rounded, normalised,
 //            packed fp32.
 //   linear — App. A.2: Y = X W, dL/dW = X^T G, and dL/dX = G W^T (chain rule).
+//   conv   — Sec. 3.4: the same inner products with the convolution's index pattern.
 // Random numbers: the paper only says they are generated on the fly; this
 // build fixes Philox-4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11), keyed by the
 // seed, with the tensor's stream id and the element index as the counter.
@@ -282,6 +283,150 @@ int fxp_ref_linear_bwd(const float* dY, const int8_t* Xq, const int8_t* Wq, int3
         int32_t* acc = new int32_t[static_cast<size_t>(K * N) + 1];
         rc = fxp_ref_gemm(1, 0, K, N, M, Xq, K, dYq, N, acc, N);
         if (!rc) rc = fxp_ref_unmap(acc, static_cast<uint64_t>(K * N), eX, bits, *eG, bits, dW);
+        delete[] acc;
+        if (rc) return rc;
+    }
+    return 0;
+}
+
+
+// ---- convolution (Sec. 3.4, "Linear and convolutional layers": the same integer inner products) ----
+// Channels-last tensors: X[N,H,W,C], W[Cout,KH,KW,C], Y and dY [N,Ho,Wo,Cout], zero padding `pad`,
+// stride `stride`, Ho = (H + 2 pad - KH) / stride + 1 (same for Wo).  The three functions below are
+// the textbook definitions on the int8 mantissas with int32 accumulation.
+static bool conv_dims_ok(int64_t N, int64_t H, int64_t W, int64_t C, int64_t Cout, int64_t KH, int64_t KW, int64_t stride,
+                         int64_t pad, int64_t* Ho, int64_t* Wo) {
+    if (N < 1 || H < 1 || W < 1 || C < 1 || Cout < 1 || KH < 1 || KW < 1 || stride < 1 || pad < 0) return false;
+    if (H + 2 * pad < KH || W + 2 * pad < KW) return false;
+    *Ho = (H + 2 * pad - KH) / stride + 1;
+    *Wo = (W + 2 * pad - KW) / stride + 1;
+    return true;
+}
+
+int fxp_ref_conv2d_fwd_acc(const int8_t* Xq, int64_t N, int64_t H, int64_t W, int64_t C, const int8_t* Wq, int64_t Cout,
+                           int64_t KH, int64_t KW, int64_t stride, int64_t pad, int32_t* acc) {
+    int64_t Ho, Wo;
+    if (!conv_dims_ok(N, H, W, C, Cout, KH, KW, stride, pad, &Ho, &Wo)) return -2;
+    if (!Xq || !Wq || !acc) return -1;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t ho = 0; ho < Ho; ++ho)
+            for (int64_t wo = 0; wo < Wo; ++wo)
+                for (int64_t co = 0; co < Cout; ++co) {
+                    int32_t sum = 0;
+                    for (int64_t kh = 0; kh < KH; ++kh)
+                        for (int64_t kw = 0; kw < KW; ++kw) {
+                            const int64_t h = ho * stride + kh - pad, w = wo * stride + kw - pad;
+                            if (h < 0 || h >= H || w < 0 || w >= W) continue;   // zero padding
+                            for (int64_t c = 0; c < C; ++c)
+                                sum += static_cast<int32_t>(Xq[((n * H + h) * W + w) * C + c]) *
+                                       static_cast<int32_t>(Wq[((co * KH + kh) * KW + kw) * C + c]);
+                        }
+                    acc[((n * Ho + ho) * Wo + wo) * Cout + co] = sum;
+                }
+    return 0;
+}
+
+// dL/dX[n,h,w,c] = sum over (co,kh,kw) with (h + pad - kh) = ho * stride, (w + pad - kw) = wo * stride of
+// G[n,ho,wo,co] * W[co,kh,kw,c]  (chain rule through the definition above)
+int fxp_ref_conv2d_bwd_input_acc(const int8_t* Gq, const int8_t* Wq, int64_t N, int64_t H, int64_t W, int64_t C, int64_t Cout,
+                                 int64_t KH, int64_t KW, int64_t stride, int64_t pad, int32_t* dXacc) {
+    int64_t Ho, Wo;
+    if (!conv_dims_ok(N, H, W, C, Cout, KH, KW, stride, pad, &Ho, &Wo)) return -2;
+    if (!Gq || !Wq || !dXacc) return -1;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t h = 0; h < H; ++h)
+            for (int64_t w = 0; w < W; ++w)
+                for (int64_t c = 0; c < C; ++c) {
+                    int32_t sum = 0;
+                    for (int64_t kh = 0; kh < KH; ++kh)
+                        for (int64_t kw = 0; kw < KW; ++kw) {
+                            const int64_t th = h + pad - kh, tw = w + pad - kw;
+                            if (th < 0 || tw < 0 || th % stride || tw % stride) continue;
+                            const int64_t ho = th / stride, wo = tw / stride;
+                            if (ho >= Ho || wo >= Wo) continue;
+                            for (int64_t co = 0; co < Cout; ++co)
+                                sum += static_cast<int32_t>(Gq[((n * Ho + ho) * Wo + wo) * Cout + co]) *
+                                       static_cast<int32_t>(Wq[((co * KH + kh) * KW + kw) * C + c]);
+                        }
+                    dXacc[((n * H + h) * W + w) * C + c] = sum;
+                }
+    return 0;
+}
+
+// dL/dW[co,kh,kw,c] = sum over (n,ho,wo) of X[n, ho*stride+kh-pad, wo*stride+kw-pad, c] * G[n,ho,wo,co]
+int fxp_ref_conv2d_bwd_weight_acc(const int8_t* Xq, const int8_t* Gq, int64_t N, int64_t H, int64_t W, int64_t C,
+                                  int64_t Cout, int64_t KH, int64_t KW, int64_t stride, int64_t pad, int32_t* dWacc) {
+    int64_t Ho, Wo;
+    if (!conv_dims_ok(N, H, W, C, Cout, KH, KW, stride, pad, &Ho, &Wo)) return -2;
+    if (!Xq || !Gq || !dWacc) return -1;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t co = 0; co < Cout; ++co)
+        for (int64_t kh = 0; kh < KH; ++kh)
+            for (int64_t kw = 0; kw < KW; ++kw)
+                for (int64_t c = 0; c < C; ++c) {
+                    int32_t sum = 0;
+                    for (int64_t n = 0; n < N; ++n)
+                        for (int64_t ho = 0; ho < Ho; ++ho) {
+                            const int64_t h = ho * stride + kh - pad;
+                            if (h < 0 || h >= H) continue;
+                            for (int64_t wo = 0; wo < Wo; ++wo) {
+                                const int64_t w = wo * stride + kw - pad;
+                                if (w < 0 || w >= W) continue;
+                                sum += static_cast<int32_t>(Xq[((n * H + h) * W + w) * C + c]) *
+                                       static_cast<int32_t>(Gq[((n * Ho + ho) * Wo + wo) * Cout + co]);
+                            }
+                        }
+                    dWacc[((co * KH + kh) * KW + kw) * C + c] = sum;
+                }
+    return 0;
+}
+
+// Integer convolution layer, forward: the activation tensor is mapped ONCE as a whole (one scale,
+// element index = its channels-last flat index, stream tag 0), the weights likewise (tag 1).
+int fxp_ref_conv2d_fwd(const float* X, const float* Wt, int64_t N, int64_t H, int64_t W, int64_t C, int64_t Cout, int64_t KH,
+                       int64_t KW, int64_t stride, int64_t pad, float* Y, int8_t* Xq, int8_t* Wq, int32_t* eX, int32_t* eW,
+                       uint64_t seed, uint64_t step, int rounding, int bits) {
+    int64_t Ho, Wo;
+    if (!conv_dims_ok(N, H, W, C, Cout, KH, KW, stride, pad, &Ho, &Wo)) return -2;
+    if (!X || !Wt || !Y || !Xq || !Wq || !eX || !eW) return -1;
+    int rc;
+    if ((rc = fxp_ref_scale(X, static_cast<uint64_t>(N * H * W * C), eX))) return rc;
+    if ((rc = fxp_ref_scale(Wt, static_cast<uint64_t>(Cout * KH * KW * C), eW))) return rc;
+    if ((rc = fxp_ref_map(X, N * H * W, C, *eX, Xq, nullptr, seed, (step << 8) | 0u, rounding, bits))) return rc;
+    if ((rc = fxp_ref_map(Wt, Cout, KH * KW * C, *eW, Wq, nullptr, seed, (step << 8) | 1u, rounding, bits))) return rc;
+    const size_t n_out = static_cast<size_t>(N * Ho * Wo * Cout);
+    int32_t* acc = new int32_t[n_out + 1];
+    rc = fxp_ref_conv2d_fwd_acc(Xq, N, H, W, C, Wq, Cout, KH, KW, stride, pad, acc);
+    if (!rc) rc = fxp_ref_unmap(acc, n_out, *eX, bits, *eW, bits, Y);
+    delete[] acc;
+    return rc;
+}
+
+// Backward: the upstream gradient dY[N,Ho,Wo,Cout] is mapped once (tag 2) and used by both gradients.
+int fxp_ref_conv2d_bwd(const float* dY, const int8_t* Xq, const int8_t* Wq, int32_t eX, int32_t eW, int64_t N, int64_t H,
+                       int64_t W, int64_t C, int64_t Cout, int64_t KH, int64_t KW, int64_t stride, int64_t pad, float* dX,
+                       float* dW, int8_t* dYq, int32_t* eG, uint64_t seed, uint64_t step, int rounding, int bits) {
+    int64_t Ho, Wo;
+    if (!conv_dims_ok(N, H, W, C, Cout, KH, KW, stride, pad, &Ho, &Wo)) return -2;
+    if (!dY || !Xq || !Wq || !dYq || !eG) return -1;
+    int rc;
+    if ((rc = fxp_ref_scale(dY, static_cast<uint64_t>(N * Ho * Wo * Cout), eG))) return rc;
+    if ((rc = fxp_ref_map(dY, N * Ho * Wo, Cout, *eG, dYq, nullptr, seed, (step << 8) | 2u, rounding, bits))) return rc;
+    if (dX) {
+        const size_t n = static_cast<size_t>(N * H * W * C);
+        int32_t* acc = new int32_t[n + 1];
+        rc = fxp_ref_conv2d_bwd_input_acc(dYq, Wq, N, H, W, C, Cout, KH, KW, stride, pad, acc);
+        if (!rc) rc = fxp_ref_unmap(acc, n, *eG, bits, eW, bits, dX);
+        delete[] acc;
+        if (rc) return rc;
+    }
+    if (dW) {
+        const size_t n = static_cast<size_t>(Cout * KH * KW * C);
+        int32_t* acc = new int32_t[n + 1];
+        rc = fxp_ref_conv2d_bwd_weight_acc(Xq, dYq, N, H, W, C, Cout, KH, KW, stride, pad, acc);
+        if (!rc) rc = fxp_ref_unmap(acc, n, eX, bits, *eG, bits, dW);
         delete[] acc;
         if (rc) return rc;
     }
