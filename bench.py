@@ -32,8 +32,9 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "c2conv"])
     ap.add_argument("--sigma", type=float, default=1.0, help="c5 only")
+    ap.add_argument("--bits", type=int, default=8, help="width of the fixed-point values (8 = the paper's int8; 4..7 = its ablation)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a 256 MiB elementwise copy (for scaling rocprofv3 byte counters)")
@@ -57,6 +58,57 @@ def read_traffic(workload, kernel_class):
     return None
 
 
+def bench_conv(args, torch, fxp, synth, dev):
+    """The c2 layer given as a convolution (channels-last): map the activation once, int8 im2col, GEMMs,
+    gather col2im.  Same integer work as c2 (3 x 2*M*K*Cout), far fewer fp32 bytes."""
+    X, Wt, dY, g = synth.conv_tensors()
+    buf = fxp.ConvBuffers(g["N"], g["H"], g["W"], g["C"], g["Cout"], g["KH"], g["KW"], g["stride"], g["pad"], device=dev)
+    Xd, Wd, dYd = (torch.from_numpy(a).to(dev) for a in (X, Wt, dY))
+
+    def step(i):
+        fxp.conv2d_fwd(Xd, Wd, buf, seed=0, step=i, bits=args.bits)
+        fxp.conv2d_bwd(dYd, buf, seed=0, step=i, bits=args.bits)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    M, K, Cout = g["N"] * buf.Ho * buf.Wo, g["KH"] * g["KW"] * g["C"], g["Cout"]
+    ops = 3 * 2.0 * M * K * Cout
+    nx, nw, ny = X.size, Wt.size, dY.size
+    # algorithmic HBM bytes of every kernel of the step (see DESIGN.md, convolution path)
+    step_bytes = (4 * nx + 5 * nx) + (4 * nw + 6 * nw) + (nx + M * K) + (M * K + nw + 4 * ny) \
+        + (4 * ny + 6 * ny) + (nx + M * K) + (M * K + ny + 4 * nw) + (ny + nw + 4 * M * K) + (4 * M * K + 4 * nx)
+    gbs = step_bytes / (ms * 1e-3) / 1e9
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        rows = 4
+        t = time.perf_counter()
+        _, sv = oracle.conv2d_fwd(X[:rows], Wt, g["stride"], g["pad"], 0, 0)
+        oracle.conv2d_bwd(dY[:rows], sv, 0, 0)
+        dt = time.perf_counter() - t
+        cpu = dict(value=round(ops * rows / g["N"] / dt / 1e12, 6), unit="TOPS", cores=oracle.num_threads(), kind="oracle",
+                   seconds=round(dt, 2), sample=f"first {rows} of {g['N']} images, fwd+bwd")
+    print(json.dumps({
+        "metric": "int8 fixed-point layer fwd+bwd TOPS", "value": round(ops / (ms * 1e-3) / 1e12, 3), "unit": "TOPS",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "c2conv: the c2 ResNet-18 3x3 convolution as a channels-last convolution layer "
+                               f"N={g['N']} H=W={g['H']} C={g['C']} Cout={g['Cout']} (M={M} K={K})",
+                   "pass": "scale+map X, W, dY; int8 im2col; 3 int8 GEMMs; gather col2im + inverse map",
+                   "rounding": "stochastic (Philox-4x32-10)", "bits": args.bits},
+        "roofline": dict(bound="hbm", achieved=round(gbs, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                         frac=round(gbs / PEAK_HBM_GBS, 4), kernel="whole step (14 kernels, all HBM-bound)",
+                         algorithmic_per_launch=step_bytes, traffic=None),
+        "cpu_baseline": cpu,
+    }))
+
+
 def main():
     args = parse_args()
     world = int(os.environ.get("WORLD_SIZE", "1"))
@@ -74,6 +126,8 @@ def main():
     fxp.lib()
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+    if args.workload == "c2conv":
+        return bench_conv(args, torch, fxp, synth, dev)
     layers = synth.WORKLOADS[args.workload]
     host_inputs, dev_inputs, bufs = [], [], []
     for li, layer in enumerate(layers):
@@ -85,8 +139,8 @@ def main():
 
     def step(i):
         for (X, W, dY), buf in zip(dev_inputs, bufs):
-            fxp.linear_fwd(X, W, buf, seed=seed, step=i)
-            fxp.linear_bwd(dY, buf, seed=seed, step=i)
+            fxp.linear_fwd(X, W, buf, seed=seed, step=i, bits=args.bits)
+            fxp.linear_bwd(dY, buf, seed=seed, step=i, bits=args.bits)
 
     # ------------------------------------------------------------------ whole step
     for i in range(args.warmup):
@@ -137,15 +191,15 @@ def main():
             # scale: 4 B read per element (k_absmax_partials; the finishing block is negligible)
             add("scale", "k_absmax_partials", timed(lambda: lib.fxp_scale(p(t), n, p(e), p(ws), ws.numel(), st)), 4.0 * n)
             # map: 4 B read + 1 B written per copy (both orientations) per element
-            add("map", "k_map_tile<true>",
-                timed(lambda: lib.fxp_map(p(t), t.shape[0], t.shape[1], p(e), p(q), p(qT), seed, 0, 0, 8, st)), 6.0 * n)
+            add("map", "k_map_tile<true, *>",
+                timed(lambda: lib.fxp_map(p(t), t.shape[0], t.shape[1], p(e), p(q), p(qT), seed, 0, 0, args.bits, st)), 6.0 * n)
             del q, qT
         gemms = [("fwd", M, N, K, buf.Xq, buf.WqT, buf.eX, buf.eW, buf.Y),
                  ("dX", M, K, N, buf.dYq, buf.Wq, buf.e_dY, buf.eW, buf.dX),
                  ("dW", K, N, M, buf.XqT, buf.dYqT, buf.eX, buf.e_dY, buf.dW)]
         for name, gm, gn, gk, A, B, eA, eB, C in gemms:
             gws = torch.empty(max(256, fxp.workspace_bytes(fxp.OP_GEMM, gm, gn, gk)), dtype=torch.uint8, device=dev)
-            dt = timed(lambda: lib.fxp_gemm_unmap(0, 1, gm, gn, gk, p(A), gk, p(B), gk, p(eA), 8, p(eB), 8, p(C), gn,
+            dt = timed(lambda: lib.fxp_gemm_unmap(0, 1, gm, gn, gk, p(A), gk, p(B), gk, p(eA), args.bits, p(eB), args.bits, p(C), gn,
                                                   p(gws), gws.numel(), st))
             del gws
             ops, nbytes = 2.0 * gm * gn * gk, float(gm * gk + gn * gk + 4 * gm * gn)
@@ -221,7 +275,7 @@ def main():
         "config": {"workload": f"{args.workload}: " + ", ".join(f"{l.name} M={l.M} K={l.K} N={l.N}" for l in layers)
                    + (f", sigma={args.sigma}" if args.workload == "c5" else ""),
                    "pass": "scale+map X,W,dY (int8, both orientations) + 3 int8 GEMMs with fused inverse map",
-                   "rounding": "stochastic (Philox-4x32-10)", "bits": 8},
+                   "rounding": "stochastic (Philox-4x32-10)", "bits": args.bits},
         "map_gbs": kernels["map"]["gbs"],
         "roofline": roofline,
         "kernels": kernels,

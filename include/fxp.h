@@ -153,6 +153,40 @@ int fxp_linear_bwd(const float* dY, const fxp_saved* saved, int64_t M, int64_t K
                    int8_t* dYq, int8_t* dYqT, int32_t* e_dY, uint64_t seed, uint64_t step, int rounding, int bits,
                    void* ws, size_t ws_bytes, void* stream);
 
+/* ---- convolution layer (Sec. 3.4: "Linear and convolutional layers" share the integer inner product) ----
+ * Channels-last tensors: X[N,H,W,C], W[Cout,KH,KW,C], Y and dY [N,Ho,Wo,Cout] with
+ * Ho = (H + 2 pad - KH) / stride + 1 (same for Wo), zero padding.  Host struct. */
+typedef struct fxp_conv2d_shape {
+    int64_t N, H, W, C, Cout, KH, KW, stride, pad;
+} fxp_conv2d_shape;
+
+/* What a forward call leaves for the backward call (host struct of device pointers, caller-allocated,
+ * 16-byte aligned): the int8 activation itself, the int8 weights in both orientations, the scales. */
+typedef struct fxp_conv_saved {
+    int8_t* Xq;   /* [N,H,W,C] */
+    int8_t* Wq;   /* [Cout, KH*KW*C] */
+    int8_t* WqT;  /* [KH*KW*C, Cout] */
+    int8_t* WqF;  /* [C, KH*KW*Cout]: kernel flipped in both spatial axes, for the input gradient */
+    int32_t* eX;  /* 1 */
+    int32_t* eW;  /* 1 */
+} fxp_conv_saved;
+
+/* Scratch bytes of fxp_conv2d_fwd (backward = 0) or fxp_conv2d_bwd (backward = 1); 0 on a bad shape. */
+size_t fxp_conv2d_workspace_bytes(const fxp_conv2d_shape* shape, int backward);
+
+/* Forward: the activation tensor is mapped once as a whole (element index = its channels-last flat index,
+ * FXP_TAG_X), the weights likewise (FXP_TAG_W); int8 patches are gathered into scratch and multiplied on the
+ * matrix cores; Y receives the inverse-mapped fp32 result.  Contraction KH*KW*C <= 133144. */
+int fxp_conv2d_fwd(const float* X, const float* W, const fxp_conv2d_shape* shape, float* Y, const fxp_conv_saved* saved,
+                   uint64_t seed, uint64_t step, int rounding, int bits, void* ws, size_t ws_bytes, void* stream);
+
+/* Backward: dY is mapped once (FXP_TAG_DY); dW[Cout,KH,KW,C] sums over all N*Ho*Wo output pixels (<= 133144),
+ * dX[N,H,W,C] sums, per input pixel, the patch entries that read it (exact int32, then one inverse mapping).
+ * dX or dW may be NULL.  dYq [N*Ho*Wo, Cout], dYqT [Cout, N*Ho*Wo] and e_dY are caller-allocated. */
+int fxp_conv2d_bwd(const float* dY, const fxp_conv_saved* saved, const fxp_conv2d_shape* shape, float* dX, float* dW,
+                   int8_t* dYq, int8_t* dYqT, int32_t* e_dY, uint64_t seed, uint64_t step, int rounding, int bits,
+                   void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

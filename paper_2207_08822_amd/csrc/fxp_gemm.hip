@@ -727,6 +727,7 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const int32_t* __restrict
         if (vec) {
             for (int i = blockIdx.x * 256 + threadIdx.x; i < nvec; i += gridDim.x * 256) {
                 int4 acc = make_int4(0, 0, 0, 0);
+#pragma unroll 8
                 for (int sidx = 0; sidx < splits; ++sidx) {
                     const int4 v = reinterpret_cast<const int4*>(prow + sidx * stride)[i];
                     acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;

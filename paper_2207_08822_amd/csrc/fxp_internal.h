@@ -47,6 +47,16 @@ __device__ inline uint32_t block_max(uint32_t v, uint32_t* lds) {
     return r;
 }
 
+// scale + map of one tensor: block maxima, then the map kernel finishes the reduction and publishes *e
+inline int scale_and_map(const float* x, int64_t rows, int64_t cols, int32_t* e, int8_t* q, int8_t* qT, uint64_t seed,
+                         uint64_t sid, int rounding, int bits, uint32_t* partials, hipStream_t s) {
+    int np = 0;
+    int rc = scale_partials(x, static_cast<size_t>(rows * cols), partials, &np, s);
+    if (rc) return rc;
+    return map_launch(x, rows, cols, nullptr, partials, np, e, q, qT, seed, sid, rounding, bits, s);
+}
+
+
 // exponent of one unit of a mapped tensor
 __host__ __device__ inline int lsb_exponent(int e_max, int bits) { return e_max - 127 - (bits - 2); }
 

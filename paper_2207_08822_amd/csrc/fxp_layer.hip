@@ -23,14 +23,6 @@ static int check_layer(int64_t M, int64_t K, int64_t N, int rounding, int bits, 
     return FXP_OK;
 }
 
-static int scale_and_map(const float* x, int64_t rows, int64_t cols, int32_t* e, int8_t* q, int8_t* qT, uint64_t seed,
-                         uint64_t sid, int rounding, int bits, uint32_t* partials, hipStream_t s) {
-    int np = 0;
-    int rc = scale_partials(x, static_cast<size_t>(rows * cols), partials, &np, s);
-    if (rc) return rc;
-    return map_launch(x, rows, cols, nullptr, partials, np, e, q, qT, seed, sid, rounding, bits, s);
-}
-
 }  // namespace fxp
 
 extern "C" const char* fxp_strerror(int status) {

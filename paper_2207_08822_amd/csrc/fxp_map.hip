@@ -22,7 +22,6 @@ namespace fxp {
 
 constexpr int kTile = 128;
 constexpr int kMapThreads = 256;
-constexpr int kTStride = 33;  // dwords per staged column: 128 row bytes + 4 pad
 
 struct MapCfg {
     int e_max;
@@ -112,13 +111,16 @@ __device__ inline int resolve_scale(const int32_t* e_in, const uint32_t* partial
     return e;
 }
 
-// One 128 x 128 tile.  EDGE = the tile sticks out of the tensor: loads are clamped to valid
+// One (32 * PASSES) x 128 tile (PASSES = 4 for large tensors, 1 when the tensor is too small to fill
+// the chip with 128-row tiles).  EDGE = the tile sticks out of the tensor: loads are clamped to valid
 // addresses and stores are predicated; interior tiles carry no bounds code at all.  All
 // per-thread addressing is a 32-bit element offset from the tile's (wave-uniform) origin.
-template <bool STOCH, bool EDGE>
+template <bool STOCH, bool EDGE, int PASSES>
 __device__ inline void map_tile_body(const uint32_t* __restrict__ x, int64_t rows, int64_t cols, const MapCfg& cfg,
                                      int8_t* __restrict__ q, int8_t* __restrict__ qT, uint32_t key0, uint32_t key1,
                                      uint32_t sid0, uint32_t sid1, int64_t r0, int64_t c0, uint32_t* stage) {
+    constexpr int TR = 32 * PASSES;               // rows of the tile
+    constexpr int TS = 8 * PASSES + 1;            // dwords per staged column (TR row bytes + 4 pad)
     const int tid = threadIdx.x;
     const int cg = tid & 31;                      // group of 4 columns
     const uint32_t ucols = static_cast<uint32_t>(cols);
@@ -126,14 +128,14 @@ __device__ inline void map_tile_body(const uint32_t* __restrict__ x, int64_t row
     const uint32_t* xt = x + origin;
     int8_t* qt = q ? q + origin : nullptr;
     const uint64_t blk0 = static_cast<uint64_t>(origin) >> 2;
-    const int rows_here = EDGE ? static_cast<int>(min<int64_t>(kTile, rows - r0)) : kTile;
+    const int rows_here = EDGE ? static_cast<int>(min<int64_t>(TR, rows - r0)) : TR;
     const int cols_here = EDGE ? static_cast<int>(min<int64_t>(kTile, cols - c0)) : kTile;
     const bool col_ok = !EDGE || 4 * cg < cols_here;
     const uint32_t col_ld = EDGE ? static_cast<uint32_t>(min(4 * cg, cols_here - 4)) : 4 * cg;
     const bool scale_ok = cfg.e_max >= 25 && cfg.e_max < 255;
     const uint32_t over_bit = cfg.sat + 1u;       // a fast-path result with this bit set needs saturation
 
-    // Four passes of 32 rows.  The loads of pass p+1 are issued before the arithmetic of pass
+    // PASSES passes of 32 rows.  The loads of pass p+1 are issued before the arithmetic of pass
     // p, so a block keeps the memory pipe busy while it runs its Philox rounds.
     auto load_pass = [&](int p, uint4 (&v)[4]) {
         const int lrow = 4 * (p * 8 + (tid >> 5));
@@ -146,10 +148,10 @@ __device__ inline void map_tile_body(const uint32_t* __restrict__ x, int64_t row
     uint4 cur[4], nxt[4];
     load_pass(0, cur);
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
+    for (int p = 0; p < PASSES; ++p) {
         const int rg = p * 8 + (tid >> 5);        // group of 4 rows
         const int lrow = 4 * rg;
-        if (p < 3) load_pass(p + 1, nxt);
+        if (p + 1 < PASSES) load_pass(p + 1, nxt);
         auto words_of = [&](int k) {
             const uint32_t off = static_cast<uint32_t>(lrow + k) * ucols + 4 * cg;   // element offset in the tile
             const uint64_t blk = blk0 + (off >> 2);
@@ -188,7 +190,7 @@ __device__ inline void map_tile_body(const uint32_t* __restrict__ x, int64_t row
             for (int c = 0; c < 4; ++c) {
                 const uint32_t t = ((o[0] >> (8 * c)) & 0xffu) | (((o[1] >> (8 * c)) & 0xffu) << 8) |
                                    (((o[2] >> (8 * c)) & 0xffu) << 16) | (((o[3] >> (8 * c)) & 0xffu) << 24);
-                stage[(4 * cg + c) * kTStride + rg] = t;
+                stage[(4 * cg + c) * TS + rg] = t;
             }
         }
 #pragma unroll
@@ -200,42 +202,44 @@ __device__ inline void map_tile_body(const uint32_t* __restrict__ x, int64_t row
     const uint32_t urows = static_cast<uint32_t>(rows);
     if ((rows & 15) == 0) {
         // 16 rows of one column = 16 contiguous bytes of qT
+        constexpr int PIECES = TR / 16;                     // per column
 #pragma unroll
-        for (int it = 0; it < (kTile * kTile / 16) / kMapThreads; ++it) {
+        for (int it = 0; it < (kTile * PIECES + kMapThreads - 1) / kMapThreads; ++it) {
             const int id = it * kMapThreads + tid;
-            const int c = id >> 3, ch = id & 7;
-            if (!EDGE || (c < cols_here && 16 * ch < rows_here)) {
-                const uint32_t* src = stage + c * kTStride + 4 * ch;
+            const int c = id / PIECES, ch = id % PIECES;
+            if (c < kTile && (!EDGE || (c < cols_here && 16 * ch < rows_here))) {
+                const uint32_t* src = stage + c * TS + 4 * ch;
                 *reinterpret_cast<uint4*>(qTt + static_cast<uint64_t>(c) * urows + 16 * ch) =
                     make_uint4(src[0], src[1], src[2], src[3]);
             }
         }
     } else {
         const uint8_t* bytes = reinterpret_cast<const uint8_t*>(stage);
-        for (int id = tid; id < kTile * kTile; id += kMapThreads) {
-            const int c = id >> 7, r = id & 127;
+        for (int id = tid; id < kTile * TR; id += kMapThreads) {
+            const int c = id / TR, r = id % TR;
             if (c < cols_here && r < rows_here)
-                qTt[static_cast<uint64_t>(c) * urows + r] = static_cast<int8_t>(bytes[c * kTStride * 4 + r]);
+                qTt[static_cast<uint64_t>(c) * urows + r] = static_cast<int8_t>(bytes[c * TS * 4 + r]);
         }
     }
 }
 
-template <bool STOCH>
+template <bool STOCH, int PASSES>
 __global__ __launch_bounds__(kMapThreads) void k_map_tile(const uint32_t* __restrict__ x, int64_t rows, int64_t cols,
                                                           const int32_t* __restrict__ e_in,
                                                           const uint32_t* __restrict__ partials, int n_partials,
                                                           int32_t* __restrict__ e_out, int8_t* __restrict__ q,
                                                           int8_t* __restrict__ qT, uint32_t key0, uint32_t key1,
                                                           uint32_t sid0, uint32_t sid1, int bits, int tiles_c) {
-    __shared__ uint32_t stage[kTile * kTStride];
+    constexpr int TR = 32 * PASSES;
+    __shared__ uint32_t stage[kTile * (8 * PASSES + 1)];
     __shared__ uint32_t red[kMapThreads / 64];
     const MapCfg cfg = make_cfg(resolve_scale(e_in, partials, n_partials, e_out, red), bits);
-    const int64_t r0 = static_cast<int64_t>(blockIdx.x / tiles_c) * kTile;
+    const int64_t r0 = static_cast<int64_t>(blockIdx.x / tiles_c) * TR;
     const int64_t c0 = static_cast<int64_t>(blockIdx.x % tiles_c) * kTile;
-    if (r0 + kTile <= rows && c0 + kTile <= cols)
-        map_tile_body<STOCH, false>(x, rows, cols, cfg, q, qT, key0, key1, sid0, sid1, r0, c0, stage);
+    if (r0 + TR <= rows && c0 + kTile <= cols)
+        map_tile_body<STOCH, false, PASSES>(x, rows, cols, cfg, q, qT, key0, key1, sid0, sid1, r0, c0, stage);
     else
-        map_tile_body<STOCH, true>(x, rows, cols, cfg, q, qT, key0, key1, sid0, sid1, r0, c0, stage);
+        map_tile_body<STOCH, true, PASSES>(x, rows, cols, cfg, q, qT, key0, key1, sid0, sid1, r0, c0, stage);
 }
 
 // One element per thread, any shape and alignment.
@@ -275,17 +279,22 @@ int map_launch(const float* x, int64_t rows, int64_t cols, const int32_t* e_in, 
     const uint32_t s0 = static_cast<uint32_t>(stream_id), s1 = static_cast<uint32_t>(stream_id >> 32);
     const uint32_t* xb = reinterpret_cast<const uint32_t*>(x);
     const bool stoch = rounding == FXP_ROUND_STOCHASTIC;
-    const int64_t tiles_r = (rows + kTile - 1) / kTile, tiles_c = (cols + kTile - 1) / kTile;
+    const int64_t tiles_c = (cols + kTile - 1) / kTile;
+    // 128-row tiles need about 2000 workgroups to fill the chip; smaller tensors take 32-row tiles
+    const bool small = ((rows + kTile - 1) / kTile) * tiles_c < 2048;
+    const int64_t tiles_r = small ? (rows + 31) / 32 : (rows + kTile - 1) / kTile;
     const bool tile_path = (cols % 4 == 0) && aligned(x, 16) && (!q || aligned(q, 16)) && (!qT || aligned(qT, 16)) &&
                            tiles_r * tiles_c > 0 && tiles_r * tiles_c < (int64_t{1} << 31) && cols < (int64_t{1} << 24);   // 32-bit offsets inside a tile
     if (tile_path) {
         const dim3 grid(static_cast<unsigned>(tiles_r * tiles_c)), block(kMapThreads);
-        if (stoch)
-            hipLaunchKernelGGL(k_map_tile<true>, grid, block, 0, s, xb, rows, cols, e_in, partials, n_partials, e_out, q,
-                               qT, k0, k1, s0, s1, bits, static_cast<int>(tiles_c));
-        else
-            hipLaunchKernelGGL(k_map_tile<false>, grid, block, 0, s, xb, rows, cols, e_in, partials, n_partials, e_out,
-                               q, qT, k0, k1, s0, s1, bits, static_cast<int>(tiles_c));
+#define FXP_MAP_LAUNCH(STOCH, PASSES)                                                                                   \
+    hipLaunchKernelGGL((k_map_tile<STOCH, PASSES>), grid, block, 0, s, xb, rows, cols, e_in, partials, n_partials, e_out, q, \
+                       qT, k0, k1, s0, s1, bits, static_cast<int>(tiles_c))
+        if (stoch && small) FXP_MAP_LAUNCH(true, 1);
+        else if (stoch) FXP_MAP_LAUNCH(true, 4);
+        else if (small) FXP_MAP_LAUNCH(false, 1);
+        else FXP_MAP_LAUNCH(false, 4);
+#undef FXP_MAP_LAUNCH
     } else {
         const uint64_t n = static_cast<uint64_t>(rows) * static_cast<uint64_t>(cols);
         uint64_t want = (n + kMapThreads - 1) / kMapThreads;

@@ -52,8 +52,8 @@ __global__ __launch_bounds__(kScaleThreads) void k_absmax_finish(const uint32_t*
 }
 
 int scale_partials(const float* x, size_t n, uint32_t* partials, int* n_partials, hipStream_t s) {
-    // 64 bytes per thread per trip; enough blocks to fill the chip, at most kMaxPartials
-    size_t want = (n / 4 + kScaleThreads * 4 - 1) / (kScaleThreads * 4);
+    // 16K elements or more per block (the map kernel re-reads every block maximum), at most kMaxPartials
+    size_t want = (n + 16383) / 16384;
     int grid = static_cast<int>(want < 1 ? 1 : (want > kMaxPartials ? kMaxPartials : want));
     hipLaunchKernelGGL(k_absmax_partials, dim3(grid), dim3(kScaleThreads), 0, s, reinterpret_cast<const uint32_t*>(x),
                        n, partials);

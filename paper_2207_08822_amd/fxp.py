@@ -26,6 +26,15 @@ class _Saved(ctypes.Structure):
                 ("eX", ctypes.c_void_p), ("eW", ctypes.c_void_p)]
 
 
+class _ConvShape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int64) for n in ("N", "H", "W", "C", "Cout", "KH", "KW", "stride", "pad")]
+
+
+class _ConvSaved(ctypes.Structure):
+    _fields_ = [("Xq", ctypes.c_void_p), ("Wq", ctypes.c_void_p), ("WqT", ctypes.c_void_p), ("WqF", ctypes.c_void_p),
+                ("eX", ctypes.c_void_p), ("eW", ctypes.c_void_p)]
+
+
 _lib = None
 
 
@@ -54,6 +63,13 @@ def lib():
     L.fxp_gemm_unmap.argtypes = [ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, ci, vp, ci, vp, i64, vp, sz, vp]
     L.fxp_linear_fwd.argtypes = [vp, vp, i64, i64, i64, vp, c.POINTER(_Saved), u64, u64, ci, ci, vp, sz, vp]
     L.fxp_linear_bwd.argtypes = [vp, c.POINTER(_Saved), i64, i64, i64, vp, vp, vp, vp, vp, u64, u64, ci, ci, vp, sz, vp]
+    L.fxp_conv2d_workspace_bytes.restype = sz
+    L.fxp_conv2d_workspace_bytes.argtypes = [c.POINTER(_ConvShape), ci]
+    L.fxp_conv2d_fwd.argtypes = [vp, vp, c.POINTER(_ConvShape), vp, c.POINTER(_ConvSaved), u64, u64, ci, ci, vp, sz, vp]
+    L.fxp_conv2d_bwd.argtypes = [vp, c.POINTER(_ConvSaved), c.POINTER(_ConvShape), vp, vp, vp, vp, vp, u64, u64, ci, ci,
+                                 vp, sz, vp]
+    L.fxp_conv2d_fwd.restype = ci
+    L.fxp_conv2d_bwd.restype = ci
     for name in ("fxp_scale", "fxp_map", "fxp_scale_map", "fxp_gemm", "fxp_unmap", "fxp_unmap_i8", "fxp_gemm_unmap",
                  "fxp_linear_fwd", "fxp_linear_bwd"):
         getattr(L, name).restype = ci
@@ -225,4 +241,52 @@ def linear_bwd(dY, buf, seed=0, step=0, rounding=STOCHASTIC, bits=8, need_dX=Tru
     _check(lib().fxp_linear_bwd(_p(dY), ctypes.byref(buf.saved), buf.M, buf.K, buf.N, _p(dX), _p(dW), _p(buf.dYq),
                                 _p(buf.dYqT), buf.e[2:3].data_ptr(), seed, step, rounding, bits, _p(buf.ws),
                                 buf.ws.numel(), _stream()), "fxp_linear_bwd")
+    return dX, dW
+
+
+class ConvBuffers:
+    """Caller-owned device buffers of one convolution layer (channels-last), allocated once."""
+
+    def __init__(self, N, H, W, C, Cout, KH, KW, stride=1, pad=0, device="cuda"):
+        self.shape = _ConvShape(N, H, W, C, Cout, KH, KW, stride, pad)
+        self.Ho, self.Wo = (H + 2 * pad - KH) // stride + 1, (W + 2 * pad - KW) // stride + 1
+        M, K = N * self.Ho * self.Wo, KH * KW * C
+        i8 = dict(dtype=torch.int8, device=device)
+        f32 = dict(dtype=torch.float32, device=device)
+        self.Xq = torch.empty((N, H, W, C), **i8)
+        self.Wq, self.WqT = torch.empty((Cout, K), **i8), torch.empty((K, Cout), **i8)
+        self.WqF = torch.empty((C, KH * KW * Cout), **i8)
+        self.dYq, self.dYqT = torch.empty((M, Cout), **i8), torch.empty((Cout, M), **i8)
+        self.e = torch.zeros(3, dtype=torch.int32, device=device)          # eX, eW, e_dY
+        self.Y = torch.empty((N, self.Ho, self.Wo, Cout), **f32)
+        self.dX = torch.empty((N, H, W, C), **f32)
+        self.dW = torch.empty((Cout, KH, KW, C), **f32)
+        nbytes = max(int(lib().fxp_conv2d_workspace_bytes(ctypes.byref(self.shape), 0)),
+                     int(lib().fxp_conv2d_workspace_bytes(ctypes.byref(self.shape), 1)), 256)
+        self.ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        self.saved = _ConvSaved(_p(self.Xq), _p(self.Wq), _p(self.WqT), _p(self.WqF), self.e[0:1].data_ptr(),
+                                self.e[1:2].data_ptr())
+
+
+def conv2d_fwd(X, W, buf, seed=0, step=0, rounding=STOCHASTIC, bits=8):
+    """Y[N,Ho,Wo,Cout] of the integer convolution layer; X[N,H,W,C], W[Cout,KH,KW,C] fp32."""
+    X, W = _dev(X, torch.float32, "X"), _dev(W, torch.float32, "W")
+    sh = buf.shape
+    if tuple(X.shape) != (sh.N, sh.H, sh.W, sh.C) or tuple(W.shape) != (sh.Cout, sh.KH, sh.KW, sh.C):
+        raise FxpError("shapes do not match the convolution buffers")
+    _check(lib().fxp_conv2d_fwd(_p(X), _p(W), ctypes.byref(sh), _p(buf.Y), ctypes.byref(buf.saved), seed, step, rounding,
+                                bits, _p(buf.ws), buf.ws.numel(), _stream()), "fxp_conv2d_fwd")
+    return buf.Y
+
+
+def conv2d_bwd(dY, buf, seed=0, step=0, rounding=STOCHASTIC, bits=8, need_dX=True, need_dW=True):
+    dY = _dev(dY, torch.float32, "dY")
+    sh = buf.shape
+    if tuple(dY.shape) != (sh.N, buf.Ho, buf.Wo, sh.Cout):
+        raise FxpError("shapes do not match the convolution buffers")
+    dX = buf.dX if need_dX else None
+    dW = buf.dW if need_dW else None
+    _check(lib().fxp_conv2d_bwd(_p(dY), ctypes.byref(buf.saved), ctypes.byref(sh), _p(dX), _p(dW), _p(buf.dYq),
+                                _p(buf.dYqT), buf.e[2:3].data_ptr(), seed, step, rounding, bits, _p(buf.ws),
+                                buf.ws.numel(), _stream()), "fxp_conv2d_bwd")
     return dX, dW

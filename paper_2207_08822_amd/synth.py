@@ -110,3 +110,24 @@ def ops_per_layer(layer):
 def mapped_elements(layer):
     """fp32 elements that go through scale + map in one layer step (X, W, dY)."""
     return layer.M * layer.K + layer.K * layer.N + layer.M * layer.N
+
+
+# The convolution of workload c2 given as a convolution (channels-last) instead of its patch matrix.
+C2_CONV = dict(N=32, H=28, W=28, C=128, Cout=128, KH=3, KW=3, stride=1, pad=1)
+
+
+def conv_tensors(seed=1, N=None, H=None, W=None, C=None, Cout=None, KH=3, KW=3, stride=1, pad=1):
+    """fp32 (X[N,H,W,C], Wt[Cout,KH,KW,C], dY[N,Ho,Wo,Cout]): ReLU'd N(0,1) activations, N(0, 2/fan_in)
+    weights, N(0, 1e-3) gradients; defaults are the c2 layer."""
+    g = dict(C2_CONV)
+    for k, v in dict(N=N, H=H, W=W, C=C, Cout=Cout).items():
+        if v is not None:
+            g[k] = v
+    g.update(KH=KH, KW=KW, stride=stride, pad=pad)
+    rng = np.random.Generator(np.random.PCG64([seed, 77]))
+    X = np.maximum(_normal(rng, (g["N"], g["H"], g["W"], g["C"]), 1.0), 0.0)
+    fan_in = KH * KW * g["C"]
+    Wt = _normal(rng, (g["Cout"], KH, KW, g["C"]), np.sqrt(2.0 / fan_in))
+    Ho, Wo = (g["H"] + 2 * pad - KH) // stride + 1, (g["W"] + 2 * pad - KW) // stride + 1
+    dY = _normal(rng, (g["N"], Ho, Wo, g["Cout"]), 1e-3)
+    return X, Wt, dY, g
