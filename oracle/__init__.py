@@ -39,6 +39,10 @@ def lib():
         L.fxp_ref_linear_bwd.argtypes = [vp, vp, vp, i32, i32, i64, i64, i64, vp, vp, vp, vp, u64, u64, c.c_int,
                                          c.c_int]
         cd = [i64] * 9       # N, H, W, C, Cout, KH, KW, stride, pad
+        L.fxp_ref_gemm_batched.argtypes = [c.c_int, c.c_int, i64, i64, i64, vp, i64, i64, vp, i64, i64, vp, i64, i64, i64]
+        L.fxp_ref_bmm_fwd.argtypes = [vp, vp, i64, i64, i64, i64, c.c_int, vp, vp, vp, vp, vp, u64, u64, c.c_int, c.c_int]
+        L.fxp_ref_bmm_bwd.argtypes = [vp, vp, vp, i32, i32, i64, i64, i64, i64, c.c_int, vp, vp, vp, vp, u64, u64, c.c_int,
+                                      c.c_int]
         L.fxp_ref_conv2d_fwd_acc.argtypes = [vp, i64, i64, i64, i64, vp, i64, i64, i64, i64, i64, vp]
         L.fxp_ref_conv2d_bwd_input_acc.argtypes = [vp, vp] + cd + [vp]
         L.fxp_ref_conv2d_bwd_weight_acc.argtypes = [vp, vp] + cd + [vp]
@@ -223,3 +227,50 @@ def conv2d_bwd(dY, saved, seed=0, step=0, rounding=STOCHASTIC, bits=8, need_dX=T
                                     saved["stride"], saved["pad"], _ptr(dX), _ptr(dW), _ptr(dYq), _ptr(eG), seed, step,
                                     rounding, bits), "conv2d_bwd")
     return dX, dW, dict(dYq=dYq, eG=int(eG[0]))
+
+
+# ---- batched products (attention matmuls): A[batch,M,K], Bm[batch,K,N] or [batch,N,K] with transB -------
+def gemm_batched(A, B, transA=False, transB=False):
+    """A[batch,.,.], B[batch,.,.] int8, dense; returns int32 C[batch,M,N] with C_b = op(A_b) op(B_b)."""
+    A, B = _i8(A), _i8(B)
+    batch = A.shape[0]
+    assert B.shape[0] == batch
+    M, K = (A.shape[2], A.shape[1]) if transA else A.shape[1:]
+    Kb, N = (B.shape[2], B.shape[1]) if transB else B.shape[1:]
+    assert K == Kb, "contraction lengths differ"
+    C = np.empty((batch, M, N), dtype=np.int32)
+    _check(lib().fxp_ref_gemm_batched(int(transA), int(transB), M, N, K, _ptr(A), A.shape[2], A.shape[1] * A.shape[2],
+                                      _ptr(B), B.shape[2], B.shape[1] * B.shape[2], _ptr(C), N, M * N, batch),
+           "gemm_batched")
+    return C
+
+
+def bmm_fwd(A, Bm, transB=False, seed=0, step=0, rounding=STOCHASTIC, bits=8):
+    """Returns Y[batch,M,N] and the saved state dict(Aq, Bq, eA, eB, transB)."""
+    A, Bm = _f32(A), _f32(Bm)
+    batch, M, K = A.shape
+    N = Bm.shape[1] if transB else Bm.shape[2]
+    assert Bm.shape == ((batch, N, K) if transB else (batch, K, N))
+    Y = np.empty((batch, M, N), dtype=np.float32)
+    Aq = np.empty(A.shape, dtype=np.int8)
+    Bq = np.empty(Bm.shape, dtype=np.int8)
+    eA = np.zeros(1, dtype=np.int32)
+    eB = np.zeros(1, dtype=np.int32)
+    _check(lib().fxp_ref_bmm_fwd(_ptr(A), _ptr(Bm), batch, M, K, N, int(transB), _ptr(Y), _ptr(Aq), _ptr(Bq), _ptr(eA),
+                                 _ptr(eB), seed, step, rounding, bits), "bmm_fwd")
+    return Y, dict(Aq=Aq, Bq=Bq, eA=int(eA[0]), eB=int(eB[0]), transB=bool(transB))
+
+
+def bmm_bwd(dY, saved, seed=0, step=0, rounding=STOCHASTIC, bits=8, need_dA=True, need_dB=True):
+    """Returns dA, dBm (in the layouts of A, Bm) and dict(dYq, eG)."""
+    dY = _f32(dY)
+    batch, M, N = dY.shape
+    K = saved["Aq"].shape[2]
+    dA = np.empty(saved["Aq"].shape, dtype=np.float32) if need_dA else None
+    dB = np.empty(saved["Bq"].shape, dtype=np.float32) if need_dB else None
+    dYq = np.empty(dY.shape, dtype=np.int8)
+    eG = np.zeros(1, dtype=np.int32)
+    _check(lib().fxp_ref_bmm_bwd(_ptr(dY), _ptr(saved["Aq"]), _ptr(saved["Bq"]), saved["eA"], saved["eB"], batch, M, K, N,
+                                 int(saved["transB"]), _ptr(dA), _ptr(dB), _ptr(dYq), _ptr(eG), seed, step, rounding,
+                                 bits), "bmm_bwd")
+    return dA, dB, dict(dYq=dYq, eG=int(eG[0]))

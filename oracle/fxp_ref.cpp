@@ -433,4 +433,78 @@ int fxp_ref_conv2d_bwd(const float* dY, const int8_t* Xq, const int8_t* Wq, int3
     return 0;
 }
 
+// ---- batched matrix products (attention: the paper runs Q K^T and A V on the integer mantissas and
+// keeps the softmax in floating point; Sec. 5, vision transformer) ----
+// `batch` independent products C_b = op(A_b) op(B_b); matrix b of an operand starts b * stride elements
+// after matrix 0.  Each product is the plain definition above.
+int fxp_ref_gemm_batched(int transA, int transB, int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda,
+                         int64_t strideA, const int8_t* B, int64_t ldb, int64_t strideB, int32_t* C, int64_t ldc,
+                         int64_t strideC, int64_t batch) {
+    if (batch < 0) return -2;
+    for (int64_t b = 0; b < batch; ++b) {
+        const int rc = fxp_ref_gemm(transA, transB, M, N, K, A + b * strideA, lda, B + b * strideB, ldb, C + b * strideC, ldc);
+        if (rc) return rc;
+    }
+    return 0;
+}
+
+// Forward of a batched product layer, Y_b = unmap(map(A)_b * op(map(Bm)_b)).  A[batch,M,K]; Bm[batch,K,N], or
+// [batch,N,K] with transB (keys of an attention head: scores = Q K^T).  Each TENSOR gets one scale and is
+// mapped once as a whole (row-major element index into the random stream; tags 0 for A, 1 for Bm), exactly
+// like the operands of a linear layer.  Aq / Bq come back in the layouts of A / Bm.
+int fxp_ref_bmm_fwd(const float* A, const float* Bm, int64_t batch, int64_t M, int64_t K, int64_t N, int transB,
+                    float* Y, int8_t* Aq, int8_t* Bq, int32_t* eA, int32_t* eB, uint64_t seed, uint64_t step,
+                    int rounding, int bits) {
+    if (!A || !Bm || !Y || !Aq || !Bq || !eA || !eB) return -1;
+    if (batch < 0 || M < 0 || K < 0 || N < 0) return -2;
+    int rc;
+    if ((rc = fxp_ref_scale(A, static_cast<uint64_t>(batch * M * K), eA))) return rc;
+    if ((rc = fxp_ref_scale(Bm, static_cast<uint64_t>(batch * K * N), eB))) return rc;
+    if ((rc = fxp_ref_map(A, batch * M, K, *eA, Aq, nullptr, seed, (step << 8) | 0u, rounding, bits))) return rc;
+    const int64_t b_rows = transB ? N : K, b_cols = transB ? K : N;
+    if ((rc = fxp_ref_map(Bm, batch * b_rows, b_cols, *eB, Bq, nullptr, seed, (step << 8) | 1u, rounding, bits))) return rc;
+    const size_t n = static_cast<size_t>(batch * M * N);
+    int32_t* acc = new int32_t[n + 1];
+    rc = fxp_ref_gemm_batched(0, transB, M, N, K, Aq, K, M * K, Bq, b_cols, K * N, acc, N, M * N, batch);
+    if (!rc) rc = fxp_ref_unmap(acc, n, *eA, bits, *eB, bits, Y);
+    delete[] acc;
+    return rc;
+}
+
+// Backward: G = map(dY[batch,M,N]) once (tag 2); dA_b = unmap(G_b * op(Bq_b)^T) [M,K];
+// dBm_b = unmap(Aq_b^T * G_b) [K,N], or its transpose unmap(G_b^T * Aq_b) [N,K] with transB.
+int fxp_ref_bmm_bwd(const float* dY, const int8_t* Aq, const int8_t* Bq, int32_t eA, int32_t eB, int64_t batch,
+                    int64_t M, int64_t K, int64_t N, int transB, float* dA, float* dBm, int8_t* dYq, int32_t* eG,
+                    uint64_t seed, uint64_t step, int rounding, int bits) {
+    if (!dY || !Aq || !Bq || !dYq || !eG) return -1;
+    if (batch < 0 || M < 0 || K < 0 || N < 0) return -2;
+    int rc;
+    if ((rc = fxp_ref_scale(dY, static_cast<uint64_t>(batch * M * N), eG))) return rc;
+    if ((rc = fxp_ref_map(dY, batch * M, N, *eG, dYq, nullptr, seed, (step << 8) | 2u, rounding, bits))) return rc;
+    const int64_t b_cols = transB ? K : N;
+    if (dA) {
+        const size_t n = static_cast<size_t>(batch * M * K);
+        int32_t* acc = new int32_t[n + 1];
+        // contraction over N: op(B_b)^T is [N,K], which is Bq_b as stored when transB, else its transpose
+        rc = fxp_ref_gemm_batched(0, transB ? 0 : 1, M, K, N, dYq, N, M * N, Bq, b_cols, K * N, acc, K, M * K, batch);
+        if (!rc) rc = fxp_ref_unmap(acc, n, *eG, bits, eB, bits, dA);
+        delete[] acc;
+        if (rc) return rc;
+    }
+    if (dBm) {
+        const size_t n = static_cast<size_t>(batch * K * N);
+        int32_t* acc = new int32_t[n + 1];
+        if (transB) {   // dBm_b[N,K] = G_b^T[N,M] * Aq_b[M,K]
+            rc = fxp_ref_gemm_batched(1, 0, N, K, M, dYq, N, M * N, Aq, K, M * K, acc, K, K * N, batch);
+            if (!rc) rc = fxp_ref_unmap(acc, n, *eG, bits, eA, bits, dBm);
+        } else {        // dBm_b[K,N] = Aq_b^T[K,M] * G_b[M,N]
+            rc = fxp_ref_gemm_batched(1, 0, K, N, M, Aq, K, M * K, dYq, N, M * N, acc, N, K * N, batch);
+            if (!rc) rc = fxp_ref_unmap(acc, n, eA, bits, *eG, bits, dBm);
+        }
+        delete[] acc;
+        if (rc) return rc;
+    }
+    return 0;
+}
+
 }  // extern "C"
