@@ -32,7 +32,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "c2conv"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "c2conv", "vitb_attn"])
     ap.add_argument("--sigma", type=float, default=1.0, help="c5 only")
     ap.add_argument("--bits", type=int, default=8, help="width of the fixed-point values (8 = the paper's int8; 4..7 = its ablation)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -109,6 +109,64 @@ def bench_conv(args, torch, fxp, synth, dev):
     }))
 
 
+def bench_attn(args, torch, fxp, synth, dev):
+    """The two attention products of one ViT-B/16 block at batch 64 (768 heads, 197 tokens padded to 208, head
+    width 64), forward + backward each: scores = Q K^T and context = P V as batched product layers."""
+    t, g = synth.attention_tensors()
+    b, S, d = g["batch"], g["S"], g["d"]
+    qk = fxp.BmmBuffers(b, S, d, S, True, device=dev)
+    pv = fxp.BmmBuffers(b, S, S, d, False, device=dev)
+    td = {k: torch.from_numpy(v).to(dev) for k, v in t.items()}
+
+    def step(i):
+        fxp.bmm_fwd(td["Q"], td["K"], qk, seed=0, step=i, bits=args.bits)
+        fxp.bmm_bwd(td["dS"], qk, seed=0, step=i, bits=args.bits)
+        fxp.bmm_fwd(td["P"], td["V"], pv, seed=0, step=i, bits=args.bits)
+        fxp.bmm_bwd(td["dO"], pv, seed=0, step=i, bits=args.bits)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    ops = 2 * 3 * 2.0 * b * S * S * d
+    nq, ns = b * S * d, b * S * S
+
+    def layer_bytes(na, nb, ny):   # three tensors scaled + mapped to both orientations, three products
+        return 10 * (na + nb + ny) + (na + nb + 4 * ny) + (ny + nb + 4 * na) + (na + ny + 4 * nb)
+
+    step_bytes = layer_bytes(nq, nq, ns) + layer_bytes(ns, nq, nq)
+    gbs = step_bytes / (ms * 1e-3) / 1e9
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        nb = 16
+        tt = time.perf_counter()
+        _, sv = oracle.bmm_fwd(t["Q"][:nb], t["K"][:nb], True, 0, 0)
+        oracle.bmm_bwd(t["dS"][:nb], sv, 0, 0)
+        _, sv = oracle.bmm_fwd(t["P"][:nb], t["V"][:nb], False, 0, 0)
+        oracle.bmm_bwd(t["dO"][:nb], sv, 0, 0)
+        dt = time.perf_counter() - tt
+        cpu = dict(value=round(ops * nb / b / dt / 1e12, 6), unit="TOPS", cores=oracle.num_threads(), kind="oracle",
+                   seconds=round(dt, 2), sample=f"first {nb} of {b} heads, both products fwd+bwd")
+    print(json.dumps({
+        "metric": "int8 fixed-point layer fwd+bwd TOPS", "value": round(ops / (ms * 1e-3) / 1e12, 3), "unit": "TOPS",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": f"vitb_attn: attention products of one ViT-B/16 block, batch 64 x 12 heads = {b}, "
+                               f"S={g['S_real']} padded to {S}, d={d}: Q K^T and P V, forward + backward",
+                   "pass": "per product: scale+map 3 tensors (both orientations), 3 batched int8 GEMMs with fused inverse map",
+                   "rounding": "stochastic (Philox-4x32-10)", "bits": args.bits},
+        "roofline": dict(bound="hbm", achieved=round(gbs, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                         frac=round(gbs / PEAK_HBM_GBS, 4), kernel="whole step (18 kernels, all HBM-bound)",
+                         algorithmic_per_launch=step_bytes, traffic=None),
+        "cpu_baseline": cpu,
+    }))
+
+
 def main():
     args = parse_args()
     world = int(os.environ.get("WORLD_SIZE", "1"))
@@ -128,6 +186,8 @@ def main():
     dev = torch.device("cuda:0")
     if args.workload == "c2conv":
         return bench_conv(args, torch, fxp, synth, dev)
+    if args.workload == "vitb_attn":
+        return bench_attn(args, torch, fxp, synth, dev)
     layers = synth.WORKLOADS[args.workload]
     host_inputs, dev_inputs, bufs = [], [], []
     for li, layer in enumerate(layers):

@@ -54,7 +54,7 @@ enum {
 };
 
 /* Operation selector of fxp_workspace_bytes. */
-enum { FXP_OP_SCALE = 0, FXP_OP_GEMM = 1, FXP_OP_LINEAR_FWD = 2, FXP_OP_LINEAR_BWD = 3 };
+enum { FXP_OP_SCALE = 0, FXP_OP_GEMM = 1, FXP_OP_LINEAR_FWD = 2, FXP_OP_LINEAR_BWD = 3, FXP_OP_BMM_FWD = 4, FXP_OP_BMM_BWD = 5 };
 
 /* Random-stream tags of the layer calls: stream_id = (step << 8) | tag. */
 enum { FXP_TAG_X = 0, FXP_TAG_W = 1, FXP_TAG_DY = 2 };
@@ -67,6 +67,8 @@ int fxp_version(void);
 
 /* Scratch bytes an operation needs.  FXP_OP_SCALE: M = number of elements.
  * FXP_OP_GEMM: worst case over the operand forms of fxp_gemm / fxp_gemm_unmap.
+ * FXP_OP_GEMM includes the int32 slices a long, narrow product is split into along K.
+ * FXP_OP_BMM_FWD / _BWD: scale scratch only, whatever the shapes.
  * FXP_OP_LINEAR_FWD / _BWD: layer shapes M, N, K as above.  Returns 0 on bad
  * arguments. */
 size_t fxp_workspace_bytes(int op, int64_t M, int64_t N, int64_t K);
@@ -152,6 +154,51 @@ int fxp_linear_fwd(const float* X, const float* W, int64_t M, int64_t K, int64_t
 int fxp_linear_bwd(const float* dY, const fxp_saved* saved, int64_t M, int64_t K, int64_t N, float* dX, float* dW,
                    int8_t* dYq, int8_t* dYqT, int32_t* e_dY, uint64_t seed, uint64_t step, int rounding, int bits,
                    void* ws, size_t ws_bytes, void* stream);
+
+/* Batched integer GEMM for the attention products (the paper runs Q K^T and A V as int8 matmuls with the
+ * softmax in floating point, Sec. 5 / ViT): `batch` (<= 65535) independent products in the native form
+ * C_b[M,N] = A_b[M,K] * B_b[N,K]^T, matrix b of an operand starting b * stride elements after matrix 0.
+ * One scale per TENSOR (all matrices of A share eA, all of B share eB), as everywhere in the method.
+ * Fast loads need 16-byte aligned bases, and lda, ldb, strideA, strideB, K multiples of 16. */
+int fxp_gemm_batched(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, int64_t strideA, const int8_t* B,
+                     int64_t ldb, int64_t strideB, int32_t* C, int64_t ldc, int64_t strideC, int64_t batch, void* stream);
+
+int fxp_gemm_unmap_batched(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, int64_t strideA, const int8_t* B,
+                           int64_t ldb, int64_t strideB, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB, float* C,
+                           int64_t ldc, int64_t strideC, int64_t batch, void* stream);
+
+/* Mapped operands of a batched product layer (host struct of device pointers, caller-allocated, 16-byte
+ * aligned).  Each tensor is mapped ONCE as a whole, as a matrix of (batch * rows) x cols, in both orientations:
+ *   Aq [batch*M, K]      AqT [K, batch*M]
+ *   Bq  as Bm is laid out: [batch*K, N], or [batch*N, K] with transB;   BqT its transpose
+ * so that every one of the three products per matrix reads K-contiguous operands through a leading dimension
+ * and a batch stride alone (matrix b of a transposed copy is a block of columns). */
+typedef struct fxp_bmm_saved {
+    int8_t* Aq;
+    int8_t* AqT;
+    int8_t* Bq;
+    int8_t* BqT;
+    int32_t* eA;  /* 1 */
+    int32_t* eB;  /* 1 */
+} fxp_bmm_saved;
+
+/* Forward of a batched product layer, the attention matmuls of the vision transformer (Sec. 5: Q K^T and A V
+ * run on the integer mantissas, the softmax stays in floating point): Y_b = unmap(map(A)_b * op(map(Bm)_b)),
+ * b < batch <= 65535.  A[batch,M,K] fp32; Bm[batch,K,N], or [batch,N,K] with transB != 0 (keys: scores =
+ * Q K^T); Y[batch,M,N] fp32.  One scale per tensor; random streams FXP_TAG_X for A, FXP_TAG_W for Bm, element
+ * index = row-major index in the whole tensor.  Fills every member of *saved.  Full speed needs M, K, N
+ * multiples of 16 (pad the sequence length); other sizes take the slower general loads, same results.
+ * ws: fxp_workspace_bytes(FXP_OP_BMM_FWD, ...) bytes, 256-byte aligned. */
+int fxp_bmm_fwd(const float* A, const float* Bm, int64_t batch, int64_t M, int64_t K, int64_t N, int transB, float* Y,
+                const fxp_bmm_saved* saved, uint64_t seed, uint64_t step, int rounding, int bits, void* ws,
+                size_t ws_bytes, void* stream);
+
+/* Backward: dY[batch,M,N] is mapped once (FXP_TAG_DY; dYq [batch*M,N], dYqT [N,batch*M], e_dY returned);
+ * dA_b = unmap(G_b * op(Bq_b)^T) [batch,M,K]; dBm_b = unmap(Aq_b^T * G_b), in the layout of Bm.  dA or dBm may
+ * be NULL to skip it. */
+int fxp_bmm_bwd(const float* dY, const fxp_bmm_saved* saved, int64_t batch, int64_t M, int64_t K, int64_t N,
+                int transB, float* dA, float* dBm, int8_t* dYq, int8_t* dYqT, int32_t* e_dY, uint64_t seed,
+                uint64_t step, int rounding, int bits, void* ws, size_t ws_bytes, void* stream);
 
 /* ---- convolution layer (Sec. 3.4: "Linear and convolutional layers" share the integer inner product) ----
  * Channels-last tensors: X[N,H,W,C], W[Cout,KH,KW,C], Y and dY [N,Ho,Wo,Cout] with

@@ -30,6 +30,12 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 enum { kStoreI32 = 0, kStoreF32 = 1, kAtomicI32 = 2 };
 
+// batched product: `count` matrices, element strides between consecutive ones (grid.z)
+struct Batch {
+    unsigned count = 1;
+    int64_t a = 0, b = 0, c = 0;
+};
+
 template <int V>
 using IC = std::integral_constant<int, V>;
 
@@ -60,7 +66,8 @@ template <int BM, int BN, int BK, int WM, int WN, bool VEC, int MODE>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm_nt(
     const int8_t* __restrict__ A, int64_t lda, const int8_t* __restrict__ B, int64_t ldb, void* __restrict__ Cv,
     int64_t ldc, int M, int N, int K, int k_per_split, const int32_t* __restrict__ eA, int bitsA,
-    const int32_t* __restrict__ eB, int bitsB, int tiles_m, int tiles_n, int group_m, int64_t split_stride) {
+    const int32_t* __restrict__ eB, int bitsB, int tiles_m, int tiles_n, int group_m, int64_t split_stride,
+    int64_t batch_a, int64_t batch_b, int64_t batch_c) {
     constexpr int NT = (BM / WM) * (BN / WN) * 64;
     constexpr int CPR = BK / 16;
     constexpr int NA = BM * CPR / NT, NB = BN * CPR / NT;   // 16-byte pieces per thread per step
@@ -74,7 +81,10 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm_nt(
     const int m0 = tm * BM, n0 = tn * BN;
     const int kb = blockIdx.y * k_per_split;
     // split-K into a workspace: slice y owns its own M x N int32 matrix (split_stride elements apart)
-    Cv = static_cast<int32_t*>(Cv) + static_cast<int64_t>(blockIdx.y) * split_stride;
+    Cv = static_cast<int32_t*>(Cv) + static_cast<int64_t>(blockIdx.y) * split_stride + static_cast<int64_t>(blockIdx.z) * batch_c;
+    // batched product: matrix z of each operand lies batch_* elements further on
+    A += static_cast<int64_t>(blockIdx.z) * batch_a;
+    B += static_cast<int64_t>(blockIdx.z) * batch_b;
     const int ke = min(K, kb + k_per_split);
     const int nk = (ke - kb + BK - 1) / BK;
 
@@ -212,7 +222,8 @@ template <int BM, int BN, int BK, int WM, int WN, int STAGES, int MODE, bool SCH
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm_nt_dma(
     const int8_t* __restrict__ A, int64_t lda, const int8_t* __restrict__ B, int64_t ldb, void* __restrict__ Cv,
     int64_t ldc, int M, int N, int K, int k_per_split, const int32_t* __restrict__ eA, int bitsA,
-    const int32_t* __restrict__ eB, int bitsB, int tiles_m, int tiles_n, int group_m, int64_t split_stride) {
+    const int32_t* __restrict__ eB, int bitsB, int tiles_m, int tiles_n, int group_m, int64_t split_stride,
+    int64_t batch_a, int64_t batch_b, int64_t batch_c) {
     constexpr int NW = (BM / WM) * (BN / WN);
     constexpr int CPR = BK / 16;                     // 16-byte pieces per LDS row
     constexpr int RROWS = 64 / CPR;                  // tile rows per 1 KiB region
@@ -233,7 +244,10 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm_nt_dma(
     const int m0 = tm * BM, n0 = tn * BN;
     const int kb = blockIdx.y * k_per_split;
     // split-K into a workspace: slice y owns its own M x N int32 matrix (split_stride elements apart)
-    Cv = static_cast<int32_t*>(Cv) + static_cast<int64_t>(blockIdx.y) * split_stride;
+    Cv = static_cast<int32_t*>(Cv) + static_cast<int64_t>(blockIdx.y) * split_stride + static_cast<int64_t>(blockIdx.z) * batch_c;
+    // batched product: matrix z of each operand lies batch_* elements further on
+    A += static_cast<int64_t>(blockIdx.z) * batch_a;
+    B += static_cast<int64_t>(blockIdx.z) * batch_b;
     const int ke = min(K, kb + k_per_split);
     const int nk = (ke - kb) / BK;
 
@@ -394,7 +408,8 @@ template <int WM, int WN, int MODE, bool SCHED>
 __global__ __launch_bounds__((256 / WM) * (256 / WN) * 64) void k_gemm_nt_ring(
     const int8_t* __restrict__ A, int64_t lda, const int8_t* __restrict__ B, int64_t ldb, void* __restrict__ Cv,
     int64_t ldc, int M, int N, int K, int k_per_split, const int32_t* __restrict__ eA, int bitsA,
-    const int32_t* __restrict__ eB, int bitsB, int tiles_m, int tiles_n, int group_m, int64_t split_stride) {
+    const int32_t* __restrict__ eB, int bitsB, int tiles_m, int tiles_n, int group_m, int64_t split_stride,
+    int64_t batch_a, int64_t batch_b, int64_t batch_c) {
     constexpr int BM = 256, BN = 256, BK = 128;
     constexpr int NW = (BM / WM) * (BN / WN);
     constexpr int SLOT = 256 * BK;                   // bytes of a half-stage
@@ -409,7 +424,10 @@ __global__ __launch_bounds__((256 / WM) * (256 / WN) * 64) void k_gemm_nt_ring(
     const int m0 = tm * BM, n0 = tn * BN;
     const int kb = blockIdx.y * k_per_split;
     // split-K into a workspace: slice y owns its own M x N int32 matrix (split_stride elements apart)
-    Cv = static_cast<int32_t*>(Cv) + static_cast<int64_t>(blockIdx.y) * split_stride;
+    Cv = static_cast<int32_t*>(Cv) + static_cast<int64_t>(blockIdx.y) * split_stride + static_cast<int64_t>(blockIdx.z) * batch_c;
+    // batched product: matrix z of each operand lies batch_* elements further on
+    A += static_cast<int64_t>(blockIdx.z) * batch_a;
+    B += static_cast<int64_t>(blockIdx.z) * batch_b;
     const int ke = min(K, kb + k_per_split);
     const int nk = (ke - kb) / BK;
 
@@ -638,7 +656,8 @@ int transpose_i8_launch(const int8_t* src, int64_t rows, int64_t cols, int64_t l
 template <int BM, int BN, int BK, int WM, int WN>
 static int launch_cfg(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                       void* C, int64_t ldc, int mode, bool vec, int splits, const int32_t* eA, int bitsA,
-                      const int32_t* eB, int bitsB, hipStream_t s, int64_t split_stride = 0, int* slices = nullptr) {
+                      const int32_t* eB, int bitsB, hipStream_t s, int64_t split_stride = 0, int* slices = nullptr,
+                      Batch bt = Batch()) {
     constexpr int NT = (BM / WM) * (BN / WN) * 64;
     const int tiles_m = static_cast<int>((M + BM - 1) / BM), tiles_n = static_cast<int>((N + BN - 1) / BN);
     int k_per_split = static_cast<int>((K + splits - 1) / splits);
@@ -646,12 +665,12 @@ static int launch_cfg(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t 
     if (k_per_split == 0) k_per_split = BK;
     const int ny = K > 0 ? static_cast<int>((K + k_per_split - 1) / k_per_split) : 1;
     if (slices) *slices = ny;
-    const dim3 grid(static_cast<unsigned>(tiles_m) * tiles_n, ny), block(NT);
+    const dim3 grid(static_cast<unsigned>(tiles_m) * tiles_n, ny, bt.count), block(NT);
     const int group_m = 8;
 #define FXP_GEMM_LAUNCH(VEC, MODE)                                                                                 \
     hipLaunchKernelGGL((k_gemm_nt<BM, BN, BK, WM, WN, VEC, MODE>), grid, block, 0, s, A, lda, B, ldb, C, ldc,       \
                        static_cast<int>(M), static_cast<int>(N), static_cast<int>(K), k_per_split, eA, bitsA, eB,   \
-                       bitsB, tiles_m, tiles_n, group_m, split_stride)
+                       bitsB, tiles_m, tiles_n, group_m, split_stride, bt.a, bt.b, bt.c)
     if (vec) {
         if (mode == kStoreI32) FXP_GEMM_LAUNCH(true, kStoreI32);
         else if (mode == kStoreF32) FXP_GEMM_LAUNCH(true, kStoreF32);
@@ -668,19 +687,20 @@ static int launch_cfg(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t 
 template <int WM, int WN, bool SCHED = true>
 static int launch_ring(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                        void* C, int64_t ldc, int mode, int splits, const int32_t* eA, int bitsA, const int32_t* eB,
-                       int bitsB, hipStream_t s, int64_t split_stride = 0, int* slices = nullptr) {
+                       int bitsB, hipStream_t s, int64_t split_stride = 0, int* slices = nullptr,
+                      Batch bt = Batch()) {
     constexpr int NT = (256 / WM) * (256 / WN) * 64, BK = 128;
     const int tiles_m = static_cast<int>((M + 255) / 256), tiles_n = static_cast<int>((N + 255) / 256);
     int k_per_split = static_cast<int>((K + splits - 1) / splits);
     k_per_split = (k_per_split + BK - 1) / BK * BK;
     const int ny = static_cast<int>((K + k_per_split - 1) / k_per_split);
     if (slices) *slices = ny;
-    const dim3 grid(static_cast<unsigned>(tiles_m) * tiles_n, ny), block(NT);
+    const dim3 grid(static_cast<unsigned>(tiles_m) * tiles_n, ny, bt.count), block(NT);
     const int group_m = 8;
 #define FXP_GEMM_LAUNCH(MODE)                                                                                    \
     hipLaunchKernelGGL((k_gemm_nt_ring<WM, WN, MODE, SCHED>), grid, block, 0, s, A, lda, B, ldb, C, ldc,          \
                        static_cast<int>(M), static_cast<int>(N), static_cast<int>(K), k_per_split, eA, bitsA, eB, \
-                       bitsB, tiles_m, tiles_n, group_m, split_stride)
+                       bitsB, tiles_m, tiles_n, group_m, split_stride, bt.a, bt.b, bt.c)
     if (mode == kStoreI32) FXP_GEMM_LAUNCH(kStoreI32);
     else if (mode == kStoreF32) FXP_GEMM_LAUNCH(kStoreF32);
     else FXP_GEMM_LAUNCH(kAtomicI32);
@@ -691,20 +711,21 @@ static int launch_ring(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t
 template <int BM, int BN, int BK, int WM, int WN, int STAGES, bool SCHED = true>
 static int launch_dma(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                       void* C, int64_t ldc, int mode, int splits, const int32_t* eA, int bitsA, const int32_t* eB,
-                      int bitsB, hipStream_t s, int64_t split_stride = 0, int* slices = nullptr) {
+                      int bitsB, hipStream_t s, int64_t split_stride = 0, int* slices = nullptr,
+                      Batch bt = Batch()) {
     constexpr int NT = (BM / WM) * (BN / WN) * 64;
     const int tiles_m = static_cast<int>((M + BM - 1) / BM), tiles_n = static_cast<int>((N + BN - 1) / BN);
     int k_per_split = static_cast<int>((K + splits - 1) / splits);
     k_per_split = (k_per_split + BK - 1) / BK * BK;
     const int ny = static_cast<int>((K + k_per_split - 1) / k_per_split);
     if (slices) *slices = ny;
-    const dim3 grid(static_cast<unsigned>(tiles_m) * tiles_n, ny), block(NT);
+    const dim3 grid(static_cast<unsigned>(tiles_m) * tiles_n, ny, bt.count), block(NT);
     const int group_m = 8;
 #define FXP_GEMM_LAUNCH(MODE)                                                                                      \
     hipLaunchKernelGGL((k_gemm_nt_dma<BM, BN, BK, WM, WN, STAGES, MODE, SCHED>), grid, block, 0, s, A, lda, B, ldb, C, \
                        ldc,                                                                                        \
                        static_cast<int>(M), static_cast<int>(N), static_cast<int>(K), k_per_split, eA, bitsA, eB,   \
-                       bitsB, tiles_m, tiles_n, group_m, split_stride)
+                       bitsB, tiles_m, tiles_n, group_m, split_stride, bt.a, bt.b, bt.c)
     if (mode == kStoreI32) FXP_GEMM_LAUNCH(kStoreI32);
     else if (mode == kStoreF32) FXP_GEMM_LAUNCH(kStoreF32);
     else FXP_GEMM_LAUNCH(kAtomicI32);
@@ -791,6 +812,39 @@ size_t gemm_split_ws_bytes(int64_t M, int64_t N, int64_t K) {
 //     and applies the inverse mapping; without it the slices add into the zeroed output
 //     with int32 atomics (device-scope atomics are served at the memory side on this
 //     multi-die part, about 4x slower) and a pass converts in place.  Both are exact.
+int gemm_nt_batched_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, int64_t strideA,
+                           const int8_t* B, int64_t ldb, int64_t strideB, void* C, int64_t ldc, int64_t strideC,
+                           int64_t batch, bool fp32_out, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB,
+                           hipStream_t s) {
+    // the batch supplies the parallelism: no split along K, tiles chosen per matrix
+    if (M == 0 || N == 0 || batch == 0) return FXP_OK;
+    const bool vec = aligned(A, 16) && aligned(B, 16) && lda % 16 == 0 && ldb % 16 == 0 && K % 16 == 0 && strideA % 16 == 0 &&
+                     strideB % 16 == 0;
+    const bool dma = vec && K > 0 && K % 64 == 0;
+    const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
+    const bool use256 = M >= 256 && N >= 256 && t256 * batch >= 96;
+    const int mode = fp32_out ? kStoreF32 : kStoreI32;
+    Batch bt;
+    bt.count = static_cast<unsigned>(batch);
+    bt.a = strideA; bt.b = strideB; bt.c = strideC;
+#define FXP_BATCHED_ARGS M, N, K, A, lda, B, ldb, C, ldc, mode
+#define FXP_BATCHED_TAIL 1, eA, bitsA, eB, bitsB, s, 0, nullptr, bt
+    if (!dma) {
+        // narrow outputs (head width 64 of the attention context and of dQ, dK, dV) take a tile of their own width
+        if (N <= 64) return launch_cfg<128, 64, 64, 64, 32>(FXP_BATCHED_ARGS, vec, FXP_BATCHED_TAIL);
+        if (M <= 64) return launch_cfg<64, 128, 64, 32, 64>(FXP_BATCHED_ARGS, vec, FXP_BATCHED_TAIL);
+        return launch_cfg<128, 128, 64, 64, 64>(FXP_BATCHED_ARGS, vec, FXP_BATCHED_TAIL);
+    }
+    if (use256 && K % 128 == 0) return launch_ring<64, 128>(FXP_BATCHED_ARGS, FXP_BATCHED_TAIL);
+    if (use256) return launch_dma<256, 256, 64, 64, 128, 4>(FXP_BATCHED_ARGS, FXP_BATCHED_TAIL);
+    // one or two steps along K (scores = Q K^T with head width 64): two stages, more workgroups per CU
+    if (K <= 128) return launch_dma<128, 128, 64, 64, 64, 2>(FXP_BATCHED_ARGS, FXP_BATCHED_TAIL);
+    if (K % 128 == 0) return launch_dma<128, 128, 128, 64, 32, 4>(FXP_BATCHED_ARGS, FXP_BATCHED_TAIL);
+    return launch_dma<128, 128, 64, 64, 64, 4>(FXP_BATCHED_ARGS, FXP_BATCHED_TAIL);
+#undef FXP_BATCHED_ARGS
+#undef FXP_BATCHED_TAIL
+}
+
 int gemm_nt_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                    void* C, int64_t ldc, bool fp32_out, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB,
                    void* ws, size_t ws_bytes, hipStream_t s) {
@@ -904,4 +958,36 @@ extern "C" int fxp_gemm_unmap(int transA, int transB, int64_t M, int64_t N, int6
     if (bitsA < 2 || bitsA > 8 || (eB && (bitsB < 2 || bitsB > 8))) return FXP_ERR_BITS;
     return fxp::gemm_any(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, true, eA, bitsA, eB, bitsB, ws, ws_bytes,
                          static_cast<hipStream_t>(stream));
+}
+
+// Batched products for the attention matmuls (Q K^T and P V with per-tensor scales): `batch` independent
+// C_b[M,N] = A_b[M,K] * B_b[N,K]^T, matrices of one operand strideX elements apart.
+static int check_batched(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, int64_t strideA, const void* B,
+                         int64_t ldb, int64_t strideB, const void* C, int64_t ldc, int64_t strideC, int64_t batch) {
+    if (batch < 0 || batch > 65535 || strideA < 0 || strideB < 0 || strideC < 0) return FXP_ERR_DIMS;
+    int rc = fxp::check_gemm_args(M, N, K, A, lda, 0, B, ldb, 1, C, ldc);
+    if (rc) return rc;
+    if (batch > 1 && M * N > 0 && strideC < (M - 1) * ldc + N) return FXP_ERR_DIMS;   // outputs must not overlap
+    return FXP_OK;
+}
+
+extern "C" int fxp_gemm_batched(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, int64_t strideA,
+                                const int8_t* B, int64_t ldb, int64_t strideB, int32_t* C, int64_t ldc, int64_t strideC,
+                                int64_t batch, void* stream) {
+    int rc = check_batched(M, N, K, A, lda, strideA, B, ldb, strideB, C, ldc, strideC, batch);
+    if (rc) return rc;
+    return fxp::gemm_nt_batched_launch(M, N, K, A, lda, strideA, B, ldb, strideB, C, ldc, strideC, batch, false, nullptr, 8,
+                                       nullptr, 8, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int fxp_gemm_unmap_batched(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, int64_t strideA,
+                                      const int8_t* B, int64_t ldb, int64_t strideB, const int32_t* eA, int bitsA,
+                                      const int32_t* eB, int bitsB, float* C, int64_t ldc, int64_t strideC, int64_t batch,
+                                      void* stream) {
+    int rc = check_batched(M, N, K, A, lda, strideA, B, ldb, strideB, C, ldc, strideC, batch);
+    if (rc) return rc;
+    if (!eA) return FXP_ERR_NULL;
+    if (bitsA < 2 || bitsA > 8 || (eB && (bitsB < 2 || bitsB > 8))) return FXP_ERR_BITS;
+    return fxp::gemm_nt_batched_launch(M, N, K, A, lda, strideA, B, ldb, strideB, C, ldc, strideC, batch, true, eA, bitsA, eB,
+                                       bitsB, static_cast<hipStream_t>(stream));
 }

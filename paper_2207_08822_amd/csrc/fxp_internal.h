@@ -22,6 +22,10 @@ int scale_finish(const uint32_t* partials, int n_partials, int32_t* e_max, hipSt
 int map_launch(const float* x, int64_t rows, int64_t cols, const int32_t* e_in, const uint32_t* partials,
                int n_partials, int32_t* e_out, int8_t* q, int8_t* qT, uint64_t seed, uint64_t stream_id, int rounding,
                int bits, hipStream_t s);
+int gemm_nt_batched_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, int64_t strideA,
+                           const int8_t* B, int64_t ldb, int64_t strideB, void* C, int64_t ldc, int64_t strideC,
+                           int64_t batch, bool fp32_out, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB,
+                           hipStream_t s);
 int gemm_nt_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                    void* C, int64_t ldc, bool fp32_out, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB,
                    void* ws, size_t ws_bytes, hipStream_t s);

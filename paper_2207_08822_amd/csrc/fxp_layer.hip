@@ -52,6 +52,8 @@ extern "C" size_t fxp_workspace_bytes(int op, int64_t M, int64_t N, int64_t K) {
         case FXP_OP_LINEAR_BWD:   // the two gradient GEMMs run one after the other and share the slice area
             return fxp::round_up(fxp::kScaleWsBytes, 256) +
                    std::max(fxp::gemm_split_ws_bytes(M, K, N), fxp::gemm_split_ws_bytes(K, N, M));
+        case FXP_OP_BMM_FWD: return 2 * fxp::round_up(fxp::kScaleWsBytes, 256);
+        case FXP_OP_BMM_BWD: return fxp::round_up(fxp::kScaleWsBytes, 256);
         default: return 0;
     }
 }
@@ -101,5 +103,86 @@ extern "C" int fxp_linear_bwd(const float* dY, const fxp_saved* saved, int64_t M
     if (dW && (rc = gemm_nt_launch(K, N, M, saved->XqT, M, dYqT, M, dW, N, true, saved->eX, bits, e_dY, bits, rest,
                                    rest_bytes, s)))
         return rc;
+    return FXP_OK;
+}
+
+
+// Batched product layer (attention matmuls).  Every tensor is mapped once as a (batch * rows) x cols matrix in
+// both orientations; matrix b of a transposed copy is a column block of it, reached by a batch stride of
+// `rows` and a leading dimension of batch * rows (a per-matrix transposed layout was tried: its GEMMs read
+// faster but the mapping kernel's transposed stores lose their full 128-byte lines, a net loss):
+//   Y_b   = Aq_b [M,K]            x (Bq_b [N,K] | BqT cols b*K.. [N,K])^T
+//   dA_b  = Gq_b [M,N]            x (BqT cols b*N.. [K,N] | Bq_b [K,N])^T          (transB | not)
+//   dBm_b = AqT cols b*M.. [K,M]  x GqT cols b*M.. [N,M]^T   -> [K,N]              (operands swapped for transB)
+namespace fxp {
+static int check_bmm(int64_t batch, int64_t M, int64_t K, int64_t N, int rounding, int bits, const void* ws,
+                     size_t ws_bytes, size_t need) {
+    int rc = check_layer(M, K, N, rounding, bits, ws, ws_bytes, need);
+    if (rc) return rc;
+    if (batch <= 0 || batch > 65535) return FXP_ERR_DIMS;
+    const int64_t lim = int64_t{1} << 31;
+    if (batch * M >= lim || batch * K >= lim || batch * N >= lim) return FXP_ERR_DIMS;
+    return FXP_OK;
+}
+}  // namespace fxp
+
+extern "C" int fxp_bmm_fwd(const float* A, const float* Bm, int64_t batch, int64_t M, int64_t K, int64_t N, int transB,
+                           float* Y, const fxp_bmm_saved* saved, uint64_t seed, uint64_t step, int rounding, int bits,
+                           void* ws, size_t ws_bytes, void* stream) {
+    using namespace fxp;
+    int rc = check_bmm(batch, M, K, N, rounding, bits, ws, ws_bytes, fxp_workspace_bytes(FXP_OP_BMM_FWD, M, N, K));
+    if (rc) return rc;
+    if (K > kMaxContraction) return FXP_ERR_OVERFLOW;
+    if (!A || !Bm || !Y || !saved || !saved->Aq || !saved->AqT || !saved->Bq || !saved->BqT || !saved->eA || !saved->eB)
+        return FXP_ERR_NULL;
+    if (!aligned(A, 4) || !aligned(Bm, 4) || !aligned(Y, 4) || !aligned(saved->eA, 4) || !aligned(saved->eB, 4))
+        return FXP_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint32_t* pA = static_cast<uint32_t*>(ws);
+    uint32_t* pB = pA + round_up(kScaleWsBytes, 256) / sizeof(uint32_t);
+    const int64_t b_rows = transB ? N : K, b_cols = transB ? K : N;
+    if ((rc = scale_and_map(A, batch * M, K, saved->eA, saved->Aq, saved->AqT, seed, (step << 8) | FXP_TAG_X, rounding, bits,
+                            pA, s)))
+        return rc;
+    if ((rc = scale_and_map(Bm, batch * b_rows, b_cols, saved->eB, saved->Bq, saved->BqT, seed, (step << 8) | FXP_TAG_W,
+                            rounding, bits, pB, s)))
+        return rc;
+    const int8_t* Bop = transB ? saved->Bq : saved->BqT;
+    const int64_t ldb = transB ? K : batch * K, strideB = transB ? N * K : K;
+    return gemm_nt_batched_launch(M, N, K, saved->Aq, K, M * K, Bop, ldb, strideB, Y, N, M * N, batch, true, saved->eA, bits,
+                                  saved->eB, bits, s);
+}
+
+extern "C" int fxp_bmm_bwd(const float* dY, const fxp_bmm_saved* saved, int64_t batch, int64_t M, int64_t K, int64_t N,
+                           int transB, float* dA, float* dBm, int8_t* dYq, int8_t* dYqT, int32_t* e_dY, uint64_t seed,
+                           uint64_t step, int rounding, int bits, void* ws, size_t ws_bytes, void* stream) {
+    using namespace fxp;
+    int rc = check_bmm(batch, M, K, N, rounding, bits, ws, ws_bytes, fxp_workspace_bytes(FXP_OP_BMM_BWD, M, N, K));
+    if (rc) return rc;
+    if (N > kMaxContraction || M > kMaxContraction) return FXP_ERR_OVERFLOW;
+    if (!dY || !saved || !saved->AqT || !saved->Bq || !saved->BqT || !saved->eA || !saved->eB || !dYq || !dYqT || !e_dY)
+        return FXP_ERR_NULL;
+    if (!aligned(dY, 4) || !aligned(dA, 4) || !aligned(dBm, 4) || !aligned(e_dY, 4)) return FXP_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if ((rc = scale_and_map(dY, batch * M, N, e_dY, dYq, dYqT, seed, (step << 8) | FXP_TAG_DY, rounding, bits,
+                            static_cast<uint32_t*>(ws), s)))
+        return rc;
+    if (dA) {
+        const int8_t* Bop = transB ? saved->BqT : saved->Bq;      // [K,N] per matrix, N contiguous
+        const int64_t ldb = transB ? batch * N : N, strideB = transB ? N : K * N;
+        if ((rc = gemm_nt_batched_launch(M, K, N, dYq, N, M * N, Bop, ldb, strideB, dA, K, M * K, batch, true, e_dY, bits,
+                                         saved->eB, bits, s)))
+            return rc;
+    }
+    if (dBm) {
+        const int64_t ld = batch * M;                              // both operands are column blocks of a transposed copy
+        if (transB)
+            rc = gemm_nt_batched_launch(N, K, M, dYqT, ld, M, saved->AqT, ld, M, dBm, K, N * K, batch, true, e_dY, bits,
+                                        saved->eA, bits, s);
+        else
+            rc = gemm_nt_batched_launch(K, N, M, saved->AqT, ld, M, dYqT, ld, M, dBm, N, K * N, batch, true, saved->eA, bits,
+                                        e_dY, bits, s);
+        if (rc) return rc;
+    }
     return FXP_OK;
 }

@@ -20,7 +20,6 @@
 
 namespace fxp {
 
-constexpr int kTile = 128;
 constexpr int kMapThreads = 256;
 
 struct MapCfg {
@@ -111,34 +110,39 @@ __device__ inline int resolve_scale(const int32_t* e_in, const uint32_t* partial
     return e;
 }
 
-// One (32 * PASSES) x 128 tile (PASSES = 4 for large tensors, 1 when the tensor is too small to fill
-// the chip with 128-row tiles).  EDGE = the tile sticks out of the tensor: loads are clamped to valid
+// One tile of TC columns (128, or 64 for tensors whose width pads less that way: head width 64 of the
+// attention operands) and TR = 1024 / TC * 4 * PASSES rows: every thread owns 4 x 4 elements per pass, the 256
+// threads of a pass cover 32 x 128 or 64 x 64.  PASSES = 4 for large tensors, 1 when the tensor is too small to
+// fill the chip with the tall tiles.  EDGE = the tile sticks out of the tensor: loads are clamped to valid
 // addresses and stores are predicated; interior tiles carry no bounds code at all.  All
 // per-thread addressing is a 32-bit element offset from the tile's (wave-uniform) origin.
-template <bool STOCH, bool EDGE, int PASSES>
+template <bool STOCH, bool EDGE, int PASSES, int TC>
 __device__ inline void map_tile_body(const uint32_t* __restrict__ x, int64_t rows, int64_t cols, const MapCfg& cfg,
                                      int8_t* __restrict__ q, int8_t* __restrict__ qT, uint32_t key0, uint32_t key1,
                                      uint32_t sid0, uint32_t sid1, int64_t r0, int64_t c0, uint32_t* stage) {
-    constexpr int TR = 32 * PASSES;               // rows of the tile
-    constexpr int TS = 8 * PASSES + 1;            // dwords per staged column (TR row bytes + 4 pad)
+    constexpr int CG = TC / 4;                    // groups of 4 columns
+    constexpr int RGP = kMapThreads / CG;         // groups of 4 rows per pass
+    constexpr int TR = 4 * RGP * PASSES;          // rows of the tile
+    constexpr int TS = RGP * PASSES + 1;          // dwords per staged column (TR row bytes + 4 pad)
     const int tid = threadIdx.x;
-    const int cg = tid & 31;                      // group of 4 columns
+    const int cg = tid % CG;                      // group of 4 columns
+    const int rgl = tid / CG;                     // group of 4 rows within a pass
     const uint32_t ucols = static_cast<uint32_t>(cols);
     const int64_t origin = r0 * cols + c0;        // element index of the tile's first element (multiple of 4)
     const uint32_t* xt = x + origin;
     int8_t* qt = q ? q + origin : nullptr;
     const uint64_t blk0 = static_cast<uint64_t>(origin) >> 2;
     const int rows_here = EDGE ? static_cast<int>(min<int64_t>(TR, rows - r0)) : TR;
-    const int cols_here = EDGE ? static_cast<int>(min<int64_t>(kTile, cols - c0)) : kTile;
+    const int cols_here = EDGE ? static_cast<int>(min<int64_t>(TC, cols - c0)) : TC;
     const bool col_ok = !EDGE || 4 * cg < cols_here;
     const uint32_t col_ld = EDGE ? static_cast<uint32_t>(min(4 * cg, cols_here - 4)) : 4 * cg;
     const bool scale_ok = cfg.e_max >= 25 && cfg.e_max < 255;
     const uint32_t over_bit = cfg.sat + 1u;       // a fast-path result with this bit set needs saturation
 
-    // PASSES passes of 32 rows.  The loads of pass p+1 are issued before the arithmetic of pass
+    // PASSES passes of 4 * RGP rows.  The loads of pass p+1 are issued before the arithmetic of pass
     // p, so a block keeps the memory pipe busy while it runs its Philox rounds.
     auto load_pass = [&](int p, uint4 (&v)[4]) {
-        const int lrow = 4 * (p * 8 + (tid >> 5));
+        const int lrow = 4 * (p * RGP + rgl);
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const int rr = EDGE ? min(lrow + k, rows_here - 1) : lrow + k;
@@ -149,7 +153,7 @@ __device__ inline void map_tile_body(const uint32_t* __restrict__ x, int64_t row
     load_pass(0, cur);
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
-        const int rg = p * 8 + (tid >> 5);        // group of 4 rows
+        const int rg = p * RGP + rgl;              // group of 4 rows
         const int lrow = 4 * rg;
         if (p + 1 < PASSES) load_pass(p + 1, nxt);
         auto words_of = [&](int k) {
@@ -204,10 +208,10 @@ __device__ inline void map_tile_body(const uint32_t* __restrict__ x, int64_t row
         // 16 rows of one column = 16 contiguous bytes of qT
         constexpr int PIECES = TR / 16;                     // per column
 #pragma unroll
-        for (int it = 0; it < (kTile * PIECES + kMapThreads - 1) / kMapThreads; ++it) {
+        for (int it = 0; it < (TC * PIECES + kMapThreads - 1) / kMapThreads; ++it) {
             const int id = it * kMapThreads + tid;
             const int c = id / PIECES, ch = id % PIECES;
-            if (c < kTile && (!EDGE || (c < cols_here && 16 * ch < rows_here))) {
+            if (c < TC && (!EDGE || (c < cols_here && 16 * ch < rows_here))) {
                 const uint32_t* src = stage + c * TS + 4 * ch;
                 *reinterpret_cast<uint4*>(qTt + static_cast<uint64_t>(c) * urows + 16 * ch) =
                     make_uint4(src[0], src[1], src[2], src[3]);
@@ -215,7 +219,7 @@ __device__ inline void map_tile_body(const uint32_t* __restrict__ x, int64_t row
         }
     } else {
         const uint8_t* bytes = reinterpret_cast<const uint8_t*>(stage);
-        for (int id = tid; id < kTile * TR; id += kMapThreads) {
+        for (int id = tid; id < TC * TR; id += kMapThreads) {
             const int c = id / TR, r = id % TR;
             if (c < cols_here && r < rows_here)
                 qTt[static_cast<uint64_t>(c) * urows + r] = static_cast<int8_t>(bytes[c * TS * 4 + r]);
@@ -223,23 +227,24 @@ __device__ inline void map_tile_body(const uint32_t* __restrict__ x, int64_t row
     }
 }
 
-template <bool STOCH, int PASSES>
+template <bool STOCH, int PASSES, int TC>
 __global__ __launch_bounds__(kMapThreads) void k_map_tile(const uint32_t* __restrict__ x, int64_t rows, int64_t cols,
                                                           const int32_t* __restrict__ e_in,
                                                           const uint32_t* __restrict__ partials, int n_partials,
                                                           int32_t* __restrict__ e_out, int8_t* __restrict__ q,
                                                           int8_t* __restrict__ qT, uint32_t key0, uint32_t key1,
                                                           uint32_t sid0, uint32_t sid1, int bits, int tiles_c) {
-    constexpr int TR = 32 * PASSES;
-    __shared__ uint32_t stage[kTile * (8 * PASSES + 1)];
+    constexpr int RGP = kMapThreads / (TC / 4);
+    constexpr int TR = 4 * RGP * PASSES;
+    __shared__ uint32_t stage[TC * (RGP * PASSES + 1)];
     __shared__ uint32_t red[kMapThreads / 64];
     const MapCfg cfg = make_cfg(resolve_scale(e_in, partials, n_partials, e_out, red), bits);
     const int64_t r0 = static_cast<int64_t>(blockIdx.x / tiles_c) * TR;
-    const int64_t c0 = static_cast<int64_t>(blockIdx.x % tiles_c) * kTile;
-    if (r0 + TR <= rows && c0 + kTile <= cols)
-        map_tile_body<STOCH, false, PASSES>(x, rows, cols, cfg, q, qT, key0, key1, sid0, sid1, r0, c0, stage);
+    const int64_t c0 = static_cast<int64_t>(blockIdx.x % tiles_c) * TC;
+    if (r0 + TR <= rows && c0 + TC <= cols)
+        map_tile_body<STOCH, false, PASSES, TC>(x, rows, cols, cfg, q, qT, key0, key1, sid0, sid1, r0, c0, stage);
     else
-        map_tile_body<STOCH, true, PASSES>(x, rows, cols, cfg, q, qT, key0, key1, sid0, sid1, r0, c0, stage);
+        map_tile_body<STOCH, true, PASSES, TC>(x, rows, cols, cfg, q, qT, key0, key1, sid0, sid1, r0, c0, stage);
 }
 
 // One element per thread, any shape and alignment.
@@ -279,21 +284,29 @@ int map_launch(const float* x, int64_t rows, int64_t cols, const int32_t* e_in, 
     const uint32_t s0 = static_cast<uint32_t>(stream_id), s1 = static_cast<uint32_t>(stream_id >> 32);
     const uint32_t* xb = reinterpret_cast<const uint32_t*>(x);
     const bool stoch = rounding == FXP_ROUND_STOCHASTIC;
-    const int64_t tiles_c = (cols + kTile - 1) / kTile;
-    // 128-row tiles need about 2000 workgroups to fill the chip; smaller tensors take 32-row tiles
-    const bool small = ((rows + kTile - 1) / kTile) * tiles_c < 2048;
-    const int64_t tiles_r = small ? (rows + 31) / 32 : (rows + kTile - 1) / kTile;
+    // tile width: 64 when that pads the rows less than 128 does (cols = 64, 192, ...)
+    const int tc = ((cols + 63) / 64) * 64 < ((cols + 127) / 128) * 128 ? 64 : 128;
+    const int64_t tall = tc == 128 ? 128 : 256;   // rows of a 4-pass tile
+    const int64_t tiles_c = (cols + tc - 1) / tc;
+    // tall tiles need about 2000 workgroups to fill the chip; smaller tensors take single-pass tiles
+    const bool small = ((rows + tall - 1) / tall) * tiles_c < 2048;
+    const int64_t tr = small ? tall / 4 : tall;
+    const int64_t tiles_r = (rows + tr - 1) / tr;
     const bool tile_path = (cols % 4 == 0) && aligned(x, 16) && (!q || aligned(q, 16)) && (!qT || aligned(qT, 16)) &&
-                           tiles_r * tiles_c > 0 && tiles_r * tiles_c < (int64_t{1} << 31) && cols < (int64_t{1} << 24);   // 32-bit offsets inside a tile
+                           tiles_r * tiles_c > 0 && tiles_r * tiles_c < (int64_t{1} << 31) && cols < (int64_t{1} << 22);   // 32-bit offsets inside a tile
     if (tile_path) {
         const dim3 grid(static_cast<unsigned>(tiles_r * tiles_c)), block(kMapThreads);
-#define FXP_MAP_LAUNCH(STOCH, PASSES)                                                                                   \
-    hipLaunchKernelGGL((k_map_tile<STOCH, PASSES>), grid, block, 0, s, xb, rows, cols, e_in, partials, n_partials, e_out, q, \
-                       qT, k0, k1, s0, s1, bits, static_cast<int>(tiles_c))
-        if (stoch && small) FXP_MAP_LAUNCH(true, 1);
-        else if (stoch) FXP_MAP_LAUNCH(true, 4);
-        else if (small) FXP_MAP_LAUNCH(false, 1);
-        else FXP_MAP_LAUNCH(false, 4);
+#define FXP_MAP_LAUNCH(STOCH, PASSES, TC)                                                                                  \
+    hipLaunchKernelGGL((k_map_tile<STOCH, PASSES, TC>), grid, block, 0, s, xb, rows, cols, e_in, partials, n_partials, e_out, \
+                       q, qT, k0, k1, s0, s1, bits, static_cast<int>(tiles_c))
+#define FXP_MAP_PICK(TC)                           \
+    if (stoch && small) FXP_MAP_LAUNCH(true, 1, TC);  \
+    else if (stoch) FXP_MAP_LAUNCH(true, 4, TC);      \
+    else if (small) FXP_MAP_LAUNCH(false, 1, TC);     \
+    else FXP_MAP_LAUNCH(false, 4, TC)
+        if (tc == 128) { FXP_MAP_PICK(128); }
+        else { FXP_MAP_PICK(64); }
+#undef FXP_MAP_PICK
 #undef FXP_MAP_LAUNCH
     } else {
         const uint64_t n = static_cast<uint64_t>(rows) * static_cast<uint64_t>(cols);

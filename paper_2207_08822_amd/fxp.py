@@ -13,7 +13,7 @@ import torch
 from . import build as _build
 
 STOCHASTIC, NEAREST = 0, 1
-OP_SCALE, OP_GEMM, OP_LINEAR_FWD, OP_LINEAR_BWD = 0, 1, 2, 3
+OP_SCALE, OP_GEMM, OP_LINEAR_FWD, OP_LINEAR_BWD, OP_BMM_FWD, OP_BMM_BWD = 0, 1, 2, 3, 4, 5
 TAG_X, TAG_W, TAG_DY = 0, 1, 2
 
 
@@ -70,8 +70,14 @@ def lib():
                                  vp, sz, vp]
     L.fxp_conv2d_fwd.restype = ci
     L.fxp_conv2d_bwd.restype = ci
+    L.fxp_gemm_batched.argtypes = [i64, i64, i64, vp, i64, i64, vp, i64, i64, vp, i64, i64, i64, vp]
+    L.fxp_gemm_unmap_batched.argtypes = [i64, i64, i64, vp, i64, i64, vp, i64, i64, vp, ci, vp, ci, vp, i64, i64, i64, vp]
+    L.fxp_bmm_fwd.argtypes = [vp, vp, i64, i64, i64, i64, ci, vp, c.POINTER(_Saved), u64, u64, ci, ci, vp, sz, vp]
+    L.fxp_bmm_bwd.argtypes = [vp, c.POINTER(_Saved), i64, i64, i64, i64, ci, vp, vp, vp, vp, vp, u64, u64, ci, ci, vp, sz,
+                              vp]
     for name in ("fxp_scale", "fxp_map", "fxp_scale_map", "fxp_gemm", "fxp_unmap", "fxp_unmap_i8", "fxp_gemm_unmap",
-                 "fxp_linear_fwd", "fxp_linear_bwd"):
+                 "fxp_linear_fwd", "fxp_linear_bwd", "fxp_gemm_batched", "fxp_gemm_unmap_batched", "fxp_bmm_fwd",
+                 "fxp_bmm_bwd"):
         getattr(L, name).restype = ci
     _lib = L
     return L
@@ -242,6 +248,70 @@ def linear_bwd(dY, buf, seed=0, step=0, rounding=STOCHASTIC, bits=8, need_dX=Tru
                                 _p(buf.dYqT), buf.e[2:3].data_ptr(), seed, step, rounding, bits, _p(buf.ws),
                                 buf.ws.numel(), _stream()), "fxp_linear_bwd")
     return dX, dW
+
+
+def gemm_batched(A, B, eA=None, eB=None, bitsA=8, bitsB=8):
+    """C_b = A_b[M,K] B_b[N,K]^T for dense int8 A[batch,M,K], B[batch,N,K]: int32, or fp32 through the fused
+    inverse mapping when the scales eA (and eB) are given."""
+    A, B = _dev(A, torch.int8, "A"), _dev(B, torch.int8, "B")
+    if A.dim() != 3 or B.dim() != 3 or A.shape[0] != B.shape[0] or A.shape[2] != B.shape[2]:
+        raise FxpError("gemm_batched wants A[batch,M,K] and B[batch,N,K]")
+    batch, M, K = A.shape
+    N = B.shape[1]
+    if eA is None:
+        C = torch.empty((batch, M, N), dtype=torch.int32, device=A.device)
+        _check(lib().fxp_gemm_batched(M, N, K, _p(A), K, M * K, _p(B), K, N * K, _p(C), N, M * N, batch, _stream()),
+               "fxp_gemm_batched")
+    else:
+        C = torch.empty((batch, M, N), dtype=torch.float32, device=A.device)
+        _check(lib().fxp_gemm_unmap_batched(M, N, K, _p(A), K, M * K, _p(B), K, N * K, _p(eA), bitsA, _p(eB), bitsB, _p(C),
+                                            N, M * N, batch, _stream()), "fxp_gemm_unmap_batched")
+    return C
+
+
+class BmmBuffers:
+    """Caller-owned device buffers of one batched product layer (attention matmul), allocated once."""
+
+    def __init__(self, batch, M, K, N, transB=False, device="cuda"):
+        i8 = dict(dtype=torch.int8, device=device)
+        f32 = dict(dtype=torch.float32, device=device)
+        self.batch, self.M, self.K, self.N, self.transB = batch, M, K, N, bool(transB)
+        b_shape = (batch, N, K) if transB else (batch, K, N)
+        self.Aq, self.AqT = torch.empty((batch, M, K), **i8), torch.empty((K, batch * M), **i8)
+        self.Bq, self.BqT = torch.empty(b_shape, **i8), torch.empty((b_shape[2], batch * b_shape[1]), **i8)
+        self.dYq, self.dYqT = torch.empty((batch, M, N), **i8), torch.empty((N, batch * M), **i8)
+        self.e = torch.zeros(3, dtype=torch.int32, device=device)       # eA, eB, e_dY
+        self.Y = torch.empty((batch, M, N), **f32)
+        self.dA = torch.empty((batch, M, K), **f32)
+        self.dB = torch.empty(b_shape, **f32)
+        nbytes = max(workspace_bytes(OP_BMM_FWD, M, N, K), workspace_bytes(OP_BMM_BWD, M, N, K), 256)
+        self.ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        self.saved = _Saved(_p(self.Aq), _p(self.AqT), _p(self.Bq), _p(self.BqT), self.e[0:1].data_ptr(),
+                            self.e[1:2].data_ptr())
+
+
+def bmm_fwd(A, Bm, buf, seed=0, step=0, rounding=STOCHASTIC, bits=8):
+    """Y_b = unmap(map(A)_b op(map(Bm)_b)); fills buf.Aq/AqT/Bq/BqT/e[0:2] and returns buf.Y."""
+    A, Bm = _dev(A, torch.float32, "A"), _dev(Bm, torch.float32, "Bm")
+    if tuple(A.shape) != tuple(buf.Aq.shape) or tuple(Bm.shape) != tuple(buf.Bq.shape):
+        raise FxpError("shapes do not match the layer buffers")
+    _check(lib().fxp_bmm_fwd(_p(A), _p(Bm), buf.batch, buf.M, buf.K, buf.N, int(buf.transB), _p(buf.Y),
+                             ctypes.byref(buf.saved), seed, step, rounding, bits, _p(buf.ws), buf.ws.numel(), _stream()),
+           "fxp_bmm_fwd")
+    return buf.Y
+
+
+def bmm_bwd(dY, buf, seed=0, step=0, rounding=STOCHASTIC, bits=8, need_dA=True, need_dB=True):
+    """(dA, dBm) from the upstream gradient and the operands the forward call saved."""
+    dY = _dev(dY, torch.float32, "dY")
+    if tuple(dY.shape) != (buf.batch, buf.M, buf.N):
+        raise FxpError("shapes do not match the layer buffers")
+    dA = buf.dA if need_dA else None
+    dB = buf.dB if need_dB else None
+    _check(lib().fxp_bmm_bwd(_p(dY), ctypes.byref(buf.saved), buf.batch, buf.M, buf.K, buf.N, int(buf.transB), _p(dA),
+                             _p(dB), _p(buf.dYq), _p(buf.dYqT), buf.e[2:3].data_ptr(), seed, step, rounding, bits,
+                             _p(buf.ws), buf.ws.numel(), _stream()), "fxp_bmm_bwd")
+    return dA, dB
 
 
 class ConvBuffers:

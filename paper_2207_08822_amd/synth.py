@@ -131,3 +131,30 @@ def conv_tensors(seed=1, N=None, H=None, W=None, C=None, Cout=None, KH=3, KW=3, 
     Ho, Wo = (g["H"] + 2 * pad - KH) // stride + 1, (g["W"] + 2 * pad - KW) // stride + 1
     dY = _normal(rng, (g["N"], Ho, Wo, g["Cout"]), 1e-3)
     return X, Wt, dY, g
+
+
+# The two attention products of one ViT-B/16 encoder block at batch 64: 64 x 12 heads, 197 tokens padded to
+# 208 (a multiple of 16; the padding rows are zero), head width 64.
+VITB_ATTN = dict(batch=768, S=208, S_real=197, d=64)
+
+
+def attention_tensors(seed=1, batch=None, S=None, S_real=None, d=None):
+    """fp32 inputs of the attention products: Q, K, V [batch,S,d] ~ N(0,1) with rows >= S_real zero,
+    P [batch,S,S] = row softmax of Q K^T / sqrt(d) over the real tokens (zero elsewhere), and N(0, 1e-3)
+    upstream gradients dS [batch,S,S] (of the scores) and dO [batch,S,d] (of the context)."""
+    g = dict(VITB_ATTN)
+    for k, v in dict(batch=batch, S=S, S_real=S_real, d=d).items():
+        if v is not None:
+            g[k] = v
+    b, s, r, dd = g["batch"], g["S"], g["S_real"], g["d"]
+    rng = np.random.Generator(np.random.PCG64([seed, 78]))
+    Q, K, V = (_normal(rng, (b, s, dd), 1.0) for _ in range(3))
+    for t in (Q, K, V):
+        t[:, r:, :] = 0.0
+    z = np.matmul(Q[:, :r], K[:, :r].transpose(0, 2, 1)) / np.float32(np.sqrt(dd))
+    z = np.exp(z - z.max(axis=2, keepdims=True))
+    P = np.zeros((b, s, s), dtype=np.float32)
+    P[:, :r, :r] = z / z.sum(axis=2, keepdims=True)
+    dS = _normal(rng, (b, s, s), 1e-3)
+    dO = _normal(rng, (b, s, dd), 1e-3)
+    return dict(Q=Q, K=K, V=V, P=P, dS=dS, dO=dO), g
