@@ -43,6 +43,9 @@ def lib():
         L.fxp_ref_bmm_fwd.argtypes = [vp, vp, i64, i64, i64, i64, c.c_int, vp, vp, vp, vp, vp, u64, u64, c.c_int, c.c_int]
         L.fxp_ref_bmm_bwd.argtypes = [vp, vp, vp, i32, i32, i64, i64, i64, i64, c.c_int, vp, vp, vp, vp, u64, u64, c.c_int,
                                       c.c_int]
+        L.fxp_ref_map16.argtypes = [vp, u64, i32, vp, u64, u64, c.c_int]
+        L.fxp_ref_axpy16.argtypes = [vp, vp, c.c_float, u64, vp, vp, u64, u64, c.c_int]
+        L.fxp_ref_sgd16_step.argtypes = [vp, vp, vp, u64, c.c_float, c.c_float, c.c_float, vp, u64, u64, c.c_int]
         L.fxp_ref_conv2d_fwd_acc.argtypes = [vp, i64, i64, i64, i64, vp, i64, i64, i64, i64, i64, vp]
         L.fxp_ref_conv2d_bwd_input_acc.argtypes = [vp, vp] + cd + [vp]
         L.fxp_ref_conv2d_bwd_weight_acc.argtypes = [vp, vp] + cd + [vp]
@@ -274,3 +277,34 @@ def bmm_bwd(dY, saved, seed=0, step=0, rounding=STOCHASTIC, bits=8, need_dA=True
                                  int(saved["transB"]), _ptr(dA), _ptr(dB), _ptr(dYq), _ptr(eG), seed, step, rounding,
                                  bits), "bmm_bwd")
     return dA, dB, dict(dYq=dYq, eG=int(eG[0]))
+
+
+# ---- int16 weight update (Remark 5, App. A.4) ------------------------------------------------------------
+TAG_AXPY_X, TAG_AXPY_Y, TAG_AXPY_A, TAG_AXPY_U = 3, 4, 5, 6
+
+
+def map16(x, e_max, seed=0, stream_id=0, rounding=STOCHASTIC):
+    x = _f32(x)
+    q = np.empty(x.shape, dtype=np.int16)
+    _check(lib().fxp_ref_map16(_ptr(x), x.size, int(e_max), _ptr(q), seed, stream_id, rounding), "map16")
+    return q
+
+
+def axpy16(x, y, a, seed=0, step=0, rounding=STOCHASTIC):
+    """z = x_hat + SR(a_hat * y_hat) in 16-bit fixed point; returns z (fp32) and the scales (eX, eY, eA)."""
+    x, y = _f32(x), _f32(y)
+    assert x.shape == y.shape
+    z = np.empty(x.shape, dtype=np.float32)
+    e = np.zeros(3, dtype=np.int32)
+    _check(lib().fxp_ref_axpy16(_ptr(x), _ptr(y), float(a), x.size, _ptr(z), _ptr(e), seed, step, rounding), "axpy16")
+    return z, tuple(int(v) for v in e)
+
+
+def sgd16_step(w, g, v=None, lr=0.1, momentum=0.0, weight_decay=0.0, seed=0, step=0, rounding=STOCHASTIC):
+    """Returns (w_new, v_new); the inputs are left untouched."""
+    w, g = _f32(w).copy(), _f32(g)
+    v = _f32(v).copy() if v is not None else (np.zeros_like(w) if momentum != 0.0 else None)
+    tmp = np.empty_like(w) if weight_decay != 0.0 else None
+    _check(lib().fxp_ref_sgd16_step(_ptr(w), _ptr(g), _ptr(v), w.size, float(lr), float(momentum), float(weight_decay),
+                                    _ptr(tmp), seed, step, rounding), "sgd16_step")
+    return w, v

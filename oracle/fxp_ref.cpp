@@ -18,6 +18,8 @@
 //            packed fp32.
 //   linear — App. A.2: Y = X W, dL/dW = X^T G, and dL/dX = G W^T (chain rule).
 //   conv   — Sec. 3.4: the same inner products with the convolution's index pattern.
+//   bmm    — Sec. 5 (vision transformer): the attention products Q K^T and A V, one product per head.
+//   sgd16  — Remark 5 + App. A.4: w_hat + alpha_hat * g_hat with int16 mantissas (parity unpinned, below).
 // Random numbers: the paper only says they are generated on the fly; this
 // build fixes Philox-4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11), keyed by the
 // seed, with the tensor's stream id and the element index as the counter.
@@ -28,7 +30,12 @@
 // 10^7-sample mean-error and closed-form variance tests, and, for the Philox
 // rounds, rocRAND's host-callable engine (an independent implementation of the
 // same published generator; the authors' known-answer vectors themselves are
-// not available offline).  No function is "parity unpinned".
+// not available offline).
+// PARITY UNPINNED: axpy16 / sgd16.  The paper states the integer update only as w_hat + alpha_hat * g_hat with
+// stochastic rounding (App. A.4) and gives neither the alignment of the two terms nor the place of the
+// rounding; the formula below is this build's reading.  Its tests check what the paper does fix (the operands
+// are the int16 instance of the map; the update is unbiased; representable operands give the exact result) but
+// cannot show that another reading was not meant.
 //
 // Build: g++ -O2 -fopenmp -shared -fPIC (see oracle/build.py).  OpenMP only
 // splits independent outer loops; results do not depend on the thread count.
@@ -505,6 +512,107 @@ int fxp_ref_bmm_bwd(const float* dY, const int8_t* Aq, const int8_t* Bq, int32_t
         if (rc) return rc;
     }
     return 0;
+}
+
+// ---- int16 weight update (Remark 5, App. A.4: w_hat_{k+1} = w_hat_k + alpha_hat_k * g_hat) ----------------
+// One fixed-point "a times y plus x": z = x_hat + SR(a_hat * y_hat), every operand the 16-bit instance of the
+// map of Sec. 3.1 (15 magnitude bits: the 24-bit mantissa rounded stochastically with its low 9 bits).
+//   x_hat, y_hat : tensors, scales e_x, e_y, units 2^Ex, 2^Ey with E = e_max - 127 - 14
+//   a_hat        : the scalar mapped like a one-element tensor (its own exponent is its scale), unit 2^Ea
+//   p_i = a_hat * y_hat_i          exact in int32, unit 2^(Ea + Ey)
+//   u_i = p_i brought to the unit of x_hat: shifted left when Ea + Ey >= Ex, else shifted right by
+//         s = Ex - (Ea + Ey) bits with stochastic rounding of the magnitude: up with probability
+//         (dropped bits) / 2^s, decided by word < floor((dropped bits) * 2^32 / 2^s); |u_i| saturates at
+//         2^23 - 2^15 so that the sum below stays an exact fp32 mantissa
+//   z_i = (x_hat_i + u_i) * 2^Ex   through the inverse mapping of Sec. 3.2
+// Random streams (step << 8) | tag: x 3, y 4, a 5 (element 0), rounding of u 6.  rounding = 1 replaces every
+// stochastic rounding by round-half-up on the magnitude.
+static const uint64_t kTagAxpyX = 3, kTagAxpyY = 4, kTagAxpyA = 5, kTagAxpyU = 6;
+static const int64_t kAxpyUpdateSat = (int64_t{1} << 23) - (int64_t{1} << 15);
+
+static int64_t axpy_update(int32_t p, int32_t s, uint32_t word, int rounding) {
+    const bool neg = p < 0;
+    const uint64_t m = static_cast<uint64_t>(neg ? -static_cast<int64_t>(p) : static_cast<int64_t>(p));   // < 2^30
+    uint64_t u;
+    if (s <= 0) {
+        u = (-s >= 24) ? (m ? static_cast<uint64_t>(kAxpyUpdateSat) : 0u) : (m << -s);
+    } else if (s >= 63) {
+        u = 0;                                        // below 2^-33 of a unit: never rounds up
+    } else {
+        const uint64_t kept = m >> s;
+        const uint64_t dropped = m & ((uint64_t{1} << s) - 1u);
+        uint64_t up;
+        if (rounding == 0) {
+            // dropped < 2^30: dropped * 2^32 fits 64 bits
+            const uint64_t threshold = (dropped << 32) >> s;       // floor(dropped * 2^32 / 2^s)
+            up = (static_cast<uint64_t>(word) < threshold) ? 1u : 0u;
+        } else {
+            up = (dropped >> (s - 1)) & 1u;                        // half up
+        }
+        u = kept + up;
+    }
+    if (u > static_cast<uint64_t>(kAxpyUpdateSat)) u = static_cast<uint64_t>(kAxpyUpdateSat);
+    return neg ? -static_cast<int64_t>(u) : static_cast<int64_t>(u);
+}
+
+// int16 instance of the map for a flat tensor
+int fxp_ref_map16(const float* x, uint64_t n, int32_t e_max, int16_t* q, uint64_t seed, uint64_t stream_id, int rounding) {
+    if (n && (!x || !q)) return -1;
+    if (rounding < 0 || rounding > 1) return -2;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < static_cast<int64_t>(n); ++i)
+        q[i] = static_cast<int16_t>(map_one(x[i], e_max, random_word(seed, stream_id, static_cast<uint64_t>(i)), rounding, 16));
+    return 0;
+}
+
+// z = x + a * y in 16-bit fixed point (see above).  e_out[0..2] receive the scales of x, y and a.
+int fxp_ref_axpy16(const float* x, const float* y, float a, uint64_t n, float* z, int32_t* e_out, uint64_t seed,
+                   uint64_t step, int rounding) {
+    if (n && (!x || !y || !z)) return -1;
+    if (rounding < 0 || rounding > 1) return -2;
+    int32_t ex, ey, ea;
+    int rc;
+    if ((rc = fxp_ref_scale(x, n, &ex))) return rc;
+    if ((rc = fxp_ref_scale(y, n, &ey))) return rc;
+    if ((rc = fxp_ref_scale(&a, 1, &ea))) return rc;
+    if (e_out) { e_out[0] = ex; e_out[1] = ey; e_out[2] = ea; }
+    const int32_t a_hat = map_one(a, ea, random_word(seed, (step << 8) | kTagAxpyA, 0), rounding, 16);
+    const int32_t Ex = lsb_exponent(ex, 16), Ey = lsb_exponent(ey, 16), Ea = lsb_exponent(ea, 16);
+    const int32_t s = Ex - (Ea + Ey);
+#pragma omp parallel for schedule(static)
+    for (int64_t k = 0; k < static_cast<int64_t>(n); ++k) {
+        const uint64_t i = static_cast<uint64_t>(k);
+        const int32_t x_hat = map_one(x[i], ex, random_word(seed, (step << 8) | kTagAxpyX, i), rounding, 16);
+        const int32_t y_hat = map_one(y[i], ey, random_word(seed, (step << 8) | kTagAxpyY, i), rounding, 16);
+        const int32_t p = a_hat * y_hat;
+        const int64_t r = static_cast<int64_t>(x_hat) + axpy_update(p, s, random_word(seed, (step << 8) | kTagAxpyU, i), rounding);
+        z[i] = static_cast<float>(std::ldexp(static_cast<double>(r), Ex));
+    }
+    return 0;
+}
+
+// One SGD step with weight decay and momentum (the optimiser of the paper's classification runs, App. A.5:
+// momentum 0.9), every line an axpy16:   g1 = g + wd * w;   v = g1 + momentum * v;   w = w + (-lr) * v.
+// wd == 0 skips the first line (g1 = g), momentum == 0 the second (v is not touched, the update uses g1).
+// tmp: n floats of scratch (may be NULL when wd == 0).  The three lines use steps 3*step, 3*step+1, 3*step+2
+// of the random streams.
+int fxp_ref_sgd16_step(float* w, const float* g, float* v, uint64_t n, float lr, float momentum, float wd, float* tmp,
+                       uint64_t seed, uint64_t step, int rounding) {
+    if (n && (!w || !g)) return -1;
+    if (momentum != 0.0f && n && !v) return -1;
+    if (wd != 0.0f && n && !tmp) return -1;
+    int rc;
+    const float* g1 = g;
+    if (wd != 0.0f) {
+        if ((rc = fxp_ref_axpy16(g, w, wd, n, tmp, nullptr, seed, 3 * step, rounding))) return rc;
+        g1 = tmp;
+    }
+    const float* d = g1;
+    if (momentum != 0.0f) {
+        if ((rc = fxp_ref_axpy16(g1, v, momentum, n, v, nullptr, seed, 3 * step + 1, rounding))) return rc;
+        d = v;
+    }
+    return fxp_ref_axpy16(w, d, -lr, n, w, nullptr, seed, 3 * step + 2, rounding);
 }
 
 }  // extern "C"
