@@ -280,7 +280,7 @@ def bmm_bwd(dY, saved, seed=0, step=0, rounding=STOCHASTIC, bits=8, need_dA=True
 
 
 # ---- int16 weight update (Remark 5, App. A.4) ------------------------------------------------------------
-TAG_AXPY_X, TAG_AXPY_Y, TAG_AXPY_A, TAG_AXPY_U = 3, 4, 5, 6
+TAG_AXPY_XY, TAG_AXPY_U, TAG_AXPY_A = 3, 4, 5
 
 
 def map16(x, e_max, seed=0, stream_id=0, rounding=STOCHASTIC):

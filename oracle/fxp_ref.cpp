@@ -525,9 +525,11 @@ int fxp_ref_bmm_bwd(const float* dY, const int8_t* Aq, const int8_t* Bq, int32_t
 //         (dropped bits) / 2^s, decided by word < floor((dropped bits) * 2^32 / 2^s); |u_i| saturates at
 //         2^23 - 2^15 so that the sum below stays an exact fp32 mantissa
 //   z_i = (x_hat_i + u_i) * 2^Ex   through the inverse mapping of Sec. 3.2
-// Random streams (step << 8) | tag: x 3, y 4, a 5 (element 0), rounding of u 6.  rounding = 1 replaces every
-// stochastic rounding by round-half-up on the magnitude.
-static const uint64_t kTagAxpyX = 3, kTagAxpyY = 4, kTagAxpyA = 5, kTagAxpyU = 6;
+// Random numbers, streams (step << 8) | tag: element i of x and of y round with two disjoint 9-bit fields of
+// ONE word (tag 3: bits 31..23 for x, bits 22..14 for y), the update u_i with the full 32-bit word of tag 4,
+// the scalar with the top 9 bits of word 0 of tag 5.  rounding = 1 replaces every stochastic rounding by
+// round-half-up on the magnitude.
+static const uint64_t kTagAxpyXY = 3, kTagAxpyU = 4, kTagAxpyA = 5;
 static const int64_t kAxpyUpdateSat = (int64_t{1} << 23) - (int64_t{1} << 15);
 
 static int64_t axpy_update(int32_t p, int32_t s, uint32_t word, int rounding) {
@@ -582,8 +584,9 @@ int fxp_ref_axpy16(const float* x, const float* y, float a, uint64_t n, float* z
 #pragma omp parallel for schedule(static)
     for (int64_t k = 0; k < static_cast<int64_t>(n); ++k) {
         const uint64_t i = static_cast<uint64_t>(k);
-        const int32_t x_hat = map_one(x[i], ex, random_word(seed, (step << 8) | kTagAxpyX, i), rounding, 16);
-        const int32_t y_hat = map_one(y[i], ey, random_word(seed, (step << 8) | kTagAxpyY, i), rounding, 16);
+        const uint32_t word_xy = random_word(seed, (step << 8) | kTagAxpyXY, i);
+        const int32_t x_hat = map_one(x[i], ex, word_xy, rounding, 16);        // compares bits 31..23
+        const int32_t y_hat = map_one(y[i], ey, word_xy << 9, rounding, 16);   // compares bits 22..14
         const int32_t p = a_hat * y_hat;
         const int64_t r = static_cast<int64_t>(x_hat) + axpy_update(p, s, random_word(seed, (step << 8) | kTagAxpyU, i), rounding);
         z[i] = static_cast<float>(std::ldexp(static_cast<double>(r), Ex));

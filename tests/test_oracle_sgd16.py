@@ -33,20 +33,29 @@ def test_map16_is_the_16_bit_instance_of_the_map():
     assert np.max(np.abs(q * 2.0 ** (e - 127 - 14) - w.astype(np.float64))) <= 2.0 ** (e - 127 - 14)
 
 
+def model_map16(x, e_max, r9):
+    """Exact-rational 16-bit map of a finite float with the 9-bit random number r9."""
+    fl, low, cut = pm.floor_and_prob(x, e_max, 16)
+    assert cut == 9
+    q = min(fl + (1 if r9 < low else 0), 32767)
+    return -q if (pm.f32_bits(x) >> 31) else q
+
+
 def model_axpy(x, y, a, seed, step):
     """Exact-rational model of z = x_hat + SR(a_hat y_hat) from the definition of the format."""
     ex, ey, ea = oracle.scale(x), oracle.scale(y), oracle.scale(np.float32([a]))
     Ex, Ey, Ea = (pm.lsb_exponent(e, 16) for e in (ex, ey, ea))
-    a_hat = pm.map_one(float(np.float32(a)), ea, seed, (step << 8) | 5, 0, bits=16)
+    a_hat = model_map16(float(np.float32(a)), ea, pm.random_word(seed, (step << 8) | 5, 0) >> 23)
     out = np.empty(x.size, dtype=np.uint32)
     for i in range(x.size):
-        x_hat = pm.map_one(float(x[i]), ex, seed, (step << 8) | 3, i, bits=16)
-        y_hat = pm.map_one(float(y[i]), ey, seed, (step << 8) | 4, i, bits=16)
+        word = pm.random_word(seed, (step << 8) | 3, i)          # one word, two 9-bit fields
+        x_hat = model_map16(float(x[i]), ex, word >> 23)
+        y_hat = model_map16(float(y[i]), ey, (word >> 14) & 511)
         t = Fraction(a_hat * y_hat) * pm.pow2(Ea + Ey) / pm.pow2(Ex)       # update in units of x_hat
         mag = abs(t)
         fl = mag.numerator // mag.denominator
         thr = ((mag - fl) * (1 << 32)).numerator // ((mag - fl) * (1 << 32)).denominator
-        u = fl + (1 if pm.random_word(seed, (step << 8) | 6, i) < thr else 0)
+        u = fl + (1 if pm.random_word(seed, (step << 8) | 4, i) < thr else 0)
         u = min(u, (1 << 23) - (1 << 15))
         r = x_hat + (-u if t < 0 else u)
         out[i] = pm.round_to_f32(Fraction(r) * pm.pow2(Ex))
