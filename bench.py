@@ -32,7 +32,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "c2conv", "vitb_attn"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "c2conv", "vitb_attn", "sgd16"])
     ap.add_argument("--sigma", type=float, default=1.0, help="c5 only")
     ap.add_argument("--bits", type=int, default=8, help="width of the fixed-point values (8 = the paper's int8; 4..7 = its ablation)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -87,11 +87,16 @@ def bench_conv(args, torch, fxp, synth, dev):
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        rows = 4
-        t = time.perf_counter()
-        _, sv = oracle.conv2d_fwd(X[:rows], Wt, g["stride"], g["pad"], 0, 0)
-        oracle.conv2d_bwd(dY[:rows], sv, 0, 0)
-        dt = time.perf_counter() - t
+
+        def run(rows):
+            t = time.perf_counter()
+            _, sv = oracle.conv2d_fwd(X[:rows], Wt, g["stride"], g["pad"], 0, 0)
+            oracle.conv2d_bwd(dY[:rows], sv, 0, 0)
+            return time.perf_counter() - t
+
+        per_image = run(1)      # one image first, to size the sample to about --cpu-seconds of CPU work
+        rows = int(max(1, min(g["N"], args.cpu_seconds / max(per_image, 1e-9))))
+        dt = run(rows)
         cpu = dict(value=round(ops * rows / g["N"] / dt / 1e12, 6), unit="TOPS", cores=oracle.num_threads(), kind="oracle",
                    seconds=round(dt, 2), sample=f"first {rows} of {g['N']} images, fwd+bwd")
     print(json.dumps({
@@ -143,13 +148,18 @@ def bench_attn(args, torch, fxp, synth, dev):
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        nb = 16
-        tt = time.perf_counter()
-        _, sv = oracle.bmm_fwd(t["Q"][:nb], t["K"][:nb], True, 0, 0)
-        oracle.bmm_bwd(t["dS"][:nb], sv, 0, 0)
-        _, sv = oracle.bmm_fwd(t["P"][:nb], t["V"][:nb], False, 0, 0)
-        oracle.bmm_bwd(t["dO"][:nb], sv, 0, 0)
-        dt = time.perf_counter() - tt
+
+        def run(nb):
+            tt = time.perf_counter()
+            _, sv = oracle.bmm_fwd(t["Q"][:nb], t["K"][:nb], True, 0, 0)
+            oracle.bmm_bwd(t["dS"][:nb], sv, 0, 0)
+            _, sv = oracle.bmm_fwd(t["P"][:nb], t["V"][:nb], False, 0, 0)
+            oracle.bmm_bwd(t["dO"][:nb], sv, 0, 0)
+            return time.perf_counter() - tt
+
+        per_head = run(8) / 8   # a few heads first, to size the sample to about --cpu-seconds of CPU work
+        nb = int(max(8, min(b, args.cpu_seconds / max(per_head, 1e-9))))
+        dt = run(nb)
         cpu = dict(value=round(ops * nb / b / dt / 1e12, 6), unit="TOPS", cores=oracle.num_threads(), kind="oracle",
                    seconds=round(dt, 2), sample=f"first {nb} of {b} heads, both products fwd+bwd")
     print(json.dumps({
@@ -162,6 +172,57 @@ def bench_attn(args, torch, fxp, synth, dev):
                    "rounding": "stochastic (Philox-4x32-10)", "bits": args.bits},
         "roofline": dict(bound="hbm", achieved=round(gbs, 1), peak=PEAK_HBM_GBS, unit="GB/s",
                          frac=round(gbs / PEAK_HBM_GBS, 4), kernel="whole step (18 kernels, all HBM-bound)",
+                         algorithmic_per_launch=step_bytes, traffic=None),
+        "cpu_baseline": cpu,
+    }))
+
+
+def bench_sgd(args, torch, fxp, synth, dev):
+    """int16 SGD step (weight decay 5e-4, momentum 0.9: the paper's classification optimiser) on a flat
+    parameter vector of ResNet-18's size."""
+    n = synth.RESNET18_PARAMS
+    w, g, v = synth.sgd_tensors(n)
+    wd_, gd, vd = (torch.from_numpy(a).to(dev) for a in (w, g, v))
+    buf = fxp.SgdBuffers(n, device=dev)
+
+    def step(i):
+        fxp.sgd16_step(wd_, gd, vd, buf, 0.1, 0.9, 5e-4, seed=0, step=i)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    # scales of w, g, v (4 B each) + three lines of 8 B read, 4 B written
+    step_bytes = 48 * n
+    gbs = step_bytes / (ms * 1e-3) / 1e9
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        tt = time.perf_counter()
+        oracle.sgd16_step(w, g, v, 0.1, 0.9, 5e-4, seed=0, step=0)
+        one = time.perf_counter() - tt
+        reps = int(max(1, min(400, args.cpu_seconds / max(one, 1e-9))))   # whole-vector steps, about --cpu-seconds
+        tt = time.perf_counter()
+        wc, vc = w, v
+        for r in range(reps):
+            wc, vc = oracle.sgd16_step(wc, g, vc, 0.1, 0.9, 5e-4, seed=0, step=r)
+        dt = time.perf_counter() - tt
+        cpu = dict(value=round(n * reps / dt / 1e9, 6), unit="G elements/s", cores=oracle.num_threads(), kind="oracle",
+                   seconds=round(dt, 2), sample=f"{reps} consecutive steps on all {n} parameters")
+    print(json.dumps({
+        "metric": "int16 SGD step (weight decay + momentum) G elements/s", "value": round(n / (ms * 1e-3) / 1e9, 3),
+        "unit": "G elements/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int16", "data": "synthetic",
+        "config": {"workload": f"sgd16: flat parameter vector of ResNet-18's size, n={n}, lr 0.1, momentum 0.9, "
+                               "weight decay 5e-4",
+                   "pass": "3 scale reductions (w, g, v) + 3 fixed-point axpy lines (8 B read, 4 B written each)",
+                   "rounding": "stochastic (Philox-4x32-10)", "bits": 16},
+        "roofline": dict(bound="hbm", achieved=round(gbs, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                         frac=round(gbs / PEAK_HBM_GBS, 4), kernel="whole step (3 x k_absmax_partials, 3 x k_axpy16)",
                          algorithmic_per_launch=step_bytes, traffic=None),
         "cpu_baseline": cpu,
     }))
@@ -188,6 +249,8 @@ def main():
         return bench_conv(args, torch, fxp, synth, dev)
     if args.workload == "vitb_attn":
         return bench_attn(args, torch, fxp, synth, dev)
+    if args.workload == "sgd16":
+        return bench_sgd(args, torch, fxp, synth, dev)
     layers = synth.WORKLOADS[args.workload]
     host_inputs, dev_inputs, bufs = [], [], []
     for li, layer in enumerate(layers):

@@ -200,6 +200,30 @@ int fxp_bmm_bwd(const float* dY, const fxp_bmm_saved* saved, int64_t batch, int6
                 int transB, float* dA, float* dBm, int8_t* dYq, int8_t* dYqT, int32_t* e_dY, uint64_t seed,
                 uint64_t step, int rounding, int bits, void* ws, size_t ws_bytes, void* stream);
 
+/* ---- int16 weight update (Remark 5, App. A.4: w_hat_{k+1} = w_hat_k + alpha_hat_k * g_hat, every term in fixed
+ * point with stochastic rounding; the paper's runs use "int16 SGD", Sec. 5) ----
+ * fxp_axpy16: z = x_hat + SR(a_hat * y_hat) over n elements.  x_hat, y_hat, a_hat are the 16-bit instance of
+ * the mapping (15 magnitude bits, scale = largest exponent of the tensor; the scalar's scale is its own
+ * exponent); the int32 product is brought to the unit of x_hat by a shift, with stochastic rounding of the
+ * dropped bits, saturating at 2^23 - 2^15 units; the integer sum goes through the inverse mapping.  The paper
+ * does not spell this formula out: alignment and place of the rounding are this library's reading.
+ * x, y, z: device, fp32; z may be x or y (in place).  e_out: device int32[3] receiving the scales of x, y, a,
+ * or NULL.  Random streams (step << 8) | 3..6.  ws: device, >= 2 * fxp_workspace_bytes(FXP_OP_SCALE) bytes. */
+int fxp_axpy16(const float* x, const float* y, float a, size_t n, float* z, int32_t* e_out, uint64_t seed,
+               uint64_t step, int rounding, void* ws, size_t ws_bytes, void* stream);
+
+/* One SGD step with weight decay and momentum (the optimiser of the paper's classification runs), every line
+ * an fxp_axpy16 with stream steps 3*step, 3*step+1, 3*step+2:
+ *   g1 = g + weight_decay * w      (skipped when weight_decay == 0; needs tmp[n])
+ *   v  = g1 + momentum * v         (skipped when momentum == 0; v may then be NULL)
+ *   w  = w + (-lr) * v             (g1 in place of v without momentum)
+ * w, v are updated in place; g is read only.  The scales of the intermediates come out of the producing
+ * kernel, so the step reads w, g, v once for their scales and once per line.
+ * ws: device, fxp_sgd16_workspace_bytes() bytes. */
+size_t fxp_sgd16_workspace_bytes(void);
+int fxp_sgd16_step(float* w, const float* g, float* v, size_t n, float lr, float momentum, float weight_decay, float* tmp,
+                   uint64_t seed, uint64_t step, int rounding, void* ws, size_t ws_bytes, void* stream);
+
 /* ---- convolution layer (Sec. 3.4: "Linear and convolutional layers" share the integer inner product) ----
  * Channels-last tensors: X[N,H,W,C], W[Cout,KH,KW,C], Y and dY [N,Ho,Wo,Cout] with
  * Ho = (H + 2 pad - KH) / stride + 1 (same for Wo), zero padding.  Host struct. */

@@ -51,6 +51,24 @@ __device__ inline uint32_t block_max(uint32_t v, uint32_t* lds) {
     return r;
 }
 
+// Philox-4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): counter (c0..c3), key (k0, k1), ten rounds of two
+// 32x32->64 multiplies with the Weyl key schedule.  Element i of a tensor stream uses word i % 4 of the
+// block with counter (i / 4, stream id) and key = seed.
+__device__ inline uint4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = static_cast<uint64_t>(0xD2511F53u) * c0;
+        const uint64_t p1 = static_cast<uint64_t>(0xCD9E8D57u) * c2;
+        const uint32_t n0 = static_cast<uint32_t>(p1 >> 32) ^ c1 ^ (k0 + 0x9E3779B9u * r);
+        const uint32_t n2 = static_cast<uint32_t>(p0 >> 32) ^ c3 ^ (k1 + 0xBB67AE85u * r);
+        c1 = static_cast<uint32_t>(p1);
+        c3 = static_cast<uint32_t>(p0);
+        c0 = n0;
+        c2 = n2;
+    }
+    return make_uint4(c0, c1, c2, c3);
+}
+
 // scale + map of one tensor: block maxima, then the map kernel finishes the reduction and publishes *e
 inline int scale_and_map(const float* x, int64_t rows, int64_t cols, int32_t* e, int8_t* q, int8_t* qT, uint64_t seed,
                          uint64_t sid, int rounding, int bits, uint32_t* partials, hipStream_t s) {

@@ -31,21 +31,6 @@ struct MapCfg {
     uint32_t low_mask;  // 2^cut - 1
 };
 
-__device__ inline uint4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1) {
-#pragma unroll
-    for (int r = 0; r < 10; ++r) {
-        const uint64_t p0 = static_cast<uint64_t>(0xD2511F53u) * c0;
-        const uint64_t p1 = static_cast<uint64_t>(0xCD9E8D57u) * c2;
-        const uint32_t n0 = static_cast<uint32_t>(p1 >> 32) ^ c1 ^ (k0 + 0x9E3779B9u * r);
-        const uint32_t n2 = static_cast<uint32_t>(p0 >> 32) ^ c3 ^ (k1 + 0xBB67AE85u * r);
-        c1 = static_cast<uint32_t>(p1);
-        c3 = static_cast<uint32_t>(p0);
-        c0 = n0;
-        c2 = n2;
-    }
-    return make_uint4(c0, c1, c2, c3);
-}
-
 // Magnitude of one element, every case: non-finite input, scale below the element.
 template <bool STOCH>
 __device__ inline uint32_t magnitude_full(uint32_t b, uint32_t word, const MapCfg& c) {

@@ -75,6 +75,12 @@ def lib():
     L.fxp_bmm_fwd.argtypes = [vp, vp, i64, i64, i64, i64, ci, vp, c.POINTER(_Saved), u64, u64, ci, ci, vp, sz, vp]
     L.fxp_bmm_bwd.argtypes = [vp, c.POINTER(_Saved), i64, i64, i64, i64, ci, vp, vp, vp, vp, vp, u64, u64, ci, ci, vp, sz,
                               vp]
+    L.fxp_sgd16_workspace_bytes.restype = sz
+    L.fxp_sgd16_workspace_bytes.argtypes = []
+    L.fxp_axpy16.argtypes = [vp, vp, c.c_float, sz, vp, vp, u64, u64, ci, vp, sz, vp]
+    L.fxp_sgd16_step.argtypes = [vp, vp, vp, sz, c.c_float, c.c_float, c.c_float, vp, u64, u64, ci, vp, sz, vp]
+    L.fxp_axpy16.restype = ci
+    L.fxp_sgd16_step.restype = ci
     for name in ("fxp_scale", "fxp_map", "fxp_scale_map", "fxp_gemm", "fxp_unmap", "fxp_unmap_i8", "fxp_gemm_unmap",
                  "fxp_linear_fwd", "fxp_linear_bwd", "fxp_gemm_batched", "fxp_gemm_unmap_batched", "fxp_bmm_fwd",
                  "fxp_bmm_bwd"):
@@ -360,3 +366,38 @@ def conv2d_bwd(dY, buf, seed=0, step=0, rounding=STOCHASTIC, bits=8, need_dX=Tru
                                 _p(buf.dYqT), buf.e[2:3].data_ptr(), seed, step, rounding, bits, _p(buf.ws),
                                 buf.ws.numel(), _stream()), "fxp_conv2d_bwd")
     return dX, dW
+
+
+def axpy16(x, y, a, out=None, seed=0, step=0, rounding=STOCHASTIC, ws=None):
+    """z = x_hat + SR(a_hat * y_hat) in 16-bit fixed point; returns (z, e) with e = int32[3] scales of x, y, a."""
+    x, y = _dev(x, torch.float32, "x"), _dev(y, torch.float32, "y")
+    if x.shape != y.shape:
+        raise FxpError("x and y differ in shape")
+    z = out if out is not None else torch.empty_like(x)
+    _dev(z, torch.float32, "out")
+    e = torch.zeros(3, dtype=torch.int32, device=x.device)
+    ws = ws if ws is not None else torch.empty(2 * workspace_bytes(OP_SCALE, 1), dtype=torch.uint8, device=x.device)
+    _check(lib().fxp_axpy16(_p(x), _p(y), float(a), x.numel(), _p(z), _p(e), seed, step, rounding, _p(ws), ws.numel(),
+                            _stream()), "fxp_axpy16")
+    return z, e
+
+
+class SgdBuffers:
+    """Scratch of the int16 SGD step for tensors of up to n elements."""
+
+    def __init__(self, n, device="cuda"):
+        self.tmp = torch.empty(n, dtype=torch.float32, device=device)
+        self.ws = torch.empty(int(lib().fxp_sgd16_workspace_bytes()), dtype=torch.uint8, device=device)
+
+
+def sgd16_step(w, g, v, buf, lr, momentum=0.0, weight_decay=0.0, seed=0, step=0, rounding=STOCHASTIC):
+    """In-place SGD step on w (and the momentum buffer v, which may be None when momentum == 0)."""
+    w, g = _dev(w, torch.float32, "w"), _dev(g, torch.float32, "g")
+    if v is not None:
+        _dev(v, torch.float32, "v")
+    if g.numel() != w.numel() or (v is not None and v.numel() != w.numel()) or buf.tmp.numel() < w.numel():
+        raise FxpError("w, g, v and the scratch differ in size")
+    _check(lib().fxp_sgd16_step(_p(w), _p(g), _p(v), w.numel(), float(lr), float(momentum), float(weight_decay),
+                                _p(buf.tmp), seed, step, rounding, _p(buf.ws), buf.ws.numel(), _stream()),
+           "fxp_sgd16_step")
+    return w, v

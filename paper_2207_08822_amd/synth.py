@@ -158,3 +158,14 @@ def attention_tensors(seed=1, batch=None, S=None, S_real=None, d=None):
     dS = _normal(rng, (b, s, s), 1e-3)
     dO = _normal(rng, (b, s, dd), 1e-3)
     return dict(Q=Q, K=K, V=V, P=P, dS=dS, dO=dO), g
+
+
+# Parameter count of torchvision's ResNet-18 (the smallest model of the paper's classification table), used as
+# one flat vector for the optimiser step.
+RESNET18_PARAMS = 11_689_512
+
+
+def sgd_tensors(n=RESNET18_PARAMS, seed=1):
+    """fp32 (w, g, v): N(0, 0.05) weights, N(0, 2e-3) gradients, N(0, 1e-2) momentum buffer."""
+    rng = np.random.Generator(np.random.PCG64([seed, 79]))
+    return _normal(rng, (n,), 0.05), _normal(rng, (n,), 2e-3), _normal(rng, (n,), 1e-2)

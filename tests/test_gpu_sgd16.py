@@ -1,0 +1,95 @@
+"""GPU parity of the int16 weight update (axpy16, SGD step with weight decay and momentum) against the CPU
+oracle: every output bit for bit (0 ulp), scales exact."""
+import numpy as np
+import pytest
+
+import oracle
+from tests.gpu_util import dev, host, same_bits, say
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def fxp():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU: there is no CPU path in libfxp")
+    from paper_2207_08822_amd import fxp as binding
+    binding.lib()
+    return binding
+
+
+def tensors(seed, n):
+    rng = np.random.default_rng(seed)
+    w = (rng.standard_normal(n) * 0.05).astype(np.float32)
+    g = rng.laplace(0, 2e-3, n).astype(np.float32)
+    v = rng.laplace(0, 1e-2, n).astype(np.float32)
+    return w, g, v
+
+
+@pytest.mark.parametrize("n", [1, 3, 4, 5, 1023, 4096, 262147, 3_000_001])
+@pytest.mark.parametrize("a", [-0.1, 0.9, 5e-4, 1024.0, -3.0e-6])
+def test_axpy16(fxp, n, a):
+    say("axpy16", n, a)
+    w, g, _ = tensors(n % 97, n)
+    z, e = fxp.axpy16(dev(w), dev(g), a, seed=5, step=7)
+    zo, eo = oracle.axpy16(w, g, a, seed=5, step=7)
+    assert tuple(host(e).tolist()) == eo
+    assert same_bits(host(z), zo)
+
+
+@pytest.mark.parametrize("rounding", [0, 1])
+def test_axpy16_special_values_in_place_and_unaligned(fxp, rounding):
+    say("axpy16 special", rounding)
+    rng = np.random.default_rng(2)
+    n = 5000
+    x = rng.standard_normal(n).astype(np.float32)
+    y = rng.standard_normal(n).astype(np.float32)
+    x[:8] = [0.0, -0.0, 1e-41, -1e-41, np.inf, -np.inf, np.nan, 3.0e38]
+    y[3:9] = [np.inf, np.nan, -1e-45, 0.0, 1.0, -3.0e38]
+    zo, eo = oracle.axpy16(x, y, 0.25, seed=1, step=2, rounding=rounding)
+    xd, yd = dev(x), dev(y)
+    z, e = fxp.axpy16(xd, yd, 0.25, seed=1, step=2, rounding=rounding)
+    assert tuple(host(e).tolist()) == eo and same_bits(host(z), zo)
+    # finite tensors: in place on x, and through views that are only 4-byte aligned
+    x[:8] = 0.5
+    y[3:9] = -0.25
+    zo, _ = oracle.axpy16(x[1:], y[1:], -2.0, seed=1, step=2, rounding=rounding)
+    xd, yd = dev(x), dev(y)
+    z, _ = fxp.axpy16(xd[1:], yd[1:], -2.0, out=xd[1:], seed=1, step=2, rounding=rounding)
+    assert same_bits(host(xd[1:]), zo) and host(xd)[0] == x[0]
+    # tiny and huge scalars: vanishing update, saturating update
+    for a in (1e-30, 1e30, 0.0):
+        zo, eo = oracle.axpy16(x, y, a, seed=4, step=1, rounding=rounding)
+        z, e = fxp.axpy16(dev(x), dev(y), a, seed=4, step=1, rounding=rounding)
+        assert tuple(host(e).tolist()) == eo and same_bits(host(z), zo)
+
+
+@pytest.mark.parametrize("lr,mu,wd", [(0.1, 0.9, 5e-4), (0.1, 0.0, 0.0), (0.01, 0.9, 0.0), (0.05, 0.0, 1e-5)])
+@pytest.mark.parametrize("n", [7, 1000, 1_200_003])
+def test_sgd16_step(fxp, n, lr, mu, wd):
+    say("sgd16", n, lr, mu, wd)
+    w, g, v = tensors(n % 89 + 1, n)
+    buf = fxp.SgdBuffers(n)
+    wd_, gd, vd = dev(w), dev(g), (dev(v) if mu != 0.0 else None)
+    wo, vo = w, (v if mu != 0.0 else None)
+    for step in range(3):                                  # a few steps: the state feeds back
+        fxp.sgd16_step(wd_, gd, vd, buf, lr, mu, wd, seed=8, step=step)
+        wo, vo = oracle.sgd16_step(wo, g, vo, lr, mu, wd, seed=8, step=step)
+        assert same_bits(host(wd_), wo)
+        if mu != 0.0:
+            assert same_bits(host(vd), vo)
+    assert np.array_equal(host(gd), g)
+
+
+def test_sgd16_rejects_bad_arguments(fxp):
+    w = torch.zeros(16, device="cuda")
+    buf = fxp.SgdBuffers(16)
+    L = fxp.lib()
+    p = lambda t: t.data_ptr()
+    assert L.fxp_sgd16_step(p(w), p(w), None, 16, 0.1, 0.9, 0.0, None, 0, 0, 0, p(buf.ws), buf.ws.numel(), None) == -1
+    assert L.fxp_sgd16_step(p(w), p(w), None, 16, 0.1, 0.0, 1e-4, None, 0, 0, 0, p(buf.ws), buf.ws.numel(), None) == -1
+    assert L.fxp_sgd16_step(p(w), p(w), None, 16, 0.1, 0.0, 0.0, None, 0, 0, 0, p(buf.ws), 16, None) == -4
+    assert L.fxp_sgd16_step(p(w), p(w), None, 16, 0.1, 0.0, 0.0, None, 0, 0, 7, p(buf.ws), buf.ws.numel(), None) == -5
+    assert L.fxp_axpy16(p(w), None, 0.1, 16, p(w), None, 0, 0, 0, p(buf.ws), buf.ws.numel(), None) == -1
