@@ -297,10 +297,9 @@ extern "C" int fxp_conv2d_fwd(const float* X, const float* W, const fxp_conv2d_s
     int8_t* col = reinterpret_cast<int8_t*>(w8 + 2 * round_up(kScaleWsBytes, 256));
     uint8_t* rest = reinterpret_cast<uint8_t*>(col) + round_up(static_cast<size_t>(g.M()) * g.K(), 256);
     const int64_t M = g.M(), K = g.K(), pixels = static_cast<int64_t>(g.N) * g.H * g.W;
-    if ((rc = scale_and_map(X, pixels, g.C, saved->eX, saved->Xq, nullptr, seed, (step << 8) | FXP_TAG_X, rounding, bits, pX, s)))
-        return rc;
-    if ((rc = scale_and_map(W, g.Cout, K, saved->eW, saved->Wq, saved->WqT, seed, (step << 8) | FXP_TAG_W, rounding, bits, pW, s)))
-        return rc;
+    const MapTensor tX{X, pixels, g.C, nullptr, pX, 0, saved->eX, saved->Xq, nullptr, (step << 8) | FXP_TAG_X};
+    const MapTensor tW{W, g.Cout, K, nullptr, pW, 0, saved->eW, saved->Wq, saved->WqT, (step << 8) | FXP_TAG_W};
+    if ((rc = scale_and_map2(tX, tW, seed, rounding, bits, s))) return rc;
     hipLaunchKernelGGL(k_flip_weights_i8, dim3(grid_for(static_cast<int64_t>(g.Cout) * K)), dim3(256), 0, s, saved->Wq, g,
                        saved->WqF);
     if ((rc = launch_status())) return rc;

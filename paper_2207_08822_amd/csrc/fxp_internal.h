@@ -18,10 +18,27 @@ inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Launchers used by the layer composition (all enqueue on `s`, arguments already validated).
 int scale_partials(const float* x, size_t n, uint32_t* partials, int* n_partials, hipStream_t s);
+// the same for two tensors in one launch
+int scale_partials2(const float* x0, size_t n0, uint32_t* partials0, int* n_partials0, const float* x1, size_t n1,
+                    uint32_t* partials1, int* n_partials1, hipStream_t s);
 int scale_finish(const uint32_t* partials, int n_partials, int32_t* e_max, hipStream_t s);
-int map_launch(const float* x, int64_t rows, int64_t cols, const int32_t* e_in, const uint32_t* partials,
-               int n_partials, int32_t* e_out, int8_t* q, int8_t* qT, uint64_t seed, uint64_t stream_id, int rounding,
-               int bits, hipStream_t s);
+
+// One tensor to map: x[rows, cols] fp32 -> q (row-major) and / or qT (transposed), either may be null.  The
+// scale comes from e_in (device) or, when partials is given, from the block maxima of a scale reduction, in
+// which case the kernel finishes the reduction and publishes the scale to e_out.
+struct MapTensor {
+    const float* x;
+    int64_t rows, cols;
+    const int32_t* e_in;
+    const uint32_t* partials;
+    int n_partials;
+    int32_t* e_out;
+    int8_t* q;
+    int8_t* qT;
+    uint64_t stream_id;
+};
+int map_launch(const MapTensor& t, uint64_t seed, int rounding, int bits, hipStream_t s);
+int map_launch2(const MapTensor& a, const MapTensor& b, uint64_t seed, int rounding, int bits, hipStream_t s);
 int gemm_nt_batched_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, int64_t strideA,
                            const int8_t* B, int64_t ldb, int64_t strideB, void* C, int64_t ldc, int64_t strideC,
                            int64_t batch, bool fp32_out, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB,
@@ -75,7 +92,19 @@ inline int scale_and_map(const float* x, int64_t rows, int64_t cols, int32_t* e,
     int np = 0;
     int rc = scale_partials(x, static_cast<size_t>(rows * cols), partials, &np, s);
     if (rc) return rc;
-    return map_launch(x, rows, cols, nullptr, partials, np, e, q, qT, seed, sid, rounding, bits, s);
+    const MapTensor t{x, rows, cols, nullptr, partials, np, e, q, qT, sid};
+    return map_launch(t, seed, rounding, bits, s);
+}
+
+// Scale + map of two tensors (the two operands of a forward pass) in two launches instead of four: one
+// reduction launch and one map launch cover both.  t.partials must point at kMaxPartials words each; e_in and
+// n_partials of the arguments are ignored.
+inline int scale_and_map2(MapTensor a, MapTensor b, uint64_t seed, int rounding, int bits, hipStream_t s) {
+    int rc = scale_partials2(a.x, static_cast<size_t>(a.rows * a.cols), const_cast<uint32_t*>(a.partials), &a.n_partials, b.x,
+                             static_cast<size_t>(b.rows * b.cols), const_cast<uint32_t*>(b.partials), &b.n_partials, s);
+    if (rc) return rc;
+    a.e_in = b.e_in = nullptr;
+    return map_launch2(a, b, seed, rounding, bits, s);
 }
 
 

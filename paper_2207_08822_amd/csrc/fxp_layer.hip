@@ -72,10 +72,9 @@ extern "C" int fxp_linear_fwd(const float* X, const float* W, int64_t M, int64_t
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint32_t* pX = static_cast<uint32_t*>(ws);
     uint32_t* pW = pX + round_up(kScaleWsBytes, 256) / sizeof(uint32_t);
-    if ((rc = scale_and_map(X, M, K, saved->eX, saved->Xq, saved->XqT, seed, (step << 8) | FXP_TAG_X, rounding, bits, pX, s)))
-        return rc;
-    if ((rc = scale_and_map(W, K, N, saved->eW, saved->Wq, saved->WqT, seed, (step << 8) | FXP_TAG_W, rounding, bits, pW, s)))
-        return rc;
+    const MapTensor tX{X, M, K, nullptr, pX, 0, saved->eX, saved->Xq, saved->XqT, (step << 8) | FXP_TAG_X};
+    const MapTensor tW{W, K, N, nullptr, pW, 0, saved->eW, saved->Wq, saved->WqT, (step << 8) | FXP_TAG_W};
+    if ((rc = scale_and_map2(tX, tW, seed, rounding, bits, s))) return rc;
     uint8_t* rest = static_cast<uint8_t*>(ws) + 2 * round_up(kScaleWsBytes, 256);
     return gemm_nt_launch(M, N, K, saved->Xq, K, saved->WqT, K, Y, N, true, saved->eX, bits, saved->eW, bits, rest,
                           ws_bytes - 2 * round_up(kScaleWsBytes, 256), s);
@@ -141,12 +140,9 @@ extern "C" int fxp_bmm_fwd(const float* A, const float* Bm, int64_t batch, int64
     uint32_t* pA = static_cast<uint32_t*>(ws);
     uint32_t* pB = pA + round_up(kScaleWsBytes, 256) / sizeof(uint32_t);
     const int64_t b_rows = transB ? N : K, b_cols = transB ? K : N;
-    if ((rc = scale_and_map(A, batch * M, K, saved->eA, saved->Aq, saved->AqT, seed, (step << 8) | FXP_TAG_X, rounding, bits,
-                            pA, s)))
-        return rc;
-    if ((rc = scale_and_map(Bm, batch * b_rows, b_cols, saved->eB, saved->Bq, saved->BqT, seed, (step << 8) | FXP_TAG_W,
-                            rounding, bits, pB, s)))
-        return rc;
+    const MapTensor tA{A, batch * M, K, nullptr, pA, 0, saved->eA, saved->Aq, saved->AqT, (step << 8) | FXP_TAG_X};
+    const MapTensor tB{Bm, batch * b_rows, b_cols, nullptr, pB, 0, saved->eB, saved->Bq, saved->BqT, (step << 8) | FXP_TAG_W};
+    if ((rc = scale_and_map2(tA, tB, seed, rounding, bits, s))) return rc;
     const int8_t* Bop = transB ? saved->Bq : saved->BqT;
     const int64_t ldb = transB ? K : batch * K, strideB = transB ? N * K : K;
     return gemm_nt_batched_launch(M, N, K, saved->Aq, K, M * K, Bop, ldb, strideB, Y, N, M * N, batch, true, saved->eA, bits,

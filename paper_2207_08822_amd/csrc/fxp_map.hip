@@ -85,20 +85,20 @@ __device__ inline MapCfg make_cfg(int e_max, int bits) {
 // scale of the tensor: either given, or the max of the per-block maxima (and then
 // block 0 publishes it)
 __device__ inline int resolve_scale(const int32_t* e_in, const uint32_t* partials, int n_partials, int32_t* e_out,
-                                    uint32_t* red) {
+                                    uint32_t* red, bool publish) {
     if (partials == nullptr) return e_in[0];
     uint32_t m = 0;
     for (int i = threadIdx.x; i < n_partials; i += blockDim.x) m = max(m, partials[i]);
     m = block_max(m, red);
     const int e = max(1, static_cast<int>(m >> 23));
-    if (blockIdx.x == 0 && threadIdx.x == 0) e_out[0] = e;
+    if (publish && threadIdx.x == 0) e_out[0] = e;
     return e;
 }
 
 // One tile of TC columns (128, or 64 for tensors whose width pads less that way: head width 64 of the
 // attention operands) and TR = 1024 / TC * 4 * PASSES rows: every thread owns 4 x 4 elements per pass, the 256
-// threads of a pass cover 32 x 128 or 64 x 64.  PASSES = 4 for large tensors, 1 when the tensor is too small to
-// fill the chip with the tall tiles.  EDGE = the tile sticks out of the tensor: loads are clamped to valid
+// threads of a pass cover 32 x 128 or 64 x 64.  PASSES = 4 for large tensors, 2 or 1 when the tensor is too small
+// to fill the chip with the taller tiles.  EDGE = the tile sticks out of the tensor: loads are clamped to valid
 // addresses and stores are predicated; interior tiles carry no bounds code at all.  All
 // per-thread addressing is a 32-bit element offset from the tile's (wave-uniform) origin.
 template <bool STOCH, bool EDGE, int PASSES, int TC>
@@ -212,24 +212,45 @@ __device__ inline void map_tile_body(const uint32_t* __restrict__ x, int64_t row
     }
 }
 
+// One tensor of a map launch.  A launch carries up to two (the activation and the weight of a forward pass):
+// the first `blocks` workgroups belong to job 0, the rest to job 1.
+struct MapJob {
+    const uint32_t* x;
+    int64_t rows, cols;
+    const int32_t* e_in;
+    const uint32_t* partials;
+    int n_partials;
+    int32_t* e_out;
+    int8_t* q;
+    int8_t* qT;
+    uint32_t sid0, sid1;
+    int tiles_c;
+    unsigned blocks;
+};
+struct MapJobs {
+    MapJob j[2];
+};
+
 template <bool STOCH, int PASSES, int TC>
-__global__ __launch_bounds__(kMapThreads) void k_map_tile(const uint32_t* __restrict__ x, int64_t rows, int64_t cols,
-                                                          const int32_t* __restrict__ e_in,
-                                                          const uint32_t* __restrict__ partials, int n_partials,
-                                                          int32_t* __restrict__ e_out, int8_t* __restrict__ q,
-                                                          int8_t* __restrict__ qT, uint32_t key0, uint32_t key1,
-                                                          uint32_t sid0, uint32_t sid1, int bits, int tiles_c) {
+__global__ __launch_bounds__(kMapThreads) void k_map_tile(const MapJobs jobs, uint32_t key0, uint32_t key1, int bits) {
     constexpr int RGP = kMapThreads / (TC / 4);
     constexpr int TR = 4 * RGP * PASSES;
     __shared__ uint32_t stage[TC * (RGP * PASSES + 1)];
     __shared__ uint32_t red[kMapThreads / 64];
-    const MapCfg cfg = make_cfg(resolve_scale(e_in, partials, n_partials, e_out, red), bits);
-    const int64_t r0 = static_cast<int64_t>(blockIdx.x / tiles_c) * TR;
-    const int64_t c0 = static_cast<int64_t>(blockIdx.x % tiles_c) * TC;
+    const bool second = blockIdx.x >= jobs.j[0].blocks;            // workgroup-uniform
+    const MapJob& J = jobs.j[second ? 1 : 0];
+    const unsigned bid = blockIdx.x - (second ? jobs.j[0].blocks : 0u);
+    const uint32_t* __restrict__ x = J.x;
+    int8_t* __restrict__ q = J.q;
+    int8_t* __restrict__ qT = J.qT;
+    const int64_t rows = J.rows, cols = J.cols;
+    const MapCfg cfg = make_cfg(resolve_scale(J.e_in, J.partials, J.n_partials, J.e_out, red, bid == 0), bits);
+    const int64_t r0 = static_cast<int64_t>(bid / J.tiles_c) * TR;
+    const int64_t c0 = static_cast<int64_t>(bid % J.tiles_c) * TC;
     if (r0 + TR <= rows && c0 + TC <= cols)
-        map_tile_body<STOCH, false, PASSES, TC>(x, rows, cols, cfg, q, qT, key0, key1, sid0, sid1, r0, c0, stage);
+        map_tile_body<STOCH, false, PASSES, TC>(x, rows, cols, cfg, q, qT, key0, key1, J.sid0, J.sid1, r0, c0, stage);
     else
-        map_tile_body<STOCH, true, PASSES, TC>(x, rows, cols, cfg, q, qT, key0, key1, sid0, sid1, r0, c0, stage);
+        map_tile_body<STOCH, true, PASSES, TC>(x, rows, cols, cfg, q, qT, key0, key1, J.sid0, J.sid1, r0, c0, stage);
 }
 
 // One element per thread, any shape and alignment.
@@ -241,7 +262,7 @@ __global__ __launch_bounds__(kMapThreads) void k_map_generic(const uint32_t* __r
                                                              int8_t* __restrict__ qT, uint32_t key0, uint32_t key1,
                                                              uint32_t sid0, uint32_t sid1, int bits) {
     __shared__ uint32_t red[kMapThreads / 64];
-    const MapCfg cfg = make_cfg(resolve_scale(e_in, partials, n_partials, e_out, red), bits);
+    const MapCfg cfg = make_cfg(resolve_scale(e_in, partials, n_partials, e_out, red, blockIdx.x == 0), bits);
     const uint64_t n = static_cast<uint64_t>(rows) * static_cast<uint64_t>(cols);
     for (uint64_t i = static_cast<uint64_t>(blockIdx.x) * kMapThreads + threadIdx.x; i < n;
          i += static_cast<uint64_t>(gridDim.x) * kMapThreads) {
@@ -262,48 +283,112 @@ __global__ __launch_bounds__(kMapThreads) void k_map_generic(const uint32_t* __r
     }
 }
 
-int map_launch(const float* x, int64_t rows, int64_t cols, const int32_t* e_in, const uint32_t* partials,
-               int n_partials, int32_t* e_out, int8_t* q, int8_t* qT, uint64_t seed, uint64_t stream_id, int rounding,
-               int bits, hipStream_t s) {
-    const uint32_t k0 = static_cast<uint32_t>(seed), k1 = static_cast<uint32_t>(seed >> 32);
-    const uint32_t s0 = static_cast<uint32_t>(stream_id), s1 = static_cast<uint32_t>(stream_id >> 32);
-    const uint32_t* xb = reinterpret_cast<const uint32_t*>(x);
-    const bool stoch = rounding == FXP_ROUND_STOCHASTIC;
+// how one tensor would be tiled
+struct MapPlan {
+    int tc;          // tile columns
+    int passes;      // 4, 2 or 1
+    bool tile_path;  // false: the one-element-per-thread kernel
+};
+
+static MapPlan plan_map(const MapTensor& t) {
+    MapPlan p;
     // tile width: 64 when that pads the rows less than 128 does (cols = 64, 192, ...)
-    const int tc = ((cols + 63) / 64) * 64 < ((cols + 127) / 128) * 128 ? 64 : 128;
-    const int64_t tall = tc == 128 ? 128 : 256;   // rows of a 4-pass tile
-    const int64_t tiles_c = (cols + tc - 1) / tc;
-    // tall tiles need about 2000 workgroups to fill the chip; smaller tensors take single-pass tiles
-    const bool small = ((rows + tall - 1) / tall) * tiles_c < 2048;
-    const int64_t tr = small ? tall / 4 : tall;
-    const int64_t tiles_r = (rows + tr - 1) / tr;
-    const bool tile_path = (cols % 4 == 0) && aligned(x, 16) && (!q || aligned(q, 16)) && (!qT || aligned(qT, 16)) &&
-                           tiles_r * tiles_c > 0 && tiles_r * tiles_c < (int64_t{1} << 31) && cols < (int64_t{1} << 22);   // 32-bit offsets inside a tile
-    if (tile_path) {
-        const dim3 grid(static_cast<unsigned>(tiles_r * tiles_c)), block(kMapThreads);
-#define FXP_MAP_LAUNCH(STOCH, PASSES, TC)                                                                                  \
-    hipLaunchKernelGGL((k_map_tile<STOCH, PASSES, TC>), grid, block, 0, s, xb, rows, cols, e_in, partials, n_partials, e_out, \
-                       q, qT, k0, k1, s0, s1, bits, static_cast<int>(tiles_c))
-#define FXP_MAP_PICK(TC)                           \
-    if (stoch && small) FXP_MAP_LAUNCH(true, 1, TC);  \
-    else if (stoch) FXP_MAP_LAUNCH(true, 4, TC);      \
-    else if (small) FXP_MAP_LAUNCH(false, 1, TC);     \
-    else FXP_MAP_LAUNCH(false, 4, TC)
-        if (tc == 128) { FXP_MAP_PICK(128); }
-        else { FXP_MAP_PICK(64); }
+    p.tc = ((t.cols + 63) / 64) * 64 < ((t.cols + 127) / 128) * 128 ? 64 : 128;
+    const int64_t tall = p.tc == 128 ? 128 : 256;   // rows of a 4-pass tile
+    const int64_t tiles_c = (t.cols + p.tc - 1) / p.tc;
+    // tiles need about 2000 workgroups to fill the chip: four passes per tile when the tensor is large enough
+    // for that, else two, else single-pass tiles
+    auto count = [&](int64_t tile_rows) { return ((t.rows + tile_rows - 1) / tile_rows) * tiles_c; };
+    p.passes = count(tall) >= 2048 ? 4 : (count(tall / 2) >= 2048 ? 2 : 1);
+    p.tile_path = (t.cols % 4 == 0) && aligned(t.x, 16) && (!t.q || aligned(t.q, 16)) && (!t.qT || aligned(t.qT, 16)) &&
+                  t.rows > 0 && count(tall / 4) < (int64_t{1} << 30) && t.cols < (int64_t{1} << 22);   // 32-bit offsets inside a tile
+    return p;
+}
+
+static MapJob make_job(const MapTensor& t, int tc, int passes) {
+    MapJob j;
+    const int64_t tr = (tc == 128 ? 128 : 256) / 4 * passes;
+    j.x = reinterpret_cast<const uint32_t*>(t.x);
+    j.rows = t.rows;
+    j.cols = t.cols;
+    j.e_in = t.e_in;
+    j.partials = t.partials;
+    j.n_partials = t.n_partials;
+    j.e_out = t.e_out;
+    j.q = t.q;
+    j.qT = t.qT;
+    j.sid0 = static_cast<uint32_t>(t.stream_id);
+    j.sid1 = static_cast<uint32_t>(t.stream_id >> 32);
+    j.tiles_c = static_cast<int>((t.cols + tc - 1) / tc);
+    j.blocks = static_cast<unsigned>(((t.rows + tr - 1) / tr) * j.tiles_c);
+    return j;
+}
+
+static void launch_tiles(const MapJobs& jobs, int tc, int passes, bool stoch, uint32_t k0, uint32_t k1, int bits,
+                         hipStream_t s) {
+    const dim3 grid(jobs.j[0].blocks + jobs.j[1].blocks), block(kMapThreads);
+#define FXP_MAP_LAUNCH(STOCH, PASSES, TC) \
+    hipLaunchKernelGGL((k_map_tile<STOCH, PASSES, TC>), grid, block, 0, s, jobs, k0, k1, bits)
+#define FXP_MAP_PICK(TC)                                   \
+    if (stoch) {                                           \
+        if (passes == 4) FXP_MAP_LAUNCH(true, 4, TC);      \
+        else if (passes == 2) FXP_MAP_LAUNCH(true, 2, TC); \
+        else FXP_MAP_LAUNCH(true, 1, TC);                  \
+    } else {                                               \
+        if (passes == 4) FXP_MAP_LAUNCH(false, 4, TC);     \
+        else if (passes == 2) FXP_MAP_LAUNCH(false, 2, TC);\
+        else FXP_MAP_LAUNCH(false, 1, TC);                 \
+    }
+    if (tc == 128) { FXP_MAP_PICK(128); }
+    else { FXP_MAP_PICK(64); }
 #undef FXP_MAP_PICK
 #undef FXP_MAP_LAUNCH
+}
+
+int map_launch(const MapTensor& t, uint64_t seed, int rounding, int bits, hipStream_t s) {
+    const uint32_t k0 = static_cast<uint32_t>(seed), k1 = static_cast<uint32_t>(seed >> 32);
+    const bool stoch = rounding == FXP_ROUND_STOCHASTIC;
+    const MapPlan p = plan_map(t);
+    if (p.tile_path) {
+        MapJobs jobs;
+        jobs.j[0] = make_job(t, p.tc, p.passes);
+        jobs.j[1] = jobs.j[0];
+        jobs.j[1].blocks = 0;
+        launch_tiles(jobs, p.tc, p.passes, stoch, k0, k1, bits, s);
     } else {
-        const uint64_t n = static_cast<uint64_t>(rows) * static_cast<uint64_t>(cols);
+        const uint32_t s0 = static_cast<uint32_t>(t.stream_id), s1 = static_cast<uint32_t>(t.stream_id >> 32);
+        const uint32_t* xb = reinterpret_cast<const uint32_t*>(t.x);
+        const uint64_t n = static_cast<uint64_t>(t.rows) * static_cast<uint64_t>(t.cols);
         uint64_t want = (n + kMapThreads - 1) / kMapThreads;
         const dim3 grid(static_cast<unsigned>(want < 1 ? 1 : (want > 16384 ? 16384 : want))), block(kMapThreads);
         if (stoch)
-            hipLaunchKernelGGL(k_map_generic<true>, grid, block, 0, s, xb, rows, cols, e_in, partials, n_partials, e_out,
-                               q, qT, k0, k1, s0, s1, bits);
+            hipLaunchKernelGGL(k_map_generic<true>, grid, block, 0, s, xb, t.rows, t.cols, t.e_in, t.partials, t.n_partials,
+                               t.e_out, t.q, t.qT, k0, k1, s0, s1, bits);
         else
-            hipLaunchKernelGGL(k_map_generic<false>, grid, block, 0, s, xb, rows, cols, e_in, partials, n_partials,
-                               e_out, q, qT, k0, k1, s0, s1, bits);
+            hipLaunchKernelGGL(k_map_generic<false>, grid, block, 0, s, xb, t.rows, t.cols, t.e_in, t.partials, t.n_partials,
+                               t.e_out, t.q, t.qT, k0, k1, s0, s1, bits);
     }
+    return launch_status();
+}
+
+// Two tensors in one launch when both take the tiled kernel with the same tile width; the tile height is the
+// one the larger tensor would pick.  Otherwise one launch each.
+int map_launch2(const MapTensor& a, const MapTensor& b, uint64_t seed, int rounding, int bits, hipStream_t s) {
+    const MapPlan pa = plan_map(a), pb = plan_map(b);
+    if (!pa.tile_path || !pb.tile_path || pa.tc != pb.tc) {
+        const int rc = map_launch(a, seed, rounding, bits, s);
+        return rc ? rc : map_launch(b, seed, rounding, bits, s);
+    }
+    const int passes = a.rows * a.cols >= b.rows * b.cols ? pa.passes : pb.passes;
+    MapJobs jobs;
+    jobs.j[0] = make_job(a, pa.tc, passes);
+    jobs.j[1] = make_job(b, pa.tc, passes);
+    if (static_cast<uint64_t>(jobs.j[0].blocks) + jobs.j[1].blocks >= (uint64_t{1} << 31)) {
+        const int rc = map_launch(a, seed, rounding, bits, s);
+        return rc ? rc : map_launch(b, seed, rounding, bits, s);
+    }
+    launch_tiles(jobs, pa.tc, passes, rounding == FXP_ROUND_STOCHASTIC, static_cast<uint32_t>(seed),
+                 static_cast<uint32_t>(seed >> 32), bits, s);
     return launch_status();
 }
 
@@ -325,8 +410,8 @@ extern "C" int fxp_map(const float* x, int64_t rows, int64_t cols, const int32_t
     int rc = fxp::check_map_args(x, rows, cols, e_max, q, qT, rounding, bits);
     if (rc) return rc;
     if (rows * cols == 0) return FXP_OK;
-    return fxp::map_launch(x, rows, cols, e_max, nullptr, 0, nullptr, q, qT, seed, stream_id, rounding, bits,
-                           static_cast<hipStream_t>(stream));
+    fxp::MapTensor t{x, rows, cols, e_max, nullptr, 0, nullptr, q, qT, stream_id};
+    return fxp::map_launch(t, seed, rounding, bits, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int fxp_scale_map(const float* x, int64_t rows, int64_t cols, int32_t* e_max, int8_t* q, int8_t* qT,
@@ -342,5 +427,6 @@ extern "C" int fxp_scale_map(const float* x, int64_t rows, int64_t cols, int32_t
     rc = fxp::scale_partials(x, static_cast<size_t>(rows * cols), partials, &np, s);
     if (rc) return rc;
     if (rows * cols == 0) return fxp::scale_finish(partials, np, e_max, s);
-    return fxp::map_launch(x, rows, cols, nullptr, partials, np, e_max, q, qT, seed, stream_id, rounding, bits, s);
+    fxp::MapTensor t{x, rows, cols, nullptr, partials, np, e_max, q, qT, stream_id};
+    return fxp::map_launch(t, seed, rounding, bits, s);
 }

@@ -14,9 +14,9 @@ __device__ inline uint32_t absmax4(const uint4 v) {
     return max(max(v.x & kAbs, v.y & kAbs), max(v.z & kAbs, v.w & kAbs));
 }
 
-__global__ __launch_bounds__(kScaleThreads) void k_absmax_partials(const uint32_t* __restrict__ x, size_t n,
-                                                                   uint32_t* __restrict__ partials) {
-    __shared__ uint32_t lds[kScaleThreads / 64];
+// block maxima of one tensor: block `bid` of `nblocks`
+__device__ inline void absmax_body(const uint32_t* __restrict__ x, size_t n, uint32_t* __restrict__ partials, unsigned bid,
+                                   unsigned nblocks, uint32_t* lds) {
     const uint32_t kAbs = 0x7fffffffu;
     uint32_t m = 0;
     // scalar head up to 16-byte alignment, vector body, scalar tail
@@ -25,21 +25,31 @@ __global__ __launch_bounds__(kScaleThreads) void k_absmax_partials(const uint32_
     if (head > n) head = n;
     const size_t nvec = (n - head) >> 2;
     const uint4* xv = reinterpret_cast<const uint4*>(x + head);
-    const size_t tid = static_cast<size_t>(blockIdx.x) * kScaleThreads + threadIdx.x;
-    const size_t stride = static_cast<size_t>(gridDim.x) * kScaleThreads;
+    const size_t tid = static_cast<size_t>(bid) * kScaleThreads + threadIdx.x;
+    const size_t stride = static_cast<size_t>(nblocks) * kScaleThreads;
     size_t i = tid;
     for (; i + 3 * stride < nvec; i += 4 * stride) {
         const uint4 a = xv[i], b = xv[i + stride], c = xv[i + 2 * stride], d = xv[i + 3 * stride];
         m = max(max(m, absmax4(a)), max(absmax4(b), max(absmax4(c), absmax4(d))));
     }
     for (; i < nvec; i += stride) m = max(m, absmax4(xv[i]));
-    if (blockIdx.x == 0) {
+    if (bid == 0) {
         if (threadIdx.x < head) m = max(m, x[threadIdx.x] & kAbs);
         const size_t tail0 = head + (nvec << 2);
         if (tail0 + threadIdx.x < n) m = max(m, x[tail0 + threadIdx.x] & kAbs);
     }
     m = block_max(m, lds);
-    if (threadIdx.x == 0) partials[blockIdx.x] = m;
+    if (threadIdx.x == 0) partials[bid] = m;
+}
+
+// Up to two tensors per launch: the first blocks0 workgroups reduce tensor 0, the others tensor 1.
+__global__ __launch_bounds__(kScaleThreads) void k_absmax_partials(const uint32_t* __restrict__ x0, size_t n0,
+                                                                   uint32_t* __restrict__ partials0, unsigned blocks0,
+                                                                   const uint32_t* __restrict__ x1, size_t n1,
+                                                                   uint32_t* __restrict__ partials1) {
+    __shared__ uint32_t lds[kScaleThreads / 64];
+    if (blockIdx.x < blocks0) absmax_body(x0, n0, partials0, blockIdx.x, blocks0, lds);
+    else absmax_body(x1, n1, partials1, blockIdx.x - blocks0, gridDim.x - blocks0, lds);
 }
 
 __global__ __launch_bounds__(kScaleThreads) void k_absmax_finish(const uint32_t* __restrict__ partials, int count,
@@ -51,13 +61,28 @@ __global__ __launch_bounds__(kScaleThreads) void k_absmax_finish(const uint32_t*
     if (threadIdx.x == 0) e_max[0] = max(1, static_cast<int>(m >> 23));
 }
 
+// 16K elements or more per block (the map kernel re-reads every block maximum), at most kMaxPartials
+static int partial_count(size_t n) {
+    const size_t want = (n + 16383) / 16384;
+    return static_cast<int>(want < 1 ? 1 : (want > kMaxPartials ? kMaxPartials : want));
+}
+
 int scale_partials(const float* x, size_t n, uint32_t* partials, int* n_partials, hipStream_t s) {
-    // 16K elements or more per block (the map kernel re-reads every block maximum), at most kMaxPartials
-    size_t want = (n + 16383) / 16384;
-    int grid = static_cast<int>(want < 1 ? 1 : (want > kMaxPartials ? kMaxPartials : want));
-    hipLaunchKernelGGL(k_absmax_partials, dim3(grid), dim3(kScaleThreads), 0, s, reinterpret_cast<const uint32_t*>(x),
-                       n, partials);
+    const int grid = partial_count(n);
+    hipLaunchKernelGGL(k_absmax_partials, dim3(grid), dim3(kScaleThreads), 0, s, reinterpret_cast<const uint32_t*>(x), n,
+                       partials, static_cast<unsigned>(grid), static_cast<const uint32_t*>(nullptr), size_t{0},
+                       static_cast<uint32_t*>(nullptr));
     *n_partials = grid;
+    return launch_status();
+}
+
+int scale_partials2(const float* x0, size_t n0, uint32_t* partials0, int* n_partials0, const float* x1, size_t n1,
+                    uint32_t* partials1, int* n_partials1, hipStream_t s) {
+    const int g0 = partial_count(n0), g1 = partial_count(n1);
+    hipLaunchKernelGGL(k_absmax_partials, dim3(g0 + g1), dim3(kScaleThreads), 0, s, reinterpret_cast<const uint32_t*>(x0),
+                       n0, partials0, static_cast<unsigned>(g0), reinterpret_cast<const uint32_t*>(x1), n1, partials1);
+    *n_partials0 = g0;
+    *n_partials1 = g1;
     return launch_status();
 }
 
