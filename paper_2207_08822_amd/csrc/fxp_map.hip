@@ -82,6 +82,25 @@ __device__ inline MapCfg make_cfg(int e_max, int bits) {
     return c;
 }
 
+// One tensor of a map launch.  A launch carries up to two (the activation and the weight of a forward pass):
+// the first `blocks` workgroups belong to job 0, the rest to job 1.
+struct MapJob {
+    const uint32_t* x;
+    int64_t rows, cols;
+    const int32_t* e_in;
+    const uint32_t* partials;
+    int n_partials;
+    int32_t* e_out;
+    int8_t* q;
+    int8_t* qT;
+    uint32_t sid0, sid1;
+    int tiles_c;
+    unsigned blocks;
+};
+struct MapJobs {
+    MapJob j[2];
+};
+
 // scale of the tensor: either given, or the max of the per-block maxima (and then
 // block 0 publishes it)
 __device__ inline int resolve_scale(const int32_t* e_in, const uint32_t* partials, int n_partials, int32_t* e_out,
@@ -102,9 +121,10 @@ __device__ inline int resolve_scale(const int32_t* e_in, const uint32_t* partial
 // addresses and stores are predicated; interior tiles carry no bounds code at all.  All
 // per-thread addressing is a 32-bit element offset from the tile's (wave-uniform) origin.
 template <bool STOCH, bool EDGE, int PASSES, int TC>
-__device__ inline void map_tile_body(const uint32_t* __restrict__ x, int64_t rows, int64_t cols, const MapCfg& cfg,
-                                     int8_t* __restrict__ q, int8_t* __restrict__ qT, uint32_t key0, uint32_t key1,
-                                     uint32_t sid0, uint32_t sid1, int64_t r0, int64_t c0, uint32_t* stage) {
+__device__ inline void map_tile_body(const uint32_t* __restrict__ x, int64_t rows, int64_t cols, const MapJob& J, int bits,
+                                     bool publish, uint32_t* red, int8_t* __restrict__ q, int8_t* __restrict__ qT,
+                                     uint32_t key0, uint32_t key1, uint32_t sid0, uint32_t sid1, int64_t r0, int64_t c0,
+                                     uint32_t* stage) {
     constexpr int CG = TC / 4;                    // groups of 4 columns
     constexpr int RGP = kMapThreads / CG;         // groups of 4 rows per pass
     constexpr int TR = 4 * RGP * PASSES;          // rows of the tile
@@ -121,8 +141,6 @@ __device__ inline void map_tile_body(const uint32_t* __restrict__ x, int64_t row
     const int cols_here = EDGE ? static_cast<int>(min<int64_t>(TC, cols - c0)) : TC;
     const bool col_ok = !EDGE || 4 * cg < cols_here;
     const uint32_t col_ld = EDGE ? static_cast<uint32_t>(min(4 * cg, cols_here - 4)) : 4 * cg;
-    const bool scale_ok = cfg.e_max >= 25 && cfg.e_max < 255;
-    const uint32_t over_bit = cfg.sat + 1u;       // a fast-path result with this bit set needs saturation
 
     // PASSES passes of 4 * RGP rows.  The loads of pass p+1 are issued before the arithmetic of pass
     // p, so a block keeps the memory pipe busy while it runs its Philox rounds.
@@ -136,6 +154,10 @@ __device__ inline void map_tile_body(const uint32_t* __restrict__ x, int64_t row
     };
     uint4 cur[4], nxt[4];
     load_pass(0, cur);
+    // the scale is resolved (block maxima re-read and reduced) while the first loads are in flight
+    const MapCfg cfg = make_cfg(resolve_scale(J.e_in, J.partials, J.n_partials, J.e_out, red, publish), bits);
+    const bool scale_ok = cfg.e_max >= 25 && cfg.e_max < 255;
+    const uint32_t over_bit = cfg.sat + 1u;       // a fast-path result with this bit set needs saturation
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
         const int rg = p * RGP + rgl;              // group of 4 rows
@@ -212,25 +234,6 @@ __device__ inline void map_tile_body(const uint32_t* __restrict__ x, int64_t row
     }
 }
 
-// One tensor of a map launch.  A launch carries up to two (the activation and the weight of a forward pass):
-// the first `blocks` workgroups belong to job 0, the rest to job 1.
-struct MapJob {
-    const uint32_t* x;
-    int64_t rows, cols;
-    const int32_t* e_in;
-    const uint32_t* partials;
-    int n_partials;
-    int32_t* e_out;
-    int8_t* q;
-    int8_t* qT;
-    uint32_t sid0, sid1;
-    int tiles_c;
-    unsigned blocks;
-};
-struct MapJobs {
-    MapJob j[2];
-};
-
 template <bool STOCH, int PASSES, int TC>
 __global__ __launch_bounds__(kMapThreads) void k_map_tile(const MapJobs jobs, uint32_t key0, uint32_t key1, int bits) {
     constexpr int RGP = kMapThreads / (TC / 4);
@@ -244,13 +247,12 @@ __global__ __launch_bounds__(kMapThreads) void k_map_tile(const MapJobs jobs, ui
     int8_t* __restrict__ q = J.q;
     int8_t* __restrict__ qT = J.qT;
     const int64_t rows = J.rows, cols = J.cols;
-    const MapCfg cfg = make_cfg(resolve_scale(J.e_in, J.partials, J.n_partials, J.e_out, red, bid == 0), bits);
     const int64_t r0 = static_cast<int64_t>(bid / J.tiles_c) * TR;
     const int64_t c0 = static_cast<int64_t>(bid % J.tiles_c) * TC;
     if (r0 + TR <= rows && c0 + TC <= cols)
-        map_tile_body<STOCH, false, PASSES, TC>(x, rows, cols, cfg, q, qT, key0, key1, J.sid0, J.sid1, r0, c0, stage);
+        map_tile_body<STOCH, false, PASSES, TC>(x, rows, cols, J, bits, bid == 0, red, q, qT, key0, key1, J.sid0, J.sid1, r0, c0, stage);
     else
-        map_tile_body<STOCH, true, PASSES, TC>(x, rows, cols, cfg, q, qT, key0, key1, J.sid0, J.sid1, r0, c0, stage);
+        map_tile_body<STOCH, true, PASSES, TC>(x, rows, cols, J, bits, bid == 0, red, q, qT, key0, key1, J.sid0, J.sid1, r0, c0, stage);
 }
 
 // One element per thread, any shape and alignment.
