@@ -13,6 +13,7 @@ step), a `kernels` table for all classes, and `cpu_baseline`: the CPU oracle tim
 bounded sample of the same workload on the host cores.
 """
 import argparse
+import ctypes
 import json
 import os
 import sys
@@ -307,16 +308,22 @@ def main():
     for layer, (X, W, dY), buf in zip(layers, dev_inputs, bufs):
         M, K, N = layer.M, layer.K, layer.N
         ws = torch.empty(max(256, fxp.workspace_bytes(fxp.OP_SCALE, 0)), dtype=torch.uint8, device=dev)
+        # scale: 4 B read per element (k_absmax_partials; the finishing block is negligible)
         for t, e in ((X, buf.eX), (W, buf.eW), (dY, buf.e_dY)):
             n = t.numel()
-            q = torch.empty(t.shape, dtype=torch.int8, device=dev)
-            qT = torch.empty((t.shape[1], t.shape[0]), dtype=torch.int8, device=dev)
-            # scale: 4 B read per element (k_absmax_partials; the finishing block is negligible)
             add("scale", "k_absmax_partials", timed(lambda: lib.fxp_scale(p(t), n, p(e), p(ws), ws.numel(), st)), 4.0 * n)
-            # map: 4 B read + 1 B written per copy (both orientations) per element
-            add("map", "k_map_tile<true, *>",
-                timed(lambda: lib.fxp_map(p(t), t.shape[0], t.shape[1], p(e), p(q), p(qT), seed, 0, 0, args.bits, st)), 6.0 * n)
-            del q, qT
+        # map: 4 B read + 1 B written per copy (both orientations) per element; launched as the step launches it:
+        # activation and weight in one launch, the gradient in one of its own
+        outs = [(torch.empty(t.shape, dtype=torch.int8, device=dev),
+                 torch.empty((t.shape[1], t.shape[0]), dtype=torch.int8, device=dev)) for t in (X, W, dY)]
+        dX_, dW_ = (fxp._desc(t, e, o[0], o[1], tag) for t, e, o, tag in ((X, buf.eX, outs[0], 0), (W, buf.eW, outs[1], 1)))
+        add("map", "k_map_tile<true, *>",
+            timed(lambda: lib.fxp_map2(ctypes.byref(dX_), ctypes.byref(dW_), seed, 0, args.bits, st)),
+            6.0 * (X.numel() + W.numel()))
+        add("map", "k_map_tile<true, *>",
+            timed(lambda: lib.fxp_map(p(dY), dY.shape[0], dY.shape[1], p(buf.e_dY), p(outs[2][0]), p(outs[2][1]), seed, 2, 0,
+                                      args.bits, st)), 6.0 * dY.numel())
+        del outs
         gemms = [("fwd", M, N, K, buf.Xq, buf.WqT, buf.eX, buf.eW, buf.Y),
                  ("dX", M, K, N, buf.dYq, buf.Wq, buf.e_dY, buf.eW, buf.dX),
                  ("dW", K, N, M, buf.XqT, buf.dYqT, buf.eX, buf.e_dY, buf.dW)]

@@ -101,6 +101,24 @@ int fxp_map(const float* x, int64_t rows, int64_t cols, const int32_t* e_max, in
 int fxp_scale_map(const float* x, int64_t rows, int64_t cols, int32_t* e_max, int8_t* q, int8_t* qT, uint64_t seed,
                   uint64_t stream_id, int rounding, int bits, void* ws, size_t ws_bytes, void* stream);
 
+/* Two tensors per launch: what fxp_map / fxp_scale_map do for one tensor, done for two with one map launch
+ * (and one reduction launch) instead of two each - the layer calls use this for the activation and the
+ * weight of a forward pass, where the second tensor is often too small to fill the chip by itself.  Results
+ * are identical to two separate calls.  One launch needs both tensors on the fast path of fxp_map and of the
+ * same tile width (cols <= 64 or cols % 128 in 1..64 selects the narrow tile); otherwise two launches are made. */
+typedef struct fxp_map_desc {
+    const float* x;      /* [rows, cols] fp32, device */
+    int64_t rows, cols;
+    int32_t* e_max;      /* device: read by fxp_map2, written by fxp_scale_map2 */
+    int8_t* q;           /* [rows, cols] or NULL */
+    int8_t* qT;          /* [cols, rows] or NULL */
+    uint64_t stream_id;
+} fxp_map_desc;
+int fxp_map2(const fxp_map_desc* a, const fxp_map_desc* b, uint64_t seed, int rounding, int bits, void* stream);
+/* ws: device, >= 2 * fxp_workspace_bytes(FXP_OP_SCALE, ...) bytes */
+int fxp_scale_map2(const fxp_map_desc* a, const fxp_map_desc* b, uint64_t seed, int rounding, int bits, void* ws,
+                   size_t ws_bytes, void* stream);
+
 /* Integer GEMM (Sec. 3.3, Fig. 2: int8 x int8 products, int32 accumulation).
  * C[M,N] = op(A)[M,K] * op(B)[K,N], C overwritten.
  * transA = 0: A stored [M,K], lda >= K.  transA = 1: A stored [K,M], lda >= M.

@@ -432,3 +432,44 @@ extern "C" int fxp_scale_map(const float* x, int64_t rows, int64_t cols, int32_t
     fxp::MapTensor t{x, rows, cols, nullptr, partials, np, e_max, q, qT, stream_id};
     return fxp::map_launch(t, seed, rounding, bits, s);
 }
+
+static int check_desc(const fxp_map_desc* d, int rounding, int bits) {
+    if (!d) return FXP_ERR_NULL;
+    return fxp::check_map_args(d->x, d->rows, d->cols, d->e_max, d->q, d->qT, rounding, bits);
+}
+
+extern "C" int fxp_map2(const fxp_map_desc* a, const fxp_map_desc* b, uint64_t seed, int rounding, int bits, void* stream) {
+    int rc = check_desc(a, rounding, bits);
+    if (!rc) rc = check_desc(b, rounding, bits);
+    if (rc) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const fxp::MapTensor ta{a->x, a->rows, a->cols, a->e_max, nullptr, 0, nullptr, a->q, a->qT, a->stream_id};
+    const fxp::MapTensor tb{b->x, b->rows, b->cols, b->e_max, nullptr, 0, nullptr, b->q, b->qT, b->stream_id};
+    if (a->rows * a->cols == 0 || b->rows * b->cols == 0) {     // an empty tensor has nothing to launch
+        if (a->rows * a->cols && (rc = fxp::map_launch(ta, seed, rounding, bits, s))) return rc;
+        if (b->rows * b->cols && (rc = fxp::map_launch(tb, seed, rounding, bits, s))) return rc;
+        return FXP_OK;
+    }
+    return fxp::map_launch2(ta, tb, seed, rounding, bits, s);
+}
+
+extern "C" int fxp_scale_map2(const fxp_map_desc* a, const fxp_map_desc* b, uint64_t seed, int rounding, int bits, void* ws,
+                              size_t ws_bytes, void* stream) {
+    int rc = check_desc(a, rounding, bits);
+    if (!rc) rc = check_desc(b, rounding, bits);
+    if (rc) return rc;
+    if (!ws || ws_bytes < 2 * fxp::kScaleWsBytes) return FXP_ERR_WORKSPACE;
+    if (!fxp::aligned(ws, 4)) return FXP_ERR_ALIGN;
+    uint32_t* pa = static_cast<uint32_t*>(ws);
+    uint32_t* pb = pa + fxp::kMaxPartials;
+    if (a->rows * a->cols == 0 || b->rows * b->cols == 0) {     // an empty tensor: the single-tensor path, twice
+        rc = fxp_scale_map(a->x, a->rows, a->cols, a->e_max, a->q, a->qT, seed, a->stream_id, rounding, bits, pa,
+                           fxp::kScaleWsBytes, stream);
+        return rc ? rc
+                  : fxp_scale_map(b->x, b->rows, b->cols, b->e_max, b->q, b->qT, seed, b->stream_id, rounding, bits, pb,
+                                  fxp::kScaleWsBytes, stream);
+    }
+    const fxp::MapTensor ta{a->x, a->rows, a->cols, nullptr, pa, 0, a->e_max, a->q, a->qT, a->stream_id};
+    const fxp::MapTensor tb{b->x, b->rows, b->cols, nullptr, pb, 0, b->e_max, b->q, b->qT, b->stream_id};
+    return fxp::scale_and_map2(ta, tb, seed, rounding, bits, static_cast<hipStream_t>(stream));
+}

@@ -26,6 +26,11 @@ class _Saved(ctypes.Structure):
                 ("eX", ctypes.c_void_p), ("eW", ctypes.c_void_p)]
 
 
+class _MapDesc(ctypes.Structure):
+    _fields_ = [("x", ctypes.c_void_p), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64), ("e_max", ctypes.c_void_p),
+                ("q", ctypes.c_void_p), ("qT", ctypes.c_void_p), ("stream_id", ctypes.c_uint64)]
+
+
 class _ConvShape(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int64) for n in ("N", "H", "W", "C", "Cout", "KH", "KW", "stride", "pad")]
 
@@ -75,6 +80,10 @@ def lib():
     L.fxp_bmm_fwd.argtypes = [vp, vp, i64, i64, i64, i64, ci, vp, c.POINTER(_Saved), u64, u64, ci, ci, vp, sz, vp]
     L.fxp_bmm_bwd.argtypes = [vp, c.POINTER(_Saved), i64, i64, i64, i64, ci, vp, vp, vp, vp, vp, u64, u64, ci, ci, vp, sz,
                               vp]
+    L.fxp_map2.argtypes = [c.POINTER(_MapDesc), c.POINTER(_MapDesc), u64, ci, ci, vp]
+    L.fxp_scale_map2.argtypes = [c.POINTER(_MapDesc), c.POINTER(_MapDesc), u64, ci, ci, vp, sz, vp]
+    L.fxp_map2.restype = ci
+    L.fxp_scale_map2.restype = ci
     L.fxp_sgd16_workspace_bytes.restype = sz
     L.fxp_sgd16_workspace_bytes.argtypes = []
     L.fxp_axpy16.argtypes = [vp, vp, c.c_float, sz, vp, vp, u64, u64, ci, vp, sz, vp]
@@ -401,3 +410,33 @@ def sgd16_step(w, g, v, buf, lr, momentum=0.0, weight_decay=0.0, seed=0, step=0,
                                 _p(buf.tmp), seed, step, rounding, _p(buf.ws), buf.ws.numel(), _stream()),
            "fxp_sgd16_step")
     return w, v
+
+
+def _desc(x, e, q, qT, stream_id):
+    x = _dev(x, torch.float32, "x")
+    if x.dim() != 2:
+        raise FxpError("x must be a matrix")
+    return _MapDesc(_p(x), x.shape[0], x.shape[1], _p(e), _p(q), _p(qT), stream_id)
+
+
+def map2(xa, ea, xb, eb, seed=0, stream_ids=(0, 1), rounding=STOCHASTIC, bits=8):
+    """fxp.map of two tensors (given scales) in one launch; returns ((qa, qaT), (qb, qbT))."""
+    outs = [(torch.empty(x.shape, dtype=torch.int8, device=x.device),
+             torch.empty((x.shape[1], x.shape[0]), dtype=torch.int8, device=x.device)) for x in (xa, xb)]
+    da = _desc(xa, ea, outs[0][0], outs[0][1], stream_ids[0])
+    db = _desc(xb, eb, outs[1][0], outs[1][1], stream_ids[1])
+    _check(lib().fxp_map2(ctypes.byref(da), ctypes.byref(db), seed, rounding, bits, _stream()), "fxp_map2")
+    return outs
+
+
+def scale_map2(xa, xb, seed=0, stream_ids=(0, 1), rounding=STOCHASTIC, bits=8):
+    """fxp.scale_map of two tensors in two launches; returns (e[2], (qa, qaT), (qb, qbT))."""
+    e = torch.zeros(2, dtype=torch.int32, device=xa.device)
+    outs = [(torch.empty(x.shape, dtype=torch.int8, device=x.device),
+             torch.empty((x.shape[1], x.shape[0]), dtype=torch.int8, device=x.device)) for x in (xa, xb)]
+    da = _desc(xa, e[0:1], outs[0][0], outs[0][1], stream_ids[0])
+    db = _desc(xb, e[1:2], outs[1][0], outs[1][1], stream_ids[1])
+    ws = torch.empty(2 * workspace_bytes(OP_SCALE, 1), dtype=torch.uint8, device=xa.device)
+    _check(lib().fxp_scale_map2(ctypes.byref(da), ctypes.byref(db), seed, rounding, bits, _p(ws), ws.numel(), _stream()),
+           "fxp_scale_map2")
+    return e, outs[0], outs[1]

@@ -122,6 +122,32 @@ def test_scale_map_fused_equals_two_calls(fxp):
         assert np.array_equal(host(q), want) and np.array_equal(host(qT), want.T)
 
 
+PAIRS = [((300, 516), (516, 40)), ((4000, 1152), (1152, 128)), ((64, 64), (640, 192)), ((100, 7), (64, 64)),
+         ((2600, 1024), (1024, 1024)), ((33, 64), (70, 128))]
+
+
+@pytest.mark.parametrize("sa,sb", PAIRS)
+def test_two_tensor_calls_equal_single_calls(fxp, sa, sb):
+    """fxp_map2 / fxp_scale_map2 (one launch for two tensors where their tilings agree, else two) against the
+    oracle, for equal and different tile widths, and the element-wise path."""
+    say("map2", sa, sb)
+    rng = np.random.default_rng(sa[0] + sb[1])
+    xa = (rng.standard_normal(sa) * 3).astype(np.float32)
+    xb = (rng.standard_normal(sb) * 0.02).astype(np.float32)
+    ea, eb = oracle.scale(xa), oracle.scale(xb)
+    wa, wb = oracle.map(xa, ea, seed=5, stream_id=256), oracle.map(xb, eb, seed=5, stream_id=257)
+    e, (qa, qaT), (qb, qbT) = fxp.scale_map2(dev(xa), dev(xb), seed=5, stream_ids=(256, 257))
+    assert host(e).tolist() == [ea, eb]
+    assert np.array_equal(host(qa), wa) and np.array_equal(host(qaT), wa.T)
+    assert np.array_equal(host(qb), wb) and np.array_equal(host(qbT), wb.T)
+    ed = dev(np.array([ea + 1, eb], np.int32))          # given scales (one of them above the tensor's own)
+    wa1 = oracle.map(xa, ea + 1, seed=6, stream_id=1)
+    wb1 = oracle.map(xb, eb, seed=6, stream_id=2, rounding=oracle.STOCHASTIC)
+    (qa, qaT), (qb, qbT) = fxp.map2(dev(xa), ed[0:1], dev(xb), ed[1:2], seed=6, stream_ids=(1, 2))
+    assert np.array_equal(host(qa), wa1) and np.array_equal(host(qaT), wa1.T)
+    assert np.array_equal(host(qb), wb1) and np.array_equal(host(qbT), wb1.T)
+
+
 # --------------------------------------------------------------------------- gemm
 def rand_i8(rng, shape, lo=-127, hi=127):
     return rng.integers(lo, hi + 1, size=shape, dtype=np.int64).astype(np.int8)
