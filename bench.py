@@ -109,7 +109,7 @@ def bench_conv(args, torch, fxp, synth, dev):
                    "pass": "scale+map X, W, dY; int8 im2col; 3 int8 GEMMs; gather col2im + inverse map",
                    "rounding": "stochastic (Philox-4x32-10)", "bits": args.bits},
         "roofline": dict(bound="hbm", achieved=round(gbs, 1), peak=PEAK_HBM_GBS, unit="GB/s",
-                         frac=round(gbs / PEAK_HBM_GBS, 4), kernel="whole step (14 kernels, all HBM-bound)",
+                         frac=round(gbs / PEAK_HBM_GBS, 4), kernel="whole step (12 kernels, all HBM-bound)",
                          algorithmic_per_launch=step_bytes, traffic=None),
         "cpu_baseline": cpu,
     }))
@@ -172,7 +172,7 @@ def bench_attn(args, torch, fxp, synth, dev):
                    "pass": "per product: scale+map 3 tensors (both orientations), 3 batched int8 GEMMs with fused inverse map",
                    "rounding": "stochastic (Philox-4x32-10)", "bits": args.bits},
         "roofline": dict(bound="hbm", achieved=round(gbs, 1), peak=PEAK_HBM_GBS, unit="GB/s",
-                         frac=round(gbs / PEAK_HBM_GBS, 4), kernel="whole step (18 kernels, all HBM-bound)",
+                         frac=round(gbs / PEAK_HBM_GBS, 4), kernel="whole step (16 kernels, all HBM-bound)",
                          algorithmic_per_launch=step_bytes, traffic=None),
         "cpu_baseline": cpu,
     }))
