@@ -53,3 +53,65 @@ def test_host_only_entry_points_and_argument_errors():
     assert L.fxp_gemm(0, 0, 4, 4, 16, fake, 16, fake, 16, fake, 4, None, 0, None) == -4    # needs workspace
     L.fxp_scale.argtypes = [vp, sz, vp, vp, sz, vp]
     assert L.fxp_scale(fake, 16, fake, None, 0, None) == -4
+
+
+def test_argument_errors_of_the_layer_level_entry_points():
+    """Batched products, convolution, two-tensor map and the int16 update validate before any launch."""
+    L = load()
+    vp, i64, u64, ci, sz, fl = (ctypes.c_void_p, ctypes.c_int64, ctypes.c_uint64, ctypes.c_int, ctypes.c_size_t,
+                                ctypes.c_float)
+    fake = ctypes.c_void_p(1 << 20)       # never dereferenced: every call below fails validation first
+    L.fxp_workspace_bytes.restype = sz
+    L.fxp_workspace_bytes.argtypes = [ci, i64, i64, i64]
+    assert L.fxp_workspace_bytes(4, 8, 8, 8) >= 8192 and L.fxp_workspace_bytes(5, 8, 8, 8) >= 4096
+    # the backward workspace of a weight gradient that is split along K holds its int32 slices
+    assert L.fxp_workspace_bytes(3, 25088, 128, 1152) > 4 * 1152 * 128
+    L.fxp_gemm_batched.argtypes = [i64, i64, i64, vp, i64, i64, vp, i64, i64, vp, i64, i64, i64, vp]
+    assert L.fxp_gemm_batched(16, 16, 16, fake, 16, 256, fake, 16, 256, fake, 16, 256, -1, None) == -2
+    assert L.fxp_gemm_batched(16, 16, 16, fake, 16, 256, fake, 16, 256, fake, 16, 255, 2, None) == -2   # C overlaps
+    assert L.fxp_gemm_batched(16, 16, 16, fake, 8, 256, fake, 16, 256, fake, 16, 256, 2, None) == -2    # lda < K
+    assert L.fxp_gemm_batched(16, 16, 200000, fake, 200000, 0, fake, 200000, 0, fake, 16, 256, 2, None) == -8
+
+    class Saved(ctypes.Structure):
+        _fields_ = [(n, vp) for n in ("Aq", "AqT", "Bq", "BqT", "eA", "eB")]
+
+    sv = Saved(1 << 20, 1 << 20, 1 << 20, 1 << 20, 1 << 20, 1 << 20)
+    L.fxp_bmm_fwd.argtypes = [vp, vp, i64, i64, i64, i64, ci, vp, ctypes.POINTER(Saved), u64, u64, ci, ci, vp, sz, vp]
+    ws = ctypes.c_void_p(1 << 20)
+    assert L.fxp_bmm_fwd(fake, fake, 0, 8, 8, 8, 0, fake, ctypes.byref(sv), 0, 0, 0, 8, ws, 1 << 20, None) == -2
+    assert L.fxp_bmm_fwd(fake, fake, 70000, 8, 8, 8, 0, fake, ctypes.byref(sv), 0, 0, 0, 8, ws, 1 << 20, None) == -2
+    assert L.fxp_bmm_fwd(fake, fake, 2, 8, 8, 8, 0, fake, ctypes.byref(sv), 0, 0, 0, 8, ws, 16, None) == -4
+    assert L.fxp_bmm_fwd(fake, fake, 2, 8, 8, 8, 0, fake, ctypes.byref(sv), 0, 0, 3, 8, ws, 1 << 20, None) == -5
+    assert L.fxp_bmm_fwd(None, fake, 2, 8, 8, 8, 0, fake, ctypes.byref(sv), 0, 0, 0, 8, ws, 1 << 20, None) == -1
+    assert L.fxp_bmm_fwd(fake, fake, 2, 8, 200000, 8, 0, fake, ctypes.byref(sv), 0, 0, 0, 8, ws, 1 << 20, None) == -8
+
+    L.fxp_sgd16_workspace_bytes.restype = sz
+    assert L.fxp_sgd16_workspace_bytes() >= 5 * 4096
+    L.fxp_axpy16.argtypes = [vp, vp, fl, sz, vp, vp, u64, u64, ci, vp, sz, vp]
+    assert L.fxp_axpy16(fake, fake, 0.5, 16, fake, None, 0, 0, 0, None, 0, None) == -4
+    assert L.fxp_axpy16(fake, fake, 0.5, 16, fake, None, 0, 0, 2, ws, 1 << 20, None) == -5
+    assert L.fxp_axpy16(fake, None, 0.5, 16, fake, None, 0, 0, 0, ws, 1 << 20, None) == -1
+    assert L.fxp_axpy16(None, None, 0.5, 0, None, None, 0, 0, 0, ws, 1 << 20, None) == 0          # nothing to do
+    L.fxp_sgd16_step.argtypes = [vp, vp, vp, sz, fl, fl, fl, vp, u64, u64, ci, vp, sz, vp]
+    assert L.fxp_sgd16_step(fake, fake, None, 16, 0.1, 0.9, 0.0, None, 0, 0, 0, ws, 1 << 20, None) == -1   # momentum, no v
+    assert L.fxp_sgd16_step(fake, fake, fake, 16, 0.1, 0.9, 1e-4, None, 0, 0, 0, ws, 1 << 20, None) == -1  # decay, no tmp
+    assert L.fxp_sgd16_step(fake, fake, fake, 16, 0.1, 0.9, 0.0, None, 0, 1 << 60, 0, ws, 1 << 20, None) == -2
+
+    class Desc(ctypes.Structure):
+        _fields_ = [("x", vp), ("rows", i64), ("cols", i64), ("e_max", vp), ("q", vp), ("qT", vp), ("stream_id", u64)]
+
+    good = Desc(1 << 20, 4, 4, 1 << 20, 1 << 20, None, 0)
+    bad = Desc(1 << 20, 4, 4, 1 << 20, None, None, 0)             # neither copy requested
+    L.fxp_map2.argtypes = [ctypes.POINTER(Desc), ctypes.POINTER(Desc), u64, ci, ci, vp]
+    assert L.fxp_map2(ctypes.byref(good), ctypes.byref(bad), 0, 0, 8, None) == -1
+    assert L.fxp_map2(ctypes.byref(good), None, 0, 0, 8, None) == -1
+    assert L.fxp_map2(ctypes.byref(good), ctypes.byref(good), 0, 0, 1, None) == -6
+
+    class Shape(ctypes.Structure):
+        _fields_ = [(n, i64) for n in ("N", "H", "W", "C", "Cout", "KH", "KW", "stride", "pad")]
+
+    L.fxp_conv2d_workspace_bytes.restype = sz
+    L.fxp_conv2d_workspace_bytes.argtypes = [ctypes.POINTER(Shape), ci]
+    ok_shape = Shape(2, 8, 8, 16, 16, 3, 3, 1, 1)
+    assert L.fxp_conv2d_workspace_bytes(ctypes.byref(ok_shape), 0) >= 2 * 8 * 8 * 9 * 16
+    assert L.fxp_conv2d_workspace_bytes(ctypes.byref(Shape(2, 2, 2, 16, 16, 5, 5, 1, 0)), 0) == 0   # kernel larger than image
