@@ -255,7 +255,8 @@ typedef struct fxp_conv_saved {
     int8_t* Xq;   /* [N,H,W,C] */
     int8_t* Wq;   /* [Cout, KH*KW*C] */
     int8_t* WqT;  /* [KH*KW*C, Cout] */
-    int8_t* WqF;  /* [C, KH*KW*Cout]: kernel flipped in both spatial axes, for the input gradient */
+    int8_t* WqF;  /* [C, KH*KW*Cout]: kernel flipped in both spatial axes; scratch of the backward call, which
+                     fills it from Wq when it computes the input gradient of a stride-1 convolution */
     int32_t* eX;  /* 1 */
     int32_t* eW;  /* 1 */
 } fxp_conv_saved;
@@ -264,8 +265,9 @@ typedef struct fxp_conv_saved {
 size_t fxp_conv2d_workspace_bytes(const fxp_conv2d_shape* shape, int backward);
 
 /* Forward: the activation tensor is mapped once as a whole (element index = its channels-last flat index,
- * FXP_TAG_X), the weights likewise (FXP_TAG_W); int8 patches are gathered into scratch and multiplied on the
- * matrix cores; Y receives the inverse-mapped fp32 result.  Contraction KH*KW*C <= 133144. */
+ * FXP_TAG_X), the weights likewise (FXP_TAG_W); the int8 patches are multiplied on the matrix cores - read
+ * straight from the int8 activation by the GEMM loader when C is a multiple of 128, gathered into scratch
+ * first otherwise - and Y receives the inverse-mapped fp32 result.  Contraction KH*KW*C <= 133144. */
 int fxp_conv2d_fwd(const float* X, const float* W, const fxp_conv2d_shape* shape, float* Y, const fxp_conv_saved* saved,
                    uint64_t seed, uint64_t step, int rounding, int bits, void* ws, size_t ws_bytes, void* stream);
 

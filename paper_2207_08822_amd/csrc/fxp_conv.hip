@@ -78,11 +78,36 @@ __global__ __launch_bounds__(256) void k_im2col_i8(const int8_t* __restrict__ Xq
     }
 }
 
+// WqF[c][(kh', kw', co)] = Wq[co][(KH-1-kh', KW-1-kw', c)]: the weights of the stride-1 input-gradient
+// convolution (the upstream gradient correlated with the flipped kernel), contraction-contiguous
+__device__ inline void flip_weights_body(const int8_t* __restrict__ Wq, const ConvGeo& g, int8_t* __restrict__ WqF, unsigned bid,
+                                         unsigned nblocks) {
+    const int64_t K = g.K(), Kf = static_cast<int64_t>(g.KH) * g.KW * g.Cout, total = static_cast<int64_t>(g.C) * Kf;
+    for (int64_t id = static_cast<int64_t>(bid) * 256 + threadIdx.x; id < total; id += static_cast<int64_t>(nblocks) * 256) {
+        const int c = static_cast<int>(id / Kf);
+        const int rem = static_cast<int>(id - c * Kf);
+        const int tap = rem / g.Cout, co = rem - tap * g.Cout;
+        const int kh = tap / g.KW, kw = tap - kh * g.KW;
+        WqF[id] = Wq[co * K + static_cast<int64_t>((g.KH - 1 - kh) * g.KW + (g.KW - 1 - kw)) * g.C + c];
+    }
+}
+
+__global__ __launch_bounds__(256) void k_flip_weights_i8(const int8_t* __restrict__ Wq, ConvGeo g, int8_t* __restrict__ WqF) {
+    flip_weights_body(Wq, g, WqF, blockIdx.x, gridDim.x);
+}
+
 // colT[(tap*C + c)][m] for a tile of 64 consecutive m x 64 channels of one tap.  Each thread reads a
 // 4 (m) x 4 (c) block as four dwords, transposes it in registers, parks the four "4 consecutive m of one
 // channel" dwords in LDS and the block then writes 16-byte pieces along m.  Needs C % 4 == 0.
+// Workgroups beyond the tile_blocks tiles flip the weights for the input-gradient convolution (Wq -> WqF;
+// flip_blocks of them, possibly 0): two independent pieces of the backward pass in one launch.
 __global__ __launch_bounds__(256) void k_im2col_t_i8(const int8_t* __restrict__ Xq, ConvGeo g, int8_t* __restrict__ colT,
-                                                     int tiles_m, int tiles_c) {
+                                                     int tiles_m, int tiles_c, unsigned tile_blocks,
+                                                     const int8_t* __restrict__ Wq, int8_t* __restrict__ WqF) {
+    if (blockIdx.x >= tile_blocks) {
+        flip_weights_body(Wq, g, WqF, blockIdx.x - tile_blocks, gridDim.x - tile_blocks);
+        return;
+    }
     __shared__ uint32_t t[64 * 17];                              // [channel][16 dwords of m] + 1 pad
     int b = blockIdx.x;
     const int tc = b % tiles_c; b /= tiles_c;
@@ -126,7 +151,12 @@ __global__ __launch_bounds__(256) void k_im2col_t_i8(const int8_t* __restrict__ 
 
 // same, one byte at a time, for C % 4 != 0
 __global__ __launch_bounds__(256) void k_im2col_t_i8_bytes(const int8_t* __restrict__ Xq, ConvGeo g, int8_t* __restrict__ colT,
-                                                           int tiles_m, int tiles_c) {
+                                                           int tiles_m, int tiles_c, unsigned tile_blocks,
+                                                           const int8_t* __restrict__ Wq, int8_t* __restrict__ WqF) {
+    if (blockIdx.x >= tile_blocks) {
+        flip_weights_body(Wq, g, WqF, blockIdx.x - tile_blocks, gridDim.x - tile_blocks);
+        return;
+    }
     __shared__ int8_t t[64][65];
     int b = blockIdx.x;
     const int tc = b % tiles_c; b /= tiles_c;
@@ -203,19 +233,6 @@ __global__ __launch_bounds__(256) void k_col2im_unmap(const int32_t* __restrict_
     }
 }
 
-// WqF[c][(kh', kw', co)] = Wq[co][(KH-1-kh', KW-1-kw', c)]: the weights of the stride-1 input-gradient
-// convolution (the upstream gradient correlated with the flipped kernel), contraction-contiguous
-__global__ __launch_bounds__(256) void k_flip_weights_i8(const int8_t* __restrict__ Wq, ConvGeo g, int8_t* __restrict__ WqF) {
-    const int64_t K = g.K(), Kf = static_cast<int64_t>(g.KH) * g.KW * g.Cout, total = static_cast<int64_t>(g.C) * Kf;
-    for (int64_t id = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; id < total; id += static_cast<int64_t>(gridDim.x) * 256) {
-        const int c = static_cast<int>(id / Kf);
-        const int rem = static_cast<int>(id - c * Kf);
-        const int tap = rem / g.Cout, co = rem - tap * g.Cout;
-        const int kh = tap / g.KW, kw = tap - kh * g.KW;
-        WqF[id] = Wq[co * K + static_cast<int64_t>((g.KH - 1 - kh) * g.KW + (g.KW - 1 - kw)) * g.C + c];
-    }
-}
-
 // the input gradient of a stride-1 convolution is itself a convolution: of dY, padded by K-1-pad, with WqF
 static bool dx_as_conv(const ConvGeo& g) { return g.stride == 1 && g.pad <= g.KH - 1 && g.padw <= g.KW - 1; }
 
@@ -225,6 +242,12 @@ static ConvGeo dx_geo(const ConvGeo& g) {
     d.pad = g.KH - 1 - g.pad; d.padw = g.KW - 1 - g.padw;
     d.Ho = g.H; d.Wo = g.W;
     return d;
+}
+
+static ConvTaps taps_of(const ConvGeo& g) {
+    ConvTaps t;
+    t.H = g.H; t.W = g.W; t.C = g.C; t.KW = g.KW; t.stride = g.stride; t.pad = g.pad; t.padw = g.padw; t.Ho = g.Ho; t.Wo = g.Wo;
+    return t;
 }
 
 static unsigned grid_for(int64_t items) {
@@ -300,9 +323,9 @@ extern "C" int fxp_conv2d_fwd(const float* X, const float* W, const fxp_conv2d_s
     const MapTensor tX{X, pixels, g.C, nullptr, pX, 0, saved->eX, saved->Xq, nullptr, (step << 8) | FXP_TAG_X};
     const MapTensor tW{W, g.Cout, K, nullptr, pW, 0, saved->eW, saved->Wq, saved->WqT, (step << 8) | FXP_TAG_W};
     if ((rc = scale_and_map2(tX, tW, seed, rounding, bits, s))) return rc;
-    hipLaunchKernelGGL(k_flip_weights_i8, dim3(grid_for(static_cast<int64_t>(g.Cout) * K)), dim3(256), 0, s, saved->Wq, g,
-                       saved->WqF);
-    if ((rc = launch_status())) return rc;
+    // patches read straight from the int8 image by the GEMM loader where the shape allows, else stored first
+    rc = conv_gemm_launch(taps_of(g), g.KH, M, g.Cout, saved->Xq, saved->Wq, Y, saved->eX, bits, saved->eW, bits, s);
+    if (rc != kNotApplicable) return rc;
     if (g.C % 16 == 0)
         hipLaunchKernelGGL(k_im2col_i8<16>, dim3(static_cast<unsigned>((M + 31) / 32)), dim3(256), 0, s, saved->Xq, g, col);
     else
@@ -334,16 +357,27 @@ extern "C" int fxp_conv2d_bwd(const float* dY, const fxp_conv_saved* saved, cons
     if ((rc = scale_and_map(dY, M, g.Cout, e_dY, dYq, dYqT, seed, (step << 8) | FXP_TAG_DY, rounding, bits,
                             reinterpret_cast<uint32_t*>(w8), s)))
         return rc;
+    const bool need_flip = dX && dx_as_conv(g);
+    if (need_flip && !dW) {
+        hipLaunchKernelGGL(k_flip_weights_i8, dim3(grid_for(static_cast<int64_t>(g.Cout) * K)), dim3(256), 0, s, saved->Wq, g,
+                           saved->WqF);
+        if ((rc = launch_status())) return rc;
+    }
     if (dW) {
         int8_t* colT = reinterpret_cast<int8_t*>(area);
         const int tiles_m = static_cast<int>((M + 63) / 64), tiles_c = (g.C + 63) / 64;
         const int64_t blocks = static_cast<int64_t>(g.KH) * g.KW * tiles_m * tiles_c;
         if (blocks >= (int64_t{1} << 31)) return FXP_ERR_DIMS;
+        // the flipped weights of the input-gradient convolution ride along in the same launch
+        const unsigned flip_blocks = need_flip ? grid_for(static_cast<int64_t>(g.Cout) * K) : 0u;
+        if (blocks + flip_blocks >= (int64_t{1} << 31)) return FXP_ERR_DIMS;
+        const dim3 tgrid(static_cast<unsigned>(blocks) + flip_blocks);
         if (g.C % 4 == 0)
-            hipLaunchKernelGGL(k_im2col_t_i8, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, saved->Xq, g, colT, tiles_m, tiles_c);
+            hipLaunchKernelGGL(k_im2col_t_i8, tgrid, dim3(256), 0, s, saved->Xq, g, colT, tiles_m, tiles_c,
+                               static_cast<unsigned>(blocks), saved->Wq, saved->WqF);
         else
-            hipLaunchKernelGGL(k_im2col_t_i8_bytes, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, saved->Xq, g, colT, tiles_m,
-                               tiles_c);
+            hipLaunchKernelGGL(k_im2col_t_i8_bytes, tgrid, dim3(256), 0, s, saved->Xq, g, colT, tiles_m, tiles_c,
+                               static_cast<unsigned>(blocks), saved->Wq, saved->WqF);
         if ((rc = launch_status())) return rc;
         const size_t used = round_up(static_cast<size_t>(K) * M, 256);
         // dW[Cout, K] = dYqT[Cout, M] * colT[K, M]^T, contraction over all output pixels
@@ -356,6 +390,8 @@ extern "C" int fxp_conv2d_bwd(const float* dY, const fxp_conv_saved* saved, cons
         const ConvGeo d = dx_geo(g);
         int8_t* colg = reinterpret_cast<int8_t*>(area);
         const int64_t Md = d.M(), Kd = d.K();
+        rc = conv_gemm_launch(taps_of(d), d.KH, Md, g.C, dYq, saved->WqF, dX, e_dY, bits, saved->eW, bits, s);
+        if (rc != kNotApplicable) return rc;
         if (d.C % 16 == 0)
             hipLaunchKernelGGL(k_im2col_i8<16>, dim3(static_cast<unsigned>((Md + 31) / 32)), dim3(256), 0, s, dYq, d, colg);
         else

@@ -218,12 +218,20 @@ __device__ inline void wait_loads_and_lds() {
 // that belongs in slot p.  One s_barrier per step, no fence: the only cross-wave traffic
 // is LDS written by the loads (waited for with vmcnt before the barrier) and read by
 // ds_read (waited for with lgkmcnt before the next barrier lets the buffer be refilled).
-template <int BM, int BN, int BK, int WM, int WN, int STAGES, int MODE, bool SCHED>
+// 256 zero bytes: where the patch rows of an implicit convolution read their padding from
+__device__ __attribute__((aligned(256))) const uint8_t g_zero_page[256] = {0};
+
+// CONV: the A operand is not a stored matrix but the patch matrix of a channels-last int8 image tensor
+// (A points at X[N,H,W,C]; row m is output pixel m, contraction index (kh*KW + kw)*C + c): the loader
+// works out, per K step, which input pixel a row reads (one tap of the filter, since C % BK == 0) and takes
+// the bytes straight from the image, or from a page of zeros where the tap falls into the padding.  Nothing
+// else differs from the plain product.
+template <int BM, int BN, int BK, int WM, int WN, int STAGES, int MODE, bool SCHED, bool CONV = false>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm_nt_dma(
     const int8_t* __restrict__ A, int64_t lda, const int8_t* __restrict__ B, int64_t ldb, void* __restrict__ Cv,
     int64_t ldc, int M, int N, int K, int k_per_split, const int32_t* __restrict__ eA, int bitsA,
     const int32_t* __restrict__ eB, int bitsB, int tiles_m, int tiles_n, int group_m, int64_t split_stride,
-    int64_t batch_a, int64_t batch_b, int64_t batch_c) {
+    int64_t batch_a, int64_t batch_b, int64_t batch_c, ConvTaps ct) {
     constexpr int NW = (BM / WM) * (BN / WN);
     constexpr int CPR = BK / 16;                     // 16-byte pieces per LDS row
     constexpr int RROWS = 64 / CPR;                  // tile rows per 1 KiB region
@@ -256,20 +264,47 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm_nt_dma(
     const int wm0 = (wave / (BN / WN)) * WM, wn0 = (wave % (BN / WN)) * WN;
 
     const int8_t* gp[RPW];
+    int a_h0[RPW], a_w0[RPW];                                        // CONV: top-left input coordinate of the row's patch
 #pragma unroll
     for (int j = 0; j < RPW; ++j) {
         const int row_t = (wave + j * NW) * RROWS + lane / CPR;      // row in the stacked (A;B) tile
         const int piece = (lane % CPR) ^ swizzle_of_row<BK>(row_t);  // BM % 16 == 0: same swizzle for B rows
-        gp[j] = (row_t < BM) ? A + static_cast<int64_t>(min(m0 + row_t, M - 1)) * lda + kb + piece * 16
-                             : B + static_cast<int64_t>(min(n0 + row_t - BM, N - 1)) * ldb + kb + piece * 16;
+        a_h0[j] = a_w0[j] = 0;
+        if (CONV && row_t < BM) {
+            const uint32_t m = static_cast<uint32_t>(min(m0 + row_t, M - 1));
+            const uint32_t t = m / static_cast<uint32_t>(ct.Wo), n = t / static_cast<uint32_t>(ct.Ho);
+            a_h0[j] = static_cast<int>(t - n * ct.Ho) * ct.stride - ct.pad;
+            a_w0[j] = static_cast<int>(m - t * ct.Wo) * ct.stride - ct.padw;
+            gp[j] = A + static_cast<int64_t>(n) * ct.H * ct.W * ct.C + piece * 16;          // the row's image
+        } else {
+            gp[j] = (row_t < BM) ? A + static_cast<int64_t>(min(m0 + row_t, M - 1)) * lda + kb + piece * 16
+                                 : B + static_cast<int64_t>(min(n0 + row_t - BM, N - 1)) * ldb + kb + piece * 16;
+        }
     }
     auto issue = [&](int step, int stage) {
+        int kh = 0, kw = 0, c0 = 0;                                  // CONV: the tap and channel offset of this K step
+        if (CONV) {
+            const int k0 = kb + step * BK, tap = k0 / ct.C;
+            c0 = k0 - tap * ct.C;
+            kh = tap / ct.KW;
+            kw = tap - kh * ct.KW;
+        }
 #pragma unroll
-        for (int j = 0; j < RPW; ++j)
+        for (int j = 0; j < RPW; ++j) {
+            const int8_t* src = gp[j] + static_cast<int64_t>(step) * BK;
+            if (CONV && (wave + j * NW) * RROWS < BM) {              // a region of A rows (wave-uniform)
+                const int h = a_h0[j] + kh, w = a_w0[j] + kw;
+                const bool inside = static_cast<unsigned>(h) < static_cast<unsigned>(ct.H) &&
+                                    static_cast<unsigned>(w) < static_cast<unsigned>(ct.W);
+                const int piece16 = ((lane % CPR) ^ swizzle_of_row<BK>((wave + j * NW) * RROWS + lane / CPR)) * 16;
+                src = inside ? gp[j] + (static_cast<int64_t>(h) * ct.W + w) * ct.C + c0
+                             : reinterpret_cast<const int8_t*>(g_zero_page) + piece16;
+            }
             __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(gp[j] + static_cast<int64_t>(step) * BK),
+                (const __attribute__((address_space(1))) void*)src,
                 (__attribute__((address_space(3))) void*)(&lds[stage * STAGE_BYTES + (wave + j * NW) * 1024]),
                 16, 0, 0);
+        }
     };
 
     const int frow = lane & 31, fhalf = lane >> 5;
@@ -725,7 +760,7 @@ static int launch_dma(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t 
     hipLaunchKernelGGL((k_gemm_nt_dma<BM, BN, BK, WM, WN, STAGES, MODE, SCHED>), grid, block, 0, s, A, lda, B, ldb, C, \
                        ldc,                                                                                        \
                        static_cast<int>(M), static_cast<int>(N), static_cast<int>(K), k_per_split, eA, bitsA, eB,   \
-                       bitsB, tiles_m, tiles_n, group_m, split_stride, bt.a, bt.b, bt.c)
+                       bitsB, tiles_m, tiles_n, group_m, split_stride, bt.a, bt.b, bt.c, ConvTaps())
     if (mode == kStoreI32) FXP_GEMM_LAUNCH(kStoreI32);
     else if (mode == kStoreF32) FXP_GEMM_LAUNCH(kStoreF32);
     else FXP_GEMM_LAUNCH(kAtomicI32);
@@ -887,6 +922,25 @@ int gemm_nt_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda
     }
     if (!fp32_out) return rc;
     hipLaunchKernelGGL(k_unmap_rows, hgrid, dim3(256), 0, s, static_cast<int32_t*>(C), ldc, hr, hc, eA, bitsA, eB, bitsB);
+    return launch_status();
+}
+
+// Y[M, Cout] = unmap(patches(Xq) * Wq^T) with the patch matrix never stored (see k_gemm_nt_dma, CONV): M output
+// pixels, K = KH*KW*C.  Returns kNotApplicable when the shape needs the explicit patch matrix: channels not a
+// multiple of the 128-byte K step, a product that plan_gemm would split along K or give 256 x 256 tiles.
+int conv_gemm_launch(const ConvTaps& ct, int KH, int64_t M, int64_t Cout, const int8_t* Xq, const int8_t* Wq, float* Y,
+                     const int32_t* eA, int bitsA, const int32_t* eB, int bitsB, hipStream_t s) {
+    constexpr int BM = 128, BN = 128, BK = 128, WM = 64, WN = 32, STAGES = 4;
+    const int64_t K = static_cast<int64_t>(KH) * ct.KW * ct.C;
+    if (ct.C % BK != 0 || !aligned(Xq, 16) || !aligned(Wq, 16) || M <= 0 || Cout <= 0) return kNotApplicable;
+    const GemmPlan plan = plan_gemm(M, Cout, K);
+    if (plan.splits != 1 || plan.use256) return kNotApplicable;
+    const int tiles_m = static_cast<int>((M + BM - 1) / BM), tiles_n = static_cast<int>((Cout + BN - 1) / BN);
+    const dim3 grid(static_cast<unsigned>(tiles_m) * tiles_n), block((BM / WM) * (BN / WN) * 64);
+    hipLaunchKernelGGL((k_gemm_nt_dma<BM, BN, BK, WM, WN, STAGES, kStoreF32, true, true>), grid, block, 0, s, Xq, K, Wq, K,
+                       static_cast<void*>(Y), Cout, static_cast<int>(M), static_cast<int>(Cout), static_cast<int>(K),
+                       static_cast<int>(K), eA, bitsA, eB, bitsB, tiles_m, tiles_n, 8, int64_t{0}, int64_t{0}, int64_t{0},
+                       int64_t{0}, ct);
     return launch_status();
 }
 

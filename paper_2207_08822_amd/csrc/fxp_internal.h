@@ -47,6 +47,14 @@ int gemm_nt_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda
                    void* C, int64_t ldc, bool fp32_out, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB,
                    void* ws, size_t ws_bytes, hipStream_t s);
 size_t gemm_split_ws_bytes(int64_t M, int64_t N, int64_t K);
+// geometry of the patches an implicit-convolution GEMM reads: image H x W x C (channels-last), filter width
+// KW, stride, padding (rows / columns), output Ho x Wo
+struct ConvTaps {
+    int H = 0, W = 0, C = 1, KW = 1, stride = 1, pad = 0, padw = 0, Ho = 1, Wo = 1;
+};
+constexpr int kNotApplicable = 1;
+int conv_gemm_launch(const ConvTaps& ct, int KH, int64_t M, int64_t Cout, const int8_t* Xq, const int8_t* Wq, float* Y,
+                     const int32_t* eA, int bitsA, const int32_t* eB, int bitsB, hipStream_t s);
 size_t gemm_ws_worst(int64_t M, int64_t N, int64_t K);
 int transpose_i8_launch(const int8_t* src, int64_t rows, int64_t cols, int64_t ld, int8_t* dst, hipStream_t s);
 

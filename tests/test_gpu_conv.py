@@ -44,7 +44,11 @@ def check_conv(fxp, X, Wt, dY, stride, pad, seed=3, step=1, rounding=0, bits=8, 
 
 CASES = [  # N, H, W, C, Cout, KH, KW, stride, pad
     (2, 8, 8, 16, 16, 3, 3, 1, 1), (1, 7, 9, 3, 5, 3, 3, 2, 1), (2, 6, 6, 32, 8, 1, 1, 1, 0), (1, 12, 10, 4, 6, 3, 2, 2, 0),
-    (2, 9, 9, 20, 12, 5, 5, 1, 2), (3, 14, 14, 64, 48, 3, 3, 1, 1), (2, 16, 16, 16, 64, 3, 3, 2, 1), (1, 5, 5, 1, 1, 3, 3, 3, 1)]
+    (2, 9, 9, 20, 12, 5, 5, 1, 2), (3, 14, 14, 64, 48, 3, 3, 1, 1), (2, 16, 16, 16, 64, 3, 3, 2, 1), (1, 5, 5, 1, 1, 3, 3, 3, 1),
+    # channels a multiple of 128: the GEMM loader reads the patches straight from the int8 image (forward; input
+    # gradient too when Cout is a multiple of 128 and the stride is 1); ragged pixel counts, paddings 0..2, strides
+    (2, 9, 11, 128, 40, 3, 3, 1, 1), (1, 10, 10, 256, 128, 3, 2, 2, 0), (2, 7, 7, 128, 128, 5, 5, 1, 2),
+    (3, 6, 6, 128, 16, 1, 1, 1, 0), (2, 13, 9, 128, 256, 3, 3, 1, 0), (1, 20, 20, 128, 128, 3, 3, 1, 1)]
 
 
 @pytest.mark.parametrize("N,H,W,C,Cout,KH,KW,stride,pad", CASES)
@@ -69,6 +73,14 @@ def test_conv_modes_and_partial_gradients(fxp):
     check_conv(fxp, X, Wt, dY, 1, 1, need_dX=False)
     say("conv dX only")
     check_conv(fxp, X, Wt, dY, 1, 1, need_dW=False)
+    # 128 channels in and out: patches read by the GEMM loader, in the forward pass and in the input gradient
+    X = np.maximum(rng.standard_normal((2, 9, 9, 128)), 0).astype(np.float32)
+    Wt = (rng.standard_normal((128, 3, 3, 128)) * 0.03).astype(np.float32)
+    dY = rng.standard_normal((2, 9, 9, 128)).astype(np.float32) * 1e-4
+    say("conv 128 channels, dX only / dW only / nearest 4 bits")
+    check_conv(fxp, X, Wt, dY, 1, 1, need_dW=False)
+    check_conv(fxp, X, Wt, dY, 1, 1, need_dX=False)
+    check_conv(fxp, X, Wt, dY, 1, 1, rounding=1, bits=4)
 
 
 def test_conv_c2_layer_reduced_and_full(fxp):
