@@ -81,9 +81,11 @@ def bench_conv(args, torch, fxp, synth, dev):
     M, K, Cout = g["N"] * buf.Ho * buf.Wo, g["KH"] * g["KW"] * g["C"], g["Cout"]
     ops = 3 * 2.0 * M * K * Cout
     nx, nw, ny = X.size, Wt.size, dY.size
-    # algorithmic HBM bytes of every kernel of the step (convolution path)
-    step_bytes = (4 * nx + 5 * nx) + (4 * nw + 6 * nw) + (nx + M * K) + (M * K + nw + 4 * ny) \
-        + (4 * ny + 6 * ny) + (nx + M * K) + (M * K + ny + 4 * nw) + (ny + nw + 4 * M * K) + (4 * M * K + 4 * nx)
+    # algorithmic HBM bytes of every kernel of the step (convolution path): scale + map of X (one
+    # copy), W and dY (both copies); forward GEMM reading the image and the weights; transposed patches of X and the
+    # weight flip; weight-gradient GEMM; input-gradient GEMM reading the gradient image and the flipped weights
+    step_bytes = (4 * nx + 5 * nx) + (4 * nw + 6 * nw) + (nx + nw + 4 * ny) \
+        + (4 * ny + 6 * ny) + (nx + M * K) + 2 * nw + (M * K + ny + 4 * nw) + (ny + nw + 4 * nx)
     gbs = step_bytes / (ms * 1e-3) / 1e9
     cpu = None
     if not args.no_cpu_baseline:
@@ -106,10 +108,11 @@ def bench_conv(args, torch, fxp, synth, dev):
         "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": "c2conv: the c2 ResNet-18 3x3 convolution as a channels-last convolution layer "
                                f"N={g['N']} H=W={g['H']} C={g['C']} Cout={g['Cout']} (M={M} K={K})",
-                   "pass": "scale+map X, W, dY; int8 im2col; 3 int8 GEMMs; gather col2im + inverse map",
+                   "pass": "scale+map X, W, dY; forward and input-gradient GEMMs read their patches from the int8 images; "
+                           "transposed int8 patches + GEMM for the weight gradient",
                    "rounding": "stochastic (Philox-4x32-10)", "bits": args.bits},
         "roofline": dict(bound="hbm", achieved=round(gbs, 1), peak=PEAK_HBM_GBS, unit="GB/s",
-                         frac=round(gbs / PEAK_HBM_GBS, 4), kernel="whole step (12 kernels, all HBM-bound)",
+                         frac=round(gbs / PEAK_HBM_GBS, 4), kernel="whole step (9 kernels, all HBM-bound)",
                          algorithmic_per_launch=step_bytes, traffic=None),
         "cpu_baseline": cpu,
     }))
