@@ -1,7 +1,8 @@
 /*
- * fxp.h — C ABI of libfxp: the integer (dynamic fixed-point) linear-layer step
- * of "Is Integer Arithmetic Enough for Deep Learning Training?" (arXiv
- * 2207.08822) as hand-written HIP kernels for gfx950 (MI355X).
+ * fxp.h — C ABI of libfxp: the integer (dynamic fixed-point) layer step of "Is Integer
+ * Arithmetic Enough for Deep Learning Training?" (arXiv 2207.08822) - linear, convolution
+ * and batched-product layers, forward and backward, and the int16 weight update - as
+ * hand-written HIP kernels for gfx950 (MI355X).
  *
  * Conventions that hold for every call
  *  - Every data pointer is a DEVICE pointer unless the argument says "host".

@@ -40,7 +40,7 @@ extern "C" const char* fxp_strerror(int status) {
     }
 }
 
-extern "C" int fxp_version(void) { return 100; }
+extern "C" int fxp_version(void) { return 110; }
 
 extern "C" size_t fxp_workspace_bytes(int op, int64_t M, int64_t N, int64_t K) {
     if (M < 0 || N < 0 || K < 0) return 0;

@@ -83,6 +83,22 @@ def test_sgd16_step(fxp, n, lr, mu, wd):
     assert np.array_equal(host(gd), g)
 
 
+def test_sgd16_bench_size_full_oracle(fxp):
+    """The vector bench.py times (ResNet-18's parameter count, its recipe and hyper-parameters): every element of
+    w and v against the oracle over two consecutive steps."""
+    from paper_2207_08822_amd import synth
+    n = synth.RESNET18_PARAMS
+    say("sgd16 full size", n)
+    w, g, v = synth.sgd_tensors(n)
+    buf = fxp.SgdBuffers(n)
+    wd_, gd, vd = dev(w), dev(g), dev(v)
+    wo, vo = w, v
+    for step in range(2):
+        fxp.sgd16_step(wd_, gd, vd, buf, 0.1, 0.9, 5e-4, seed=0, step=step)
+        wo, vo = oracle.sgd16_step(wo, g, vo, 0.1, 0.9, 5e-4, seed=0, step=step)
+        assert same_bits(host(wd_), wo) and same_bits(host(vd), vo)
+
+
 def test_sgd16_rejects_bad_arguments(fxp):
     w = torch.zeros(16, device="cuda")
     buf = fxp.SgdBuffers(16)
