@@ -191,7 +191,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm_nt(
                 if (col >= N) continue;
                 const int64_t off = static_cast<int64_t>(row) * ldc + col;
                 if (MODE == kStoreF32)
-                    static_cast<float*>(Cv)[off] = unmap_value(acc[i][j][r], E);
+                    __builtin_nontemporal_store(unmap_value(acc[i][j][r], E), static_cast<float*>(Cv) + off);
                 else if (MODE == kStoreI32)
                     static_cast<int32_t*>(Cv)[off] = acc[i][j][r];
                 else
@@ -420,7 +420,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm_nt_dma(
                 if (col >= N) continue;
                 const int64_t off = static_cast<int64_t>(row) * ldc + col;
                 if (MODE == kStoreF32)
-                    static_cast<float*>(Cv)[off] = unmap_value(acc[i][j][r], E);
+                    __builtin_nontemporal_store(unmap_value(acc[i][j][r], E), static_cast<float*>(Cv) + off);
                 else if (MODE == kStoreI32)
                     static_cast<int32_t*>(Cv)[off] = acc[i][j][r];
                 else
@@ -605,7 +605,7 @@ __global__ __launch_bounds__((256 / WM) * (256 / WN) * 64) void k_gemm_nt_ring(
                 if (col >= N) continue;
                 const int64_t off = static_cast<int64_t>(row) * ldc + col;
                 if (MODE == kStoreF32)
-                    static_cast<float*>(Cv)[off] = unmap_value(acc[i][j][r], E);
+                    __builtin_nontemporal_store(unmap_value(acc[i][j][r], E), static_cast<float*>(Cv) + off);
                 else if (MODE == kStoreI32)
                     static_cast<int32_t*>(Cv)[off] = acc[i][j][r];
                 else
