@@ -328,6 +328,7 @@ def main():
         r["t"] += dt; r["launches"] += 1; r["bytes"] += nbytes; r["ops"] += ops
 
     gemm_rows = []
+    map_rotating_gbs = None
     lib, p = fxp.lib(), (lambda z: z.data_ptr())
     st = torch.cuda.current_stream().cuda_stream
     for layer, (X, W, dY), buf in zip(layers, dev_inputs, bufs):
@@ -345,7 +346,7 @@ def main():
         add("map", "k_map_tile<true, *>",
             timed(lambda: lib.fxp_map2(ctypes.byref(dX_), ctypes.byref(dW_), seed, 0, args.bits, st)),
             6.0 * (X.numel() + W.numel()))
-        if layer is layers[0]:
+        if layer is layers[0] and not args.copy_calibration:      # (counter runs keep to the launches of the step)
             # the same launch over a rotating set of inputs larger than the 256 MB Infinity Cache: every launch reads
             # its tensor from HBM ("rotating"); the row above re-reads one tensor ("warm", as inside a training step,
             # where the scale reduction has just read it)
@@ -455,7 +456,7 @@ def main():
                    "pass": "scale+map X,W,dY (int8, both orientations) + 3 int8 GEMMs with fused inverse map",
                    "rounding": "stochastic (Philox-4x32-10)", "bits": args.bits},
         "map_gbs": kernels["map"]["gbs"],
-        "map_activation_weight_launch_gbs_rotating_inputs": round(map_rotating_gbs, 1),
+        "map_activation_weight_launch_gbs_rotating_inputs": round(map_rotating_gbs, 1) if map_rotating_gbs else None,
         "roofline": roofline,
         "kernels": kernels,
         "gemms": gemm_rows,
