@@ -304,3 +304,38 @@ def test_layer_only_one_gradient(fxp):
 def test_binding_refuses_cpu_tensors(fxp):
     with pytest.raises(fxp.FxpError):
         fxp.scale(torch.zeros(4))
+
+
+def test_layer_step_replays_from_a_hip_graph(fxp):
+    """The layer calls only launch kernels (no allocation, no memset, no host read), so a step can be captured
+    into a HIP graph; every replay, with eager work of other steps in between, reproduces the eager result."""
+    say("graph capture of a layer step")
+    X, W, dY = synth.layer_tensors("c3", 0, scale_down=8)
+    M, K = X.shape
+    N = W.shape[1]
+    Xd, Wd, dYd = dev(X), dev(W), dev(dY)
+    buf = fxp.LayerBuffers(M, K, N)
+
+    def step(i):
+        fxp.linear_fwd(Xd, Wd, buf, seed=7, step=i)
+        fxp.linear_bwd(dYd, buf, seed=7, step=i)
+
+    step(5)
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (buf.Y, buf.dX, buf.dW, buf.Xq, buf.dYqT, buf.e)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step(5)                                    # warm-up on the side stream, as graph capture wants
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(5)
+    for other in (1, 2, 3):
+        step(other)                                # eager work that overwrites every buffer
+        torch.cuda.synchronize()
+        assert not torch.equal(buf.Xq, want[3])
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (buf.Y, buf.dX, buf.dW, buf.Xq, buf.dYqT, buf.e)
+        assert all(torch.equal(a, b) for a, b in zip(got, want))
