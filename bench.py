@@ -97,7 +97,7 @@ def bench_conv(args, torch, fxp, synth, dev):
     M, K, Cout = g["N"] * buf.Ho * buf.Wo, g["KH"] * g["KW"] * g["C"], g["Cout"]
     ops = 3 * 2.0 * M * K * Cout
     nx, nw, ny = X.size, Wt.size, dY.size
-    # algorithmic HBM bytes of every kernel of the step (convolution path): scale + map of X (one
+    # algorithmic HBM bytes of every kernel of the step: scale + map of X (one
     # copy), W and dY (both copies); forward GEMM reading the image and the weights; transposed patches of X and the
     # weight flip; weight-gradient GEMM; input-gradient GEMM reading the gradient image and the flipped weights
     step_bytes = (4 * nx + 5 * nx) + (4 * nw + 6 * nw) + (nx + nw + 4 * ny) \
