@@ -46,6 +46,7 @@ def lib():
         L.fxp_ref_map16.argtypes = [vp, u64, i32, vp, u64, u64, c.c_int]
         L.fxp_ref_axpy16.argtypes = [vp, vp, c.c_float, u64, vp, vp, u64, u64, c.c_int]
         L.fxp_ref_sgd16_step.argtypes = [vp, vp, vp, u64, c.c_float, c.c_float, c.c_float, vp, u64, u64, c.c_int]
+        L.fxp_ref_sgd16_step_multi.argtypes = [vp, vp, vp, vp, vp, u64, c.c_float, c.c_float, c.c_float, u64, u64, c.c_int]
         L.fxp_ref_conv2d_fwd_acc.argtypes = [vp, i64, i64, i64, i64, vp, i64, i64, i64, i64, i64, vp]
         L.fxp_ref_conv2d_bwd_input_acc.argtypes = [vp, vp] + cd + [vp]
         L.fxp_ref_conv2d_bwd_weight_acc.argtypes = [vp, vp] + cd + [vp]
@@ -308,3 +309,24 @@ def sgd16_step(w, g, v=None, lr=0.1, momentum=0.0, weight_decay=0.0, seed=0, ste
     _check(lib().fxp_ref_sgd16_step(_ptr(w), _ptr(g), _ptr(v), w.size, float(lr), float(momentum), float(weight_decay),
                                     _ptr(tmp), seed, step, rounding), "sgd16_step")
     return w, v
+
+
+def sgd16_step_multi(ws, gs, vs=None, lr=0.1, momentum=0.0, weight_decay=0.0, seed=0, step=0, rounding=STOCHASTIC):
+    """One step over a list of parameter tensors (own scales per tensor); returns (new ws, new vs), inputs untouched."""
+    import ctypes as c
+    ws = [_f32(w).copy() for w in ws]
+    gs = [_f32(g) for g in gs]
+    if momentum != 0.0:
+        vs = [(_f32(v).copy() if v is not None else np.zeros_like(w)) for v, w in zip(vs or [None] * len(ws), ws)]
+    else:
+        vs = None
+    tmps = [np.empty_like(w) for w in ws] if weight_decay != 0.0 else None
+    k = len(ws)
+
+    def ptrs(arrs):
+        return (c.c_void_p * k)(*[a.ctypes.data for a in arrs]) if arrs is not None else None
+
+    n = (c.c_uint64 * k)(*[w.size for w in ws])
+    _check(lib().fxp_ref_sgd16_step_multi(ptrs(ws), ptrs(gs), ptrs(vs), ptrs(tmps), n, k, float(lr), float(momentum),
+                                          float(weight_decay), seed, step, rounding), "sgd16_step_multi")
+    return ws, vs

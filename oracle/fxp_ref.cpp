@@ -618,4 +618,19 @@ int fxp_ref_sgd16_step(float* w, const float* g, float* v, uint64_t n, float lr,
     return fxp_ref_axpy16(w, d, -lr, n, w, nullptr, seed, 3 * step + 2, rounding);
 }
 
+// The same step for a list of parameter tensors, each with its own scales (one scale per tensor, Sec. 3.1): tensor t
+// is updated exactly as fxp_ref_sgd16_step would with the stream step (step << 16) | t, so that no two tensors
+// share random numbers.  Arrays of `count` pointers / sizes; v[t] and tmp[t] may be NULL as above.
+int fxp_ref_sgd16_step_multi(float* const* w, const float* const* g, float* const* v, float* const* tmp, const uint64_t* n,
+                             uint64_t count, float lr, float momentum, float wd, uint64_t seed, uint64_t step, int rounding) {
+    if (count > 65536 || step >= (uint64_t{1} << 32)) return -2;
+    if (count && (!w || !g || !n)) return -1;
+    for (uint64_t t = 0; t < count; ++t) {
+        const int rc = fxp_ref_sgd16_step(w[t], g[t], v ? v[t] : nullptr, n[t], lr, momentum, wd, tmp ? tmp[t] : nullptr, seed,
+                                          (step << 16) | t, rounding);
+        if (rc) return rc;
+    }
+    return 0;
+}
+
 }  // extern "C"

@@ -159,3 +159,22 @@ def test_sgd16_step_is_three_axpys_and_tracks_the_float_optimiser():
     w3, v3 = oracle.sgd16_step(w, g, v, lr, mu, 0.0, seed=9, step=4)
     v3r, _ = oracle.axpy16(g, v, mu, seed=9, step=13)
     assert np.array_equal(v3, v3r) and np.array_equal(w3, oracle.axpy16(w, v3r, -lr, seed=9, step=14)[0])
+
+
+def test_multi_tensor_step_is_the_single_step_per_tensor_with_its_own_streams():
+    rng = np.random.default_rng(31)
+    sizes = [5, 64, 1000, 1, 333]
+    ws = [(rng.standard_normal(n) * 10.0 ** -k).astype(np.float32) for k, n in enumerate(sizes)]   # very different scales
+    gs = [rng.laplace(0, 2e-3, n).astype(np.float32) for n in sizes]
+    vs = [rng.laplace(0, 1e-2, n).astype(np.float32) for n in sizes]
+    w1, v1 = oracle.sgd16_step_multi(ws, gs, vs, 0.1, 0.9, 5e-4, seed=4, step=7)
+    for t in range(len(sizes)):
+        wt, vt = oracle.sgd16_step(ws[t], gs[t], vs[t], 0.1, 0.9, 5e-4, seed=4, step=(7 << 16) | t)
+        assert np.array_equal(w1[t], wt) and np.array_equal(v1[t], vt)
+    # own scale per tensor: the tiny tensor keeps its relative precision (a shared scale would flush it to zero)
+    assert np.max(np.abs(w1[4] - ws[4])) > 0 and np.max(np.abs(w1[4])) < 1e-2
+    # two tensors with identical contents do not draw identical roundings
+    same, _ = oracle.sgd16_step_multi([ws[2], ws[2]], [gs[2], gs[2]], [vs[2], vs[2]], 0.1, 0.9, 5e-4, seed=4, step=7)
+    assert not np.array_equal(same[0], same[1])
+    w2, v2 = oracle.sgd16_step_multi(ws, gs, None, 0.05, 0.0, 0.0, seed=4, step=7)
+    assert v2 is None and np.array_equal(w2[1], oracle.sgd16_step(ws[1], gs[1], None, 0.05, seed=4, step=(7 << 16) | 1)[0])
