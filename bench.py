@@ -36,7 +36,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "c2conv", "vitb_attn", "sgd16"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "c2conv", "vitb_attn", "sgd16", "sgd16_multi"])
     ap.add_argument("--sigma", type=float, default=1.0, help="c5 only")
     ap.add_argument("--bits", type=int, default=8, help="width of the fixed-point values (8 = the paper's int8; 4..7 = its ablation)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -248,6 +248,64 @@ def bench_sgd(args, torch, fxp, synth, dev):
     }))
 
 
+def bench_sgd_multi(args, torch, fxp, synth, dev):
+    """int16 SGD step over the 62 parameter tensors of a ResNet-18 (own scales per tensor) through the multi-tensor
+    entry point; the same tensors through one fxp_sgd16_step call each are timed beside it."""
+    ws, gs, vs = synth.sgd_tensor_list()
+    wd_, gd, vd = ([torch.from_numpy(a).to(dev) for a in lst] for lst in (ws, gs, vs))
+    buf = fxp.SgdMultiBuffers(wd_, gd, vd)
+    n = sum(w.numel() for w in wd_)
+    single = fxp.SgdBuffers(max(w.numel() for w in wd_), device=dev)
+
+    def step(i):
+        fxp.sgd16_step_multi(buf, 0.1, 0.9, 5e-4, seed=0, step=i)
+
+    def step_per_tensor(i):
+        for t in range(len(wd_)):
+            fxp.sgd16_step(wd_[t], gd[t], vd[t], single, 0.1, 0.9, 5e-4, seed=0, step=(i << 16) | t)
+
+    def run(fn, steps):
+        for i in range(args.warmup):
+            fn(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            fn(args.warmup + i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    ms = run(step, args.steps)
+    ms_loop = run(step_per_tensor, max(3, args.steps // 5))
+    step_bytes = 48 * n
+    gbs = step_bytes / (ms * 1e-3) / 1e9
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+
+        def once(r):
+            tt = time.perf_counter()
+            oracle.sgd16_step_multi(ws, gs, vs, 0.1, 0.9, 5e-4, seed=0, step=r)
+            return time.perf_counter() - tt
+
+        reps, dt = repeat_to_target(once, args.cpu_seconds, most=400)
+        cpu = dict(value=round(n * reps / dt / 1e9, 6), unit="G elements/s", cores=oracle.num_threads(), kind="oracle",
+                   seconds=round(dt, 2), sample=f"{reps} steps over all {len(ws)} tensors ({n} parameters)")
+    print(json.dumps({
+        "metric": "int16 SGD step (weight decay + momentum) G elements/s", "value": round(n / (ms * 1e-3) / 1e9, 3),
+        "unit": "G elements/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int16", "data": "synthetic",
+        "config": {"workload": f"sgd16_multi: the {len(ws)} parameter tensors of a ResNet-18 ({n} parameters), one scale "
+                               "per tensor, lr 0.1, momentum 0.9, weight decay 5e-4",
+                   "pass": "4 launches: block maxima of w, g, v of every tensor; 3 fixed-point axpy lines over every tensor",
+                   "rounding": "stochastic (Philox-4x32-10)", "bits": 16},
+        "ms_per_step_one_call_per_tensor": round(ms_loop, 4),
+        "roofline": dict(bound="hbm", achieved=round(gbs, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                         frac=round(gbs / PEAK_HBM_GBS, 4), kernel="whole step (k_absmax_multi, 3 x k_axpy16_multi)",
+                         algorithmic_per_launch=step_bytes, traffic=None),
+        "cpu_baseline": cpu,
+    }))
+
+
 def main():
     args = parse_args()
     world = int(os.environ.get("WORLD_SIZE", "1"))
@@ -271,6 +329,8 @@ def main():
         return bench_attn(args, torch, fxp, synth, dev)
     if args.workload == "sgd16":
         return bench_sgd(args, torch, fxp, synth, dev)
+    if args.workload == "sgd16_multi":
+        return bench_sgd_multi(args, torch, fxp, synth, dev)
     layers = synth.WORKLOADS[args.workload]
     host_inputs, dev_inputs, bufs = [], [], []
     for li, layer in enumerate(layers):

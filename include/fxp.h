@@ -243,6 +243,24 @@ size_t fxp_sgd16_workspace_bytes(void);
 int fxp_sgd16_step(float* w, const float* g, float* v, size_t n, float lr, float momentum, float weight_decay, float* tmp,
                    uint64_t seed, uint64_t step, int rounding, void* ws, size_t ws_bytes, void* stream);
 
+/* The same step for a whole list of parameter tensors, each with its own scales (the method keeps one scale per
+ * tensor), in four launches per 64 tensors instead of six per tensor: what a model with dozens of parameter
+ * tensors needs, since a dependent launch costs several microseconds.  Tensor t is updated exactly as
+ * fxp_sgd16_step would update it with the stream step (step << 16) | t (so no two tensors share random numbers);
+ * count <= 65536, step < 2^32.  `tensors` is a HOST array of device pointers (v may be NULL without momentum,
+ * tmp without weight decay; n = 0 entries are skipped); it is only read during the call.
+ * ws: device, fxp_sgd16_multi_workspace_bytes(tensors, count) bytes. */
+typedef struct fxp_sgd_tensor {
+    float* w;
+    const float* g;
+    float* v;
+    float* tmp;
+    size_t n;
+} fxp_sgd_tensor;
+size_t fxp_sgd16_multi_workspace_bytes(const fxp_sgd_tensor* tensors, size_t count);
+int fxp_sgd16_step_multi(const fxp_sgd_tensor* tensors, size_t count, float lr, float momentum, float weight_decay,
+                         uint64_t seed, uint64_t step, int rounding, void* ws, size_t ws_bytes, void* stream);
+
 /* ---- convolution layer (Sec. 3.4: "Linear and convolutional layers" share the integer inner product) ----
  * Channels-last tensors: X[N,H,W,C], W[Cout,KH,KW,C], Y and dY [N,Ho,Wo,Cout] with
  * Ho = (H + 2 pad - KH) / stride + 1 (same for Wo), zero padding.  Host struct. */

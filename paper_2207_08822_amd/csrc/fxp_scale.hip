@@ -9,38 +9,6 @@
 
 namespace fxp {
 
-__device__ inline uint32_t absmax4(const uint4 v) {
-    const uint32_t kAbs = 0x7fffffffu;
-    return max(max(v.x & kAbs, v.y & kAbs), max(v.z & kAbs, v.w & kAbs));
-}
-
-// block maxima of one tensor: block `bid` of `nblocks`
-__device__ inline void absmax_body(const uint32_t* __restrict__ x, size_t n, uint32_t* __restrict__ partials, unsigned bid,
-                                   unsigned nblocks, uint32_t* lds) {
-    const uint32_t kAbs = 0x7fffffffu;
-    uint32_t m = 0;
-    // scalar head up to 16-byte alignment, vector body, scalar tail
-    const size_t mis = (reinterpret_cast<uintptr_t>(x) >> 2) & 3u;
-    size_t head = mis ? 4 - mis : 0;
-    if (head > n) head = n;
-    const size_t nvec = (n - head) >> 2;
-    const uint4* xv = reinterpret_cast<const uint4*>(x + head);
-    const size_t tid = static_cast<size_t>(bid) * kScaleThreads + threadIdx.x;
-    const size_t stride = static_cast<size_t>(nblocks) * kScaleThreads;
-    size_t i = tid;
-    for (; i + 3 * stride < nvec; i += 4 * stride) {
-        const uint4 a = xv[i], b = xv[i + stride], c = xv[i + 2 * stride], d = xv[i + 3 * stride];
-        m = max(max(m, absmax4(a)), max(absmax4(b), max(absmax4(c), absmax4(d))));
-    }
-    for (; i < nvec; i += stride) m = max(m, absmax4(xv[i]));
-    if (bid == 0) {
-        if (threadIdx.x < head) m = max(m, x[threadIdx.x] & kAbs);
-        const size_t tail0 = head + (nvec << 2);
-        if (tail0 + threadIdx.x < n) m = max(m, x[tail0 + threadIdx.x] & kAbs);
-    }
-    m = block_max(m, lds);
-    if (threadIdx.x == 0) partials[bid] = m;
-}
 
 // Up to two tensors per launch: the first blocks0 workgroups reduce tensor 0, the others tensor 1.
 __global__ __launch_bounds__(kScaleThreads) void k_absmax_partials(const uint32_t* __restrict__ x0, size_t n0,

@@ -111,13 +111,14 @@ __device__ inline uint32_t word_of(const uint4& r, uint32_t k) { return k == 0 ?
 // VEC: x, y, z are 16-byte aligned; a thread owns whole quads of four consecutive elements (16-byte loads and
 // stores, both Philox blocks of the quad used in full) and block 0 finishes the n % 4 tail.  Otherwise one
 // element per thread and iteration.
+// Workgroup `bid` of the `nblocks` that share one line over one tensor.
 template <bool STOCH, bool VEC>
-__global__ __launch_bounds__(kAxpyThreads) void k_axpy16(const uint32_t* x, const uint32_t* y, uint32_t a_bits, uint64_t n,
-                                                         float* z, const uint32_t* __restrict__ px, int npx,
-                                                         const uint32_t* __restrict__ py, int npy,
-                                                         uint32_t* __restrict__ pz, int32_t* __restrict__ e_out,
-                                                         uint32_t key0, uint32_t key1, uint64_t step) {
-    __shared__ uint32_t red[kAxpyThreads / 64];
+__device__ __attribute__((always_inline)) inline void axpy16_body(const uint32_t* x, const uint32_t* y, uint32_t a_bits,
+                                                                  uint64_t n, float* z, const uint32_t* __restrict__ px,
+                                                                  int npx, const uint32_t* __restrict__ py, int npy,
+                                                                  uint32_t* __restrict__ pz, int32_t* __restrict__ e_out,
+                                                                  uint32_t key0, uint32_t key1, uint64_t step, unsigned bid,
+                                                                  unsigned nblocks, uint32_t* red) {
     // scales of the two tensors from their block maxima, the scalar's from its own exponent
     uint32_t mx = 0, my = 0;
     for (int i = threadIdx.x; i < npx; i += kAxpyThreads) mx = max(mx, px[i]);
@@ -127,7 +128,7 @@ __global__ __launch_bounds__(kAxpyThreads) void k_axpy16(const uint32_t* x, cons
     const int ex = __builtin_amdgcn_readfirstlane(max(1, static_cast<int>(block_max(mx, red) >> 23)));
     const int ey = __builtin_amdgcn_readfirstlane(max(1, static_cast<int>(block_max(my, red) >> 23)));
     const int ea = max(1, static_cast<int>((a_bits >> 23) & 0xffu));
-    if (e_out != nullptr && blockIdx.x == 0 && threadIdx.x == 0) {
+    if (e_out != nullptr && bid == 0 && threadIdx.x == 0) {
         e_out[0] = ex;
         e_out[1] = ey;
         e_out[2] = ea;
@@ -147,8 +148,8 @@ __global__ __launch_bounds__(kAxpyThreads) void k_axpy16(const uint32_t* x, cons
     };
 
     uint32_t zmax = 0;
-    const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kAxpyThreads;
-    const uint64_t first = static_cast<uint64_t>(blockIdx.x) * kAxpyThreads + threadIdx.x;
+    const uint64_t stride = static_cast<uint64_t>(nblocks) * kAxpyThreads;
+    const uint64_t first = static_cast<uint64_t>(bid) * kAxpyThreads + threadIdx.x;
     if (VEC) {
         const uint64_t quads = n >> 2;
         const uint4* xv = reinterpret_cast<const uint4*>(x);
@@ -205,7 +206,7 @@ __global__ __launch_bounds__(kAxpyThreads) void k_axpy16(const uint32_t* x, cons
         if (al.left < 0 && al.right < 32 && Ex >= -126 && Ex <= 127) quad_loop(IC<true>{});
         else quad_loop(IC<false>{});
         const uint32_t tail = static_cast<uint32_t>(n & 3u);
-        if (blockIdx.x == 0 && threadIdx.x < tail) {
+        if (bid == 0 && threadIdx.x < tail) {
             uint4 rxy, ru;
             blocks_of(quads, rxy, ru);
             const uint64_t i = (quads << 2) + threadIdx.x;
@@ -224,7 +225,85 @@ __global__ __launch_bounds__(kAxpyThreads) void k_axpy16(const uint32_t* x, cons
         }
     }
     zmax = block_max(zmax, red);
-    if (pz != nullptr && threadIdx.x == 0) pz[blockIdx.x] = zmax;
+    if (pz != nullptr && threadIdx.x == 0) pz[bid] = zmax;
+}
+
+template <bool STOCH, bool VEC>
+__global__ __launch_bounds__(kAxpyThreads) void k_axpy16(const uint32_t* x, const uint32_t* y, uint32_t a_bits, uint64_t n,
+                                                         float* z, const uint32_t* __restrict__ px, int npx,
+                                                         const uint32_t* __restrict__ py, int npy,
+                                                         uint32_t* __restrict__ pz, int32_t* __restrict__ e_out,
+                                                         uint32_t key0, uint32_t key1, uint64_t step) {
+    __shared__ uint32_t red[kAxpyThreads / 64];
+    axpy16_body<STOCH, VEC>(x, y, a_bits, n, z, px, npx, py, npy, pz, e_out, key0, key1, step, blockIdx.x, gridDim.x, red);
+}
+
+// ---- many parameter tensors per launch ------------------------------------------------------------------
+// Up to kMaxJobs tensors travel in the kernel argument segment.  Tensor t owns workgroups
+// [block0, block0 + blocks) of every launch of a step and the same range of each block-maxima array, so a
+// line finds the scales of its operands (and leaves those of its result) without any launch in between.
+constexpr int kMaxJobs = 64;
+struct SgdJob {
+    float* w;
+    const float* g;
+    float* v;
+    float* tmp;
+    uint64_t n;
+    uint32_t block0, blocks;
+    uint32_t index;      // position of the tensor in the caller's list: part of its random-stream id
+};
+struct SgdJobs {
+    SgdJob j[kMaxJobs];
+    int count;
+};
+
+__device__ inline int job_of_block(const SgdJobs& jobs, unsigned b) {   // last job whose block0 <= b
+    int lo = 0, hi = jobs.count - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (jobs.j[mid].block0 <= b) lo = mid;
+        else hi = mid - 1;
+    }
+    return lo;
+}
+
+// block maxima of w, g and (blockIdx.y == 2) v of every tensor
+__global__ __launch_bounds__(kScaleThreads) void k_absmax_multi(const SgdJobs jobs, uint32_t* __restrict__ pw,
+                                                                uint32_t* __restrict__ pg, uint32_t* __restrict__ pv) {
+    __shared__ uint32_t lds[kScaleThreads / 64];
+    const SgdJob& J = jobs.j[job_of_block(jobs, blockIdx.x)];
+    const float* x = blockIdx.y == 0 ? J.w : (blockIdx.y == 1 ? J.g : J.v);
+    uint32_t* p = blockIdx.y == 0 ? pw : (blockIdx.y == 1 ? pg : pv);
+    absmax_body(reinterpret_cast<const uint32_t*>(x), J.n, p + J.block0, blockIdx.x - J.block0, J.blocks, lds);
+}
+
+// one line of the step for every tensor: line 0: tmp = g + wd w; 1: v = x1 + momentum v; 2: w = w + (-lr) d, where
+// x1 is tmp when line 0 ran, else g, and d is v when line 1 ran, else x1.  px / py: block maxima of x / y; pz: of z.
+template <bool STOCH>
+__global__ __launch_bounds__(kAxpyThreads) void k_axpy16_multi(const SgdJobs jobs, int line, int have_wd, int have_mom,
+                                                               uint32_t a_bits, const uint32_t* __restrict__ px,
+                                                               const uint32_t* __restrict__ py, uint32_t* __restrict__ pz,
+                                                               uint32_t key0, uint32_t key1, uint64_t step) {
+    __shared__ uint32_t red[kAxpyThreads / 64];
+    const int t = job_of_block(jobs, blockIdx.x);
+    const SgdJob& J = jobs.j[t];
+    const float* x1 = have_wd ? J.tmp : J.g;
+    const float* x = line == 0 ? J.g : (line == 1 ? x1 : J.w);
+    const float* y = line == 0 ? J.w : (line == 1 ? J.v : (have_mom ? J.v : x1));
+    float* z = line == 0 ? J.tmp : (line == 1 ? J.v : J.w);
+    // the random streams of tensor t: those of a single-tensor step with step (step << 16) | t, three lines each
+    const uint64_t line_step = 3 * ((step << 16) | static_cast<uint64_t>(J.index)) + line;
+    const bool vec = ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(y) | reinterpret_cast<uintptr_t>(z)) & 15u) == 0;
+    const unsigned bid = blockIdx.x - J.block0;
+    const uint32_t* xb = reinterpret_cast<const uint32_t*>(x);
+    const uint32_t* yb = reinterpret_cast<const uint32_t*>(y);
+    uint32_t* pzt = pz ? pz + J.block0 : nullptr;
+    if (vec)
+        axpy16_body<STOCH, true>(xb, yb, a_bits, J.n, z, px + J.block0, J.blocks, py + J.block0, J.blocks, pzt, nullptr, key0, key1,
+                                 line_step, bid, J.blocks, red);
+    else
+        axpy16_body<STOCH, false>(xb, yb, a_bits, J.n, z, px + J.block0, J.blocks, py + J.block0, J.blocks, pzt, nullptr, key0, key1,
+                                  line_step, bid, J.blocks, red);
 }
 
 // grid of one line over n elements: at most kMaxPartials blocks, so that pz fits a scale scratch area
@@ -325,4 +404,93 @@ extern "C" int fxp_sgd16_step(float* w, const float* g, float* v, size_t n, floa
     }
     // w = w + (-lr) * d
     return axpy16_launch(w, d, -lr, n, w, pw, npw, pd, npd, nullptr, nullptr, seed, 3 * step + 2, rounding, s);
+}
+
+namespace fxp {
+// workgroups of one tensor in every launch of a multi-tensor step: eight quads or more per thread, at most 1024
+static uint32_t multi_blocks(size_t n) {
+    const uint64_t want = (((static_cast<uint64_t>(n) + 3) >> 2) + kAxpyThreads * 8 - 1) / (kAxpyThreads * 8);
+    return static_cast<uint32_t>(want < 1 ? 1 : (want > 1024 ? 1024 : want));
+}
+}  // namespace fxp
+
+extern "C" size_t fxp_sgd16_multi_workspace_bytes(const fxp_sgd_tensor* tensors, size_t count) {
+    if (!tensors) return 0;
+    size_t blocks = 0;
+    for (size_t t = 0; t < count; ++t)
+        if (tensors[t].n) blocks += fxp::multi_blocks(tensors[t].n);
+    return 5 * sizeof(uint32_t) * (blocks ? blocks : 1);
+}
+
+extern "C" int fxp_sgd16_step_multi(const fxp_sgd_tensor* tensors, size_t count, float lr, float momentum, float weight_decay,
+                                    uint64_t seed, uint64_t step, int rounding, void* ws, size_t ws_bytes, void* stream) {
+    using namespace fxp;
+    if (count > 65536 || step >= (uint64_t{1} << 32)) return FXP_ERR_DIMS;
+    if (rounding != FXP_ROUND_STOCHASTIC && rounding != FXP_ROUND_NEAREST) return FXP_ERR_ROUNDING;
+    if (count == 0) return FXP_OK;
+    if (!tensors) return FXP_ERR_NULL;
+    const bool have_wd = weight_decay != 0.0f, have_mom = momentum != 0.0f;
+    size_t total_blocks = 0;
+    for (size_t t = 0; t < count; ++t) {
+        const fxp_sgd_tensor& T = tensors[t];
+        if (T.n >= (size_t{1} << 40)) return FXP_ERR_DIMS;
+        if (T.n == 0) continue;
+        if (!T.w || !T.g || (have_mom && !T.v) || (have_wd && !T.tmp)) return FXP_ERR_NULL;
+        if (!aligned(T.w, 4) || !aligned(T.g, 4) || !aligned(T.v, 4) || !aligned(T.tmp, 4)) return FXP_ERR_ALIGN;
+        total_blocks += multi_blocks(T.n);
+    }
+    if (total_blocks == 0) return FXP_OK;
+    if (!ws || ws_bytes < 5 * sizeof(uint32_t) * total_blocks) return FXP_ERR_WORKSPACE;
+    if (!aligned(ws, 4)) return FXP_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint32_t* pw = static_cast<uint32_t*>(ws);       // block maxima of w, g, v, g1 = g + wd w, and the new v
+    uint32_t* pg = pw + total_blocks;
+    uint32_t* pv = pg + total_blocks;
+    uint32_t* pt = pv + total_blocks;
+    uint32_t* pn = pt + total_blocks;
+    const uint32_t k0 = static_cast<uint32_t>(seed), k1 = static_cast<uint32_t>(seed >> 32);
+    auto bits_of = [](float a) {
+        uint32_t b;
+        __builtin_memcpy(&b, &a, sizeof b);
+        return b;
+    };
+    size_t t = 0, block_base = 0;                    // block_base: offset of this launch group in the maxima arrays
+    while (t < count) {
+        SgdJobs jobs;
+        jobs.count = 0;
+        uint32_t blocks = 0;
+        for (; t < count && jobs.count < kMaxJobs; ++t) {
+            const fxp_sgd_tensor& T = tensors[t];
+            if (T.n == 0) continue;
+            SgdJob& J = jobs.j[jobs.count++];
+            J.w = T.w; J.g = T.g; J.v = T.v; J.tmp = T.tmp; J.n = T.n;
+            J.block0 = blocks;
+            J.blocks = multi_blocks(T.n);
+            J.index = static_cast<uint32_t>(t);
+            blocks += J.blocks;
+        }
+        if (jobs.count == 0) break;
+        uint32_t* w_ = pw + block_base; uint32_t* g_ = pg + block_base; uint32_t* v_ = pv + block_base;
+        uint32_t* t_ = pt + block_base; uint32_t* n_ = pn + block_base;
+        hipLaunchKernelGGL(k_absmax_multi, dim3(blocks, have_mom ? 3 : 2), dim3(kScaleThreads), 0, s, jobs, w_, g_, v_);
+        int rc = launch_status();
+        if (rc) return rc;
+#define FXP_LINE(LINE, A, PX, PY, PZ)                                                                                      \
+    do {                                                                                                                   \
+        if (rounding == FXP_ROUND_STOCHASTIC)                                                                              \
+            hipLaunchKernelGGL(k_axpy16_multi<true>, dim3(blocks), dim3(kAxpyThreads), 0, s, jobs, LINE, int(have_wd),      \
+                               int(have_mom), bits_of(A), PX, PY, PZ, k0, k1, step);                                        \
+        else                                                                                                               \
+            hipLaunchKernelGGL(k_axpy16_multi<false>, dim3(blocks), dim3(kAxpyThreads), 0, s, jobs, LINE, int(have_wd),     \
+                               int(have_mom), bits_of(A), PX, PY, PZ, k0, k1, step);                                        \
+        if ((rc = launch_status())) return rc;                                                                             \
+    } while (0)
+        const uint32_t* x1 = have_wd ? t_ : g_;
+        if (have_wd) FXP_LINE(0, weight_decay, g_, w_, t_);
+        if (have_mom) FXP_LINE(1, momentum, x1, v_, n_);
+        FXP_LINE(2, -lr, w_, (have_mom ? n_ : x1), static_cast<uint32_t*>(nullptr));
+#undef FXP_LINE
+        block_base += blocks;
+    }
+    return FXP_OK;
 }

@@ -31,6 +31,11 @@ class _MapDesc(ctypes.Structure):
                 ("q", ctypes.c_void_p), ("qT", ctypes.c_void_p), ("stream_id", ctypes.c_uint64)]
 
 
+class _SgdTensor(ctypes.Structure):
+    _fields_ = [("w", ctypes.c_void_p), ("g", ctypes.c_void_p), ("v", ctypes.c_void_p), ("tmp", ctypes.c_void_p),
+                ("n", ctypes.c_size_t)]
+
+
 class _ConvShape(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int64) for n in ("N", "H", "W", "C", "Cout", "KH", "KW", "stride", "pad")]
 
@@ -84,6 +89,10 @@ def lib():
     L.fxp_scale_map2.argtypes = [c.POINTER(_MapDesc), c.POINTER(_MapDesc), u64, ci, ci, vp, sz, vp]
     L.fxp_map2.restype = ci
     L.fxp_scale_map2.restype = ci
+    L.fxp_sgd16_multi_workspace_bytes.restype = sz
+    L.fxp_sgd16_multi_workspace_bytes.argtypes = [c.POINTER(_SgdTensor), sz]
+    L.fxp_sgd16_step_multi.argtypes = [c.POINTER(_SgdTensor), sz, c.c_float, c.c_float, c.c_float, u64, u64, ci, vp, sz, vp]
+    L.fxp_sgd16_step_multi.restype = ci
     L.fxp_sgd16_workspace_bytes.restype = sz
     L.fxp_sgd16_workspace_bytes.argtypes = []
     L.fxp_axpy16.argtypes = [vp, vp, c.c_float, sz, vp, vp, u64, u64, ci, vp, sz, vp]
@@ -440,3 +449,26 @@ def scale_map2(xa, xb, seed=0, stream_ids=(0, 1), rounding=STOCHASTIC, bits=8):
     _check(lib().fxp_scale_map2(ctypes.byref(da), ctypes.byref(db), seed, rounding, bits, _p(ws), ws.numel(), _stream()),
            "fxp_scale_map2")
     return e, outs[0], outs[1]
+
+
+class SgdMultiBuffers:
+    """Descriptor table and scratch for the multi-tensor int16 SGD step over fixed lists of parameter tensors."""
+
+    def __init__(self, ws, gs, vs=None, weight_decay=True):
+        k = len(ws)
+        for t in list(ws) + list(gs) + [v for v in (vs or []) if v is not None]:
+            _dev(t, torch.float32, "parameter tensors")
+        self.tmps = [torch.empty_like(w) for w in ws] if weight_decay else [None] * k
+        self.keep = (list(ws), list(gs), list(vs) if vs is not None else None)      # the table holds raw pointers
+        self.table = (_SgdTensor * k)(*[
+            _SgdTensor(_p(ws[t]), _p(gs[t]), _p(vs[t]) if vs is not None else None, _p(self.tmps[t]), ws[t].numel())
+            for t in range(k)])
+        self.count = k
+        nbytes = int(lib().fxp_sgd16_multi_workspace_bytes(self.table, k))
+        self.ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=ws[0].device)
+
+
+def sgd16_step_multi(buf, lr, momentum=0.0, weight_decay=0.0, seed=0, step=0, rounding=STOCHASTIC):
+    """In-place SGD step on every tensor of buf (own scales per tensor), a handful of launches in all."""
+    _check(lib().fxp_sgd16_step_multi(buf.table, buf.count, float(lr), float(momentum), float(weight_decay), seed, step,
+                                      rounding, _p(buf.ws), buf.ws.numel(), _stream()), "fxp_sgd16_step_multi")

@@ -169,3 +169,35 @@ def sgd_tensors(n=RESNET18_PARAMS, seed=1):
     """fp32 (w, g, v): N(0, 0.05) weights, N(0, 2e-3) gradients, N(0, 1e-2) momentum buffer."""
     rng = np.random.Generator(np.random.PCG64([seed, 79]))
     return _normal(rng, (n,), 0.05), _normal(rng, (n,), 2e-3), _normal(rng, (n,), 1e-2)
+
+
+def resnet18_parameter_sizes():
+    """Element counts of the 62 parameter tensors of a ResNet-18 classifier (7x7 stem, four stages of two basic
+    blocks at 64/128/256/512 channels with 1x1 projection shortcuts where the shape changes, 1000-way head),
+    in definition order: every convolution is followed by the scale and shift of its batch-norm."""
+    sizes = [64 * 3 * 7 * 7, 64, 64]
+    cin = 64
+    for stage, cout in enumerate((64, 128, 256, 512)):
+        for block in range(2):
+            c_in = cin if block == 0 else cout
+            sizes += [cout * c_in * 9, cout, cout, cout * cout * 9, cout, cout]
+            if block == 0 and c_in != cout:
+                sizes += [cout * c_in, cout, cout]
+        cin = cout
+    sizes += [1000 * 512, 1000]
+    assert sum(sizes) == RESNET18_PARAMS and len(sizes) == 62
+    return sizes
+
+
+def sgd_tensor_list(sizes=None, seed=1):
+    """Per-tensor fp32 (w, g, v) lists: weights N(0, 2/n-ish scale differing per tensor), gradients and momentum
+    three and one orders of magnitude below, so that every tensor has its own scale."""
+    sizes = sizes if sizes is not None else resnet18_parameter_sizes()
+    rng = np.random.Generator(np.random.PCG64([seed, 80]))
+    ws, gs, vs = [], [], []
+    for n in sizes:
+        sigma = float(np.sqrt(2.0 / max(n, 64)) * 8.0)
+        ws.append(_normal(rng, (n,), sigma))
+        gs.append(_normal(rng, (n,), sigma * 2e-2))
+        vs.append(_normal(rng, (n,), sigma * 1e-1))
+    return ws, gs, vs

@@ -115,3 +115,25 @@ def test_argument_errors_of_the_layer_level_entry_points():
     ok_shape = Shape(2, 8, 8, 16, 16, 3, 3, 1, 1)
     assert L.fxp_conv2d_workspace_bytes(ctypes.byref(ok_shape), 0) >= 2 * 8 * 8 * 9 * 16
     assert L.fxp_conv2d_workspace_bytes(ctypes.byref(Shape(2, 2, 2, 16, 16, 5, 5, 1, 0)), 0) == 0   # kernel larger than image
+
+
+def test_argument_errors_of_the_multi_tensor_update():
+    L = load()
+    vp, u64, ci, sz, fl = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int, ctypes.c_size_t, ctypes.c_float
+
+    class T(ctypes.Structure):
+        _fields_ = [("w", vp), ("g", vp), ("v", vp), ("tmp", vp), ("n", sz)]
+
+    L.fxp_sgd16_multi_workspace_bytes.restype = sz
+    L.fxp_sgd16_multi_workspace_bytes.argtypes = [ctypes.POINTER(T), sz]
+    L.fxp_sgd16_step_multi.argtypes = [ctypes.POINTER(T), sz, fl, fl, fl, u64, u64, ci, vp, sz, vp]
+    tab = (T * 3)(T(1 << 20, 1 << 20, None, None, 100), T(None, None, None, None, 0), T(1 << 21, 1 << 21, None, None, 5_000_000))
+    need = L.fxp_sgd16_multi_workspace_bytes(tab, 3)
+    assert need == 5 * 4 * (1 + 611)                       # ceil(1.25 M quads / 2048) = 611 workgroups, none for n = 0
+    ws = vp(1 << 22)
+    assert L.fxp_sgd16_step_multi(tab, 3, 0.1, 0.9, 0.0, 0, 0, 0, ws, need, None) == -1      # momentum without v
+    assert L.fxp_sgd16_step_multi(tab, 3, 0.1, 0.0, 1e-4, 0, 0, 0, ws, need, None) == -1     # weight decay without tmp
+    assert L.fxp_sgd16_step_multi(tab, 3, 0.1, 0.0, 0.0, 0, 0, 0, ws, need - 1, None) == -4
+    assert L.fxp_sgd16_step_multi(tab, 3, 0.1, 0.0, 0.0, 0, 1 << 32, 0, ws, need, None) == -2
+    assert L.fxp_sgd16_step_multi(tab, 3, 0.1, 0.0, 0.0, 0, 0, 5, ws, need, None) == -5
+    assert L.fxp_sgd16_step_multi(None, 0, 0.1, 0.0, 0.0, 0, 0, 0, None, 0, None) == 0       # nothing to do

@@ -109,3 +109,49 @@ def test_sgd16_rejects_bad_arguments(fxp):
     assert L.fxp_sgd16_step(p(w), p(w), None, 16, 0.1, 0.0, 0.0, None, 0, 0, 0, p(buf.ws), 16, None) == -4
     assert L.fxp_sgd16_step(p(w), p(w), None, 16, 0.1, 0.0, 0.0, None, 0, 0, 7, p(buf.ws), buf.ws.numel(), None) == -5
     assert L.fxp_axpy16(p(w), None, 0.1, 16, p(w), None, 0, 0, 0, p(buf.ws), buf.ws.numel(), None) == -1
+
+
+@pytest.mark.parametrize("lr,mu,wd", [(0.1, 0.9, 5e-4), (0.05, 0.0, 0.0), (0.01, 0.9, 0.0), (0.05, 0.0, 1e-4)])
+def test_sgd16_step_multi(fxp, lr, mu, wd):
+    """Lists of tensors of very different sizes and scales (more than one launch group: 70 tensors), odd lengths and
+    4-byte-aligned views: every tensor equals the oracle's single-tensor step with its own stream."""
+    say("sgd16 multi", lr, mu, wd)
+    rng = np.random.default_rng(17)
+    sizes = [5, 64, 1000, 1, 333, 70000, 4096, 3_000_001] + [int(s) for s in rng.integers(1, 5000, 62)]
+    ws = [(rng.standard_normal(n) * 10.0 ** -(k % 5)).astype(np.float32) for k, n in enumerate(sizes)]
+    gs = [rng.laplace(0, 2e-3, n).astype(np.float32) * np.float32(10.0 ** -(k % 3)) for k, n in enumerate(sizes)]
+    vs = [rng.laplace(0, 1e-2, n).astype(np.float32) for n in sizes] if mu != 0.0 else None
+    # one flat device buffer per kind with odd offsets: most views are only 4-byte aligned
+    def views(arrs):
+        flat = torch.empty(sum(a.size + 1 for a in arrs), dtype=torch.float32, device="cuda")
+        out, off = [], 0
+        for a in arrs:
+            v = flat[off:off + a.size]
+            v.copy_(torch.from_numpy(a))
+            out.append(v)
+            off += a.size + 1
+        return out
+    wd_, gd = views(ws), views(gs)
+    vd = views(vs) if vs is not None else None
+    buf = fxp.SgdMultiBuffers(wd_, gd, vd, weight_decay=(wd != 0.0))
+    wo, vo = ws, vs
+    for step in range(2):
+        fxp.sgd16_step_multi(buf, lr, mu, wd, seed=3, step=step)
+        wo, vo = oracle.sgd16_step_multi(wo, gs, vo, lr, mu, wd, seed=3, step=step)
+        for t in range(len(sizes)):
+            assert same_bits(host(wd_[t]), wo[t]), (step, t, sizes[t])
+            if mu != 0.0:
+                assert same_bits(host(vd[t]), vo[t]), (step, t, sizes[t])
+
+
+def test_sgd16_step_multi_resnet18_list(fxp):
+    """The bench's list (62 tensors of ResNet-18's sizes): every tensor against the oracle."""
+    from paper_2207_08822_amd import synth
+    say("sgd16 multi resnet18")
+    ws, gs, vs = synth.sgd_tensor_list()
+    wd_, gd, vd = [dev(a) for a in ws], [dev(a) for a in gs], [dev(a) for a in vs]
+    buf = fxp.SgdMultiBuffers(wd_, gd, vd)
+    fxp.sgd16_step_multi(buf, 0.1, 0.9, 5e-4, seed=0, step=0)
+    wo, vo = oracle.sgd16_step_multi(ws, gs, vs, 0.1, 0.9, 5e-4, seed=0, step=0)
+    for t in range(len(ws)):
+        assert same_bits(host(wd_[t]), wo[t]) and same_bits(host(vd[t]), vo[t]), t
