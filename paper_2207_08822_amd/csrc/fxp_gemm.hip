@@ -257,18 +257,24 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm_nt_dma(
     A += static_cast<int64_t>(blockIdx.z) * batch_a;
     B += static_cast<int64_t>(blockIdx.z) * batch_b;
     const int ke = min(K, kb + k_per_split);
-    const int nk = (ke - kb) / BK;
+    // whole K steps, plus one partial step when the slice ends inside a step (K a multiple of 16, not of BK):
+    // its missing 16-byte pieces are read from the page of zeros, so the multiply loop never sees a tail
+    const int nk = (ke - kb + BK - 1) / BK;
+    const int tail = (ke - kb) % BK;
+
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS targets stay in SGPRs
     const int wm0 = (wave / (BN / WN)) * WM, wn0 = (wave % (BN / WN)) * WN;
 
     const int8_t* gp[RPW];
+    int kpiece[RPW];                                                 // offset of the lane's 16-byte piece inside a K step
     int a_h0[RPW], a_w0[RPW];                                        // CONV: top-left input coordinate of the row's patch
 #pragma unroll
     for (int j = 0; j < RPW; ++j) {
         const int row_t = (wave + j * NW) * RROWS + lane / CPR;      // row in the stacked (A;B) tile
         const int piece = (lane % CPR) ^ swizzle_of_row<BK>(row_t);  // BM % 16 == 0: same swizzle for B rows
+        kpiece[j] = piece * 16;
         a_h0[j] = a_w0[j] = 0;
         if (CONV && row_t < BM) {
             const uint32_t m = static_cast<uint32_t>(min(m0 + row_t, M - 1));
@@ -289,16 +295,17 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm_nt_dma(
             kh = tap / ct.KW;
             kw = tap - kh * ct.KW;
         }
+        const bool partial = !CONV && tail != 0 && step == nk - 1;   // wave-uniform
 #pragma unroll
         for (int j = 0; j < RPW; ++j) {
             const int8_t* src = gp[j] + static_cast<int64_t>(step) * BK;
+            if (partial && kpiece[j] >= tail) src = reinterpret_cast<const int8_t*>(g_zero_page) + kpiece[j];
             if (CONV && (wave + j * NW) * RROWS < BM) {              // a region of A rows (wave-uniform)
                 const int h = a_h0[j] + kh, w = a_w0[j] + kw;
                 const bool inside = static_cast<unsigned>(h) < static_cast<unsigned>(ct.H) &&
                                     static_cast<unsigned>(w) < static_cast<unsigned>(ct.W);
-                const int piece16 = ((lane % CPR) ^ swizzle_of_row<BK>((wave + j * NW) * RROWS + lane / CPR)) * 16;
                 src = inside ? gp[j] + (static_cast<int64_t>(h) * ct.W + w) * ct.C + c0
-                             : reinterpret_cast<const int8_t*>(g_zero_page) + piece16;
+                             : reinterpret_cast<const int8_t*>(g_zero_page) + kpiece[j];
             }
             __builtin_amdgcn_global_load_lds(
                 (const __attribute__((address_space(1))) void*)src,
@@ -855,7 +862,7 @@ int gemm_nt_batched_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int
     if (M == 0 || N == 0 || batch == 0) return FXP_OK;
     const bool vec = aligned(A, 16) && aligned(B, 16) && lda % 16 == 0 && ldb % 16 == 0 && K % 16 == 0 && strideA % 16 == 0 &&
                      strideB % 16 == 0;
-    const bool dma = vec && K > 0 && K % 64 == 0;
+    const bool dma = vec && K >= 64;   // K % 16 == 0: the direct-to-LDS kernels pad a partial last step with zeros
     const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
     const bool use256 = M >= 256 && N >= 256 && t256 * batch >= 96;
     const int mode = fp32_out ? kStoreF32 : kStoreI32;
@@ -872,6 +879,8 @@ int gemm_nt_batched_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int
     }
     if (use256 && K % 128 == 0) return launch_ring<64, 128>(FXP_BATCHED_ARGS, FXP_BATCHED_TAIL);
     if (use256) return launch_dma<256, 256, 64, 64, 128, 4>(FXP_BATCHED_ARGS, FXP_BATCHED_TAIL);
+    // narrow outputs (head width 64 of the attention context and of dQ, dK, dV): a tile of their own width
+    if (N <= 64) return launch_dma<128, 64, 64, 64, 32, 4>(FXP_BATCHED_ARGS, FXP_BATCHED_TAIL);
     // one or two steps along K (scores = Q K^T with head width 64): two stages, more workgroups per CU
     if (K <= 128) return launch_dma<128, 128, 64, 64, 64, 2>(FXP_BATCHED_ARGS, FXP_BATCHED_TAIL);
     if (K % 128 == 0) return launch_dma<128, 128, 128, 64, 32, 4>(FXP_BATCHED_ARGS, FXP_BATCHED_TAIL);
@@ -885,7 +894,7 @@ int gemm_nt_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda
                    void* ws, size_t ws_bytes, hipStream_t s) {
     if (M == 0 || N == 0) return FXP_OK;
     const bool vec = aligned(A, 16) && aligned(B, 16) && lda % 16 == 0 && ldb % 16 == 0 && K % 16 == 0;
-    const bool dma = vec && K > 0 && K % 64 == 0;
+    const bool dma = vec && K >= 64;   // K % 16 == 0: the direct-to-LDS kernels pad a partial last step with zeros
     const GemmPlan plan = plan_gemm(M, N, K);
     const int splits = plan.splits;
     const bool use256 = plan.use256;
