@@ -285,7 +285,7 @@ size_t fxp_conv2d_workspace_bytes(const fxp_conv2d_shape* shape, int backward);
 
 /* Forward: the activation tensor is mapped once as a whole (element index = its channels-last flat index,
  * FXP_TAG_X), the weights likewise (FXP_TAG_W); the int8 patches are multiplied on the matrix cores - read
- * straight from the int8 activation by the GEMM loader when C is a multiple of 128, gathered into scratch
+ * straight from the int8 activation by the GEMM loader when C is a multiple of 64, gathered into scratch
  * first otherwise - and Y receives the inverse-mapped fp32 result.  Contraction KH*KW*C <= 133144. */
 int fxp_conv2d_fwd(const float* X, const float* W, const fxp_conv2d_shape* shape, float* Y, const fxp_conv_saved* saved,
                    uint64_t seed, uint64_t step, int rounding, int bits, void* ws, size_t ws_bytes, void* stream);

@@ -936,14 +936,11 @@ int gemm_nt_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda
 
 // Y[M, Cout] = unmap(patches(Xq) * Wq^T) with the patch matrix never stored (see k_gemm_nt_dma, CONV): M output
 // pixels, K = KH*KW*C.  Returns kNotApplicable when the shape needs the explicit patch matrix: channels not a
-// multiple of the 128-byte K step, a product that plan_gemm would split along K or give 256 x 256 tiles.
-int conv_gemm_launch(const ConvTaps& ct, int KH, int64_t M, int64_t Cout, const int8_t* Xq, const int8_t* Wq, float* Y,
-                     const int32_t* eA, int bitsA, const int32_t* eB, int bitsB, hipStream_t s) {
-    constexpr int BM = 128, BN = 128, BK = 128, WM = 64, WN = 32, STAGES = 4;
-    const int64_t K = static_cast<int64_t>(KH) * ct.KW * ct.C;
-    if (ct.C % BK != 0 || !aligned(Xq, 16) || !aligned(Wq, 16) || M <= 0 || Cout <= 0) return kNotApplicable;
-    const GemmPlan plan = plan_gemm(M, Cout, K);
-    if (plan.splits != 1 || plan.use256) return kNotApplicable;
+// multiple of 64 (the smallest K step), a product that plan_gemm would split along K or give 256 x 256 tiles.
+template <int BK, int WN>
+static int conv_gemm_launch_cfg(const ConvTaps& ct, int64_t K, int64_t M, int64_t Cout, const int8_t* Xq, const int8_t* Wq,
+                                float* Y, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB, hipStream_t s) {
+    constexpr int BM = 128, BN = 128, WM = 64, STAGES = 4;
     const int tiles_m = static_cast<int>((M + BM - 1) / BM), tiles_n = static_cast<int>((Cout + BN - 1) / BN);
     const dim3 grid(static_cast<unsigned>(tiles_m) * tiles_n), block((BM / WM) * (BN / WN) * 64);
     hipLaunchKernelGGL((k_gemm_nt_dma<BM, BN, BK, WM, WN, STAGES, kStoreF32, true, true>), grid, block, 0, s, Xq, K, Wq, K,
@@ -951,6 +948,17 @@ int conv_gemm_launch(const ConvTaps& ct, int KH, int64_t M, int64_t Cout, const 
                        static_cast<int>(K), eA, bitsA, eB, bitsB, tiles_m, tiles_n, 8, int64_t{0}, int64_t{0}, int64_t{0},
                        int64_t{0}, ct);
     return launch_status();
+}
+
+int conv_gemm_launch(const ConvTaps& ct, int KH, int64_t M, int64_t Cout, const int8_t* Xq, const int8_t* Wq, float* Y,
+                     const int32_t* eA, int bitsA, const int32_t* eB, int bitsB, hipStream_t s) {
+    const int64_t K = static_cast<int64_t>(KH) * ct.KW * ct.C;
+    if (ct.C % 64 != 0 || !aligned(Xq, 16) || !aligned(Wq, 16) || M <= 0 || Cout <= 0) return kNotApplicable;
+    const GemmPlan plan = plan_gemm(M, Cout, K);
+    if (plan.splits != 1 || plan.use256) return kNotApplicable;
+    // one K step = one run of channels of one filter tap: 128 channels (8 waves) where C allows, else 64 (4 waves)
+    if (ct.C % 128 == 0) return conv_gemm_launch_cfg<128, 32>(ct, K, M, Cout, Xq, Wq, Y, eA, bitsA, eB, bitsB, s);
+    return conv_gemm_launch_cfg<64, 64>(ct, K, M, Cout, Xq, Wq, Y, eA, bitsA, eB, bitsB, s);
 }
 
 static int check_gemm_args(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, int transA, const void* B,

@@ -48,7 +48,9 @@ CASES = [  # N, H, W, C, Cout, KH, KW, stride, pad
     # channels a multiple of 128: the GEMM loader reads the patches straight from the int8 image (forward; input
     # gradient too when Cout is a multiple of 128 and the stride is 1); ragged pixel counts, paddings 0..2, strides
     (2, 9, 11, 128, 40, 3, 3, 1, 1), (1, 10, 10, 256, 128, 3, 2, 2, 0), (2, 7, 7, 128, 128, 5, 5, 1, 2),
-    (3, 6, 6, 128, 16, 1, 1, 1, 0), (2, 13, 9, 128, 256, 3, 3, 1, 0), (1, 20, 20, 128, 128, 3, 3, 1, 1)]
+    (3, 6, 6, 128, 16, 1, 1, 1, 0), (2, 13, 9, 128, 256, 3, 3, 1, 0), (1, 20, 20, 128, 128, 3, 3, 1, 1),
+    # 64 and 192 channels: the 64-byte K step
+    (2, 12, 12, 64, 64, 3, 3, 1, 1), (1, 9, 7, 192, 64, 3, 3, 2, 1), (2, 8, 8, 64, 192, 5, 3, 1, 0)]
 
 
 @pytest.mark.parametrize("N,H,W,C,Cout,KH,KW,stride,pad", CASES)
