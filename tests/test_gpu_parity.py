@@ -288,6 +288,25 @@ def test_layer_ragged_shapes(fxp):
         layer_check_full(fxp, X, W, dY, seed=4, step=1)
 
 
+def test_layer_random_shapes(fxp):
+    """Seeded random layer shapes, half of them multiples of 16 (direct-to-LDS kernels with partial K steps in all
+    three products), the rest arbitrary (element-wise loaders): the whole step against the oracle."""
+    rng = np.random.default_rng(2024)
+    shapes = []
+    for k in range(28):
+        M, K, N = (int(v) for v in rng.integers(1, 700, 3))
+        if k % 2 == 0:
+            M, K, N = (max(16, v // 16 * 16) for v in (M, K, N))
+        shapes.append((M, K, N))
+    shapes += [(1040, 208, 464), (4112, 80, 1040), (272, 4240, 144)]      # several tiles, ragged, K tails, split-K
+    for (M, K, N) in shapes:
+        say("layer random", (M, K, N))
+        X = rng.standard_normal((M, K)).astype(np.float32)
+        W = (rng.standard_normal((K, N)) * 0.1).astype(np.float32)
+        dY = rng.laplace(0, 1e-3, (M, N)).astype(np.float32)
+        layer_check_full(fxp, X, W, dY, seed=M, step=K % 5)
+
+
 def test_layer_only_one_gradient(fxp):
     say("layer dW only / dX only")
     X, W, dY = synth.layer_tensors("c1")
