@@ -92,3 +92,25 @@ def test_conv_c2_layer_reduced_and_full(fxp):
     say("conv c2 geometry, batch 32 (full oracle, ~22 G integer MACs)")
     X, Wt, dY, g = synth.conv_tensors()
     check_conv(fxp, X, Wt, dY, g["stride"], g["pad"], seed=0, step=0)
+
+
+def test_conv_random_geometries(fxp):
+    """Seeded random geometries: channel counts on and off the implicit path, kernels 1..5, strides 1..2, paddings
+    0..2, non-square images."""
+    rng = np.random.default_rng(77)
+    done = 0
+    while done < 14:
+        N, H, W = int(rng.integers(1, 4)), int(rng.integers(3, 15)), int(rng.integers(3, 15))
+        C = int(rng.choice([3, 8, 20, 64, 128, 192]))
+        Cout = int(rng.choice([1, 6, 16, 64, 128]))
+        KH, KW = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        stride, pad = int(rng.integers(1, 3)), int(rng.integers(0, 3))
+        if H + 2 * pad < KH or W + 2 * pad < KW:
+            continue
+        say("conv random", (N, H, W, C, Cout, KH, KW, stride, pad))
+        X = np.maximum(rng.standard_normal((N, H, W, C)), 0).astype(np.float32)
+        Wt = (rng.standard_normal((Cout, KH, KW, C)) * 0.1).astype(np.float32)
+        Ho, Wo = oracle.conv_out_hw(H, W, KH, KW, stride, pad)
+        dY = rng.laplace(0, 1e-3, (N, Ho, Wo, Cout)).astype(np.float32)
+        check_conv(fxp, X, Wt, dY, stride, pad, seed=done, step=done % 3)
+        done += 1
