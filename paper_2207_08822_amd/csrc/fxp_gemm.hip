@@ -247,29 +247,32 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm_nt_dma(
 
     __shared__ __attribute__((aligned(1024))) int8_t lds[STAGES * STAGE_BYTES];
 
-    // Workgroups reach the XCDs round-robin in dispatch order (x fastest, then y).  One slice: the tile walk of
-    // tile_of_block.  Split along K: XCD c takes a contiguous run of (slice, tile) pairs in slice-major order, so
-    // the tiles of a slice, which all read the same K range of B, share that XCD's L2.
-    int tm, tn, slice = 0;
-    if (gridDim.y == 1) {
+    // Workgroups reach the XCDs round-robin in dispatch order (x fastest, then y, then z).  One product, one slice:
+    // the tile walk of tile_of_block.  Split along K, or a batch of products: XCD c takes a contiguous run of
+    // (slice or matrix, tile) pairs in slice-major order, so the tiles of one slice (which read the same K range of
+    // B) or of one small matrix (which read the same operands) share that XCD's L2.
+    int tm, tn, slice = 0, matrix = 0;
+    const int outer = static_cast<int>(gridDim.y * gridDim.z);     // never both: a batch is not split
+    if (outer == 1) {
         tile_of_block(blockIdx.x, tiles_m, tiles_n, group_m, &tm, &tn);
     } else {
-        const int tiles = tiles_m * tiles_n, total = tiles * static_cast<int>(gridDim.y);
-        const int v = static_cast<int>(blockIdx.y * gridDim.x + blockIdx.x);
-        const int q = total / kNumXcd, r = total % kNumXcd, xcd = v % kNumXcd, local = v / kNumXcd;
-        const int p = (xcd < r) ? xcd * (q + 1) + local : r * (q + 1) + (xcd - r) * q + local;
-        slice = p / tiles;
-        const int t = p - slice * tiles;
+        const int64_t tiles = static_cast<int64_t>(tiles_m) * tiles_n, total = tiles * outer;
+        const int64_t v = (static_cast<int64_t>(blockIdx.z) * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
+        const int64_t q = total / kNumXcd, r = total % kNumXcd, xcd = v % kNumXcd, local = v / kNumXcd;
+        const int64_t p = (xcd < r) ? xcd * (q + 1) + local : r * (q + 1) + (xcd - r) * q + local;
+        const int o = static_cast<int>(p / tiles), t = static_cast<int>(p - o * tiles);
+        if (gridDim.y > 1) slice = o;
+        else matrix = o;
         tm = t % tiles_m;
         tn = t / tiles_m;
     }
     const int m0 = tm * BM, n0 = tn * BN;
     const int kb = slice * k_per_split;
     // split-K into a workspace: every slice owns its own M x N int32 matrix (split_stride elements apart)
-    Cv = static_cast<int32_t*>(Cv) + static_cast<int64_t>(slice) * split_stride + static_cast<int64_t>(blockIdx.z) * batch_c;
+    Cv = static_cast<int32_t*>(Cv) + static_cast<int64_t>(slice) * split_stride + static_cast<int64_t>(matrix) * batch_c;
     // batched product: matrix z of each operand lies batch_* elements further on
-    A += static_cast<int64_t>(blockIdx.z) * batch_a;
-    B += static_cast<int64_t>(blockIdx.z) * batch_b;
+    A += static_cast<int64_t>(matrix) * batch_a;
+    B += static_cast<int64_t>(matrix) * batch_b;
     const int ke = min(K, kb + k_per_split);
     // whole K steps, plus one partial step when the slice ends inside a step (K a multiple of 16, not of BK):
     // its missing 16-byte pieces are read from the page of zeros, so the multiply loop never sees a tail
