@@ -384,8 +384,8 @@ def main():
     rows = {}   # kernel row -> totals over one step
 
     def add(row, kernel, dt, nbytes, ops=0.0):
-        r = rows.setdefault(row, dict(kernel=kernel, t=0.0, launches=0, bytes=0.0, ops=0.0))
-        r["t"] += dt; r["launches"] += 1; r["bytes"] += nbytes; r["ops"] += ops
+        r = rows.setdefault(row, dict(kernel=kernel, t=0.0, tmin=0.0, launches=0, bytes=0.0, ops=0.0))
+        r["t"] += dt; r["tmin"] += timed.last_min; r["launches"] += 1; r["bytes"] += nbytes; r["ops"] += ops
 
     gemm_rows = []
     map_rotating_gbs = None
@@ -459,6 +459,7 @@ def main():
                     algorithmic_per_launch=(c["ops"] if roofline["bound"] == "mfma" else c["bytes"]) / c["launches"],
                     traffic=read_traffic(args.workload, dominant))
     kernels = {k: dict(kernel=v["kernel"], launches_per_step=v["launches"], us_per_step=round(v["t"] * 1e6, 2),
+                       us_per_step_min=round(v["tmin"] * 1e6, 2),
                        gbs=round(v["bytes"] / v["t"] / 1e9, 1),
                        tops=(round(v["ops"] / v["t"] / 1e12, 1) if v["ops"] else None)) for k, v in rows.items()}
 
