@@ -358,3 +358,28 @@ def test_layer_step_replays_from_a_hip_graph(fxp):
         torch.cuda.synchronize()
         got = (buf.Y, buf.dX, buf.dW, buf.Xq, buf.dYqT, buf.e)
         assert all(torch.equal(a, b) for a, b in zip(got, want))
+
+
+def test_empty_operands_are_no_ops(fxp):
+    """Zero-sized tensors: every entry point returns FXP_OK and writes nothing."""
+    say("empty operands")
+    L = fxp.lib()
+    p = lambda t: t.data_ptr()
+    guard = torch.full((64,), 7, dtype=torch.int32, device="cuda")
+    e = torch.tensor([130], dtype=torch.int32, device="cuda")
+    ws = torch.empty(8192, dtype=torch.uint8, device="cuda")
+    x = torch.zeros(16, dtype=torch.float32, device="cuda")
+    q = torch.full((16,), 5, dtype=torch.int8, device="cuda")
+    assert L.fxp_map(p(x), 0, 16, p(e), p(q), None, 0, 0, 0, 8, None) == 0
+    assert L.fxp_map(p(x), 16, 0, p(e), p(q), None, 0, 0, 0, 8, None) == 0
+    assert L.fxp_scale_map(p(x), 0, 16, p(e), p(q), None, 0, 0, 0, 8, p(ws), ws.numel(), None) == 0
+    torch.cuda.synchronize()
+    assert int(e[0]) == 1 and bool((q == 5).all())              # the scale of an empty tensor is 1; q untouched
+    A = torch.ones((16, 16), dtype=torch.int8, device="cuda")
+    assert L.fxp_gemm(0, 1, 0, 16, 16, p(A), 16, p(A), 16, p(guard), 16, None, 0, None) == 0
+    assert L.fxp_gemm(0, 1, 16, 0, 16, p(A), 16, p(A), 16, p(guard), 16, None, 0, None) == 0
+    assert L.fxp_gemm_batched(16, 16, 16, p(A), 16, 0, p(A), 16, 0, p(guard), 16, 256, 0, None) == 0
+    assert L.fxp_unmap(p(guard), 0, p(e), 8, p(e), 8, p(x), None) == 0
+    assert L.fxp_axpy16(p(x), p(x), 0.5, 0, p(x), None, 0, 0, 0, p(ws), ws.numel(), None) == 0
+    torch.cuda.synchronize()
+    assert bool((guard == 7).all()) and bool((x == 0).all())
