@@ -122,6 +122,26 @@ def test_scale_map_fused_equals_two_calls(fxp):
         assert np.array_equal(host(q), want) and np.array_equal(host(qT), want.T)
 
 
+REUSE_SHAPES = [(256, 256), (300, 516), (1000, 64), (777, 192), (4099, 640), (25088, 128), (12608, 768), (5, 8)]
+
+
+def test_scale_map_reuses_its_scratch_area(fxp):
+    """fxp_scale_map with one scratch area from call to call: the block maxima a tensor with a larger scale left
+    there (or any other bytes) do not leak into the next tensor's scale."""
+    ws = torch.full((2 * fxp.workspace_bytes(fxp.OP_SCALE, 0),), 0xA5, dtype=torch.uint8, device="cuda")
+    for i, shape in enumerate(REUSE_SHAPES):
+        say("scale_map scratch reuse", shape)
+        rng = np.random.default_rng(100 + i)
+        x = (rng.standard_normal(shape) * 0.37).astype(np.float32)
+        for scale_up in (4096.0, 1.0):
+            xs = (x * np.float32(scale_up)).astype(np.float32)
+            e_ref = oracle.scale(xs)
+            want = oracle.map(xs, e_ref, seed=11, stream_id=3)
+            e, q, qT = fxp.scale_map(dev(xs), 11, 3, want_q=True, want_qT=True, ws=ws)
+            assert int(host(e)[0]) == e_ref
+            assert np.array_equal(host(q), want) and np.array_equal(host(qT), want.T)
+
+
 PAIRS = [((300, 516), (516, 40)), ((4000, 1152), (1152, 128)), ((64, 64), (640, 192)), ((100, 7), (64, 64)),
          ((2600, 1024), (1024, 1024)), ((33, 64), (70, 128))]
 
@@ -367,7 +387,7 @@ def test_empty_operands_are_no_ops(fxp):
     p = lambda t: t.data_ptr()
     guard = torch.full((64,), 7, dtype=torch.int32, device="cuda")
     e = torch.tensor([130], dtype=torch.int32, device="cuda")
-    ws = torch.empty(8192, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(2 * fxp.workspace_bytes(fxp.OP_SCALE, 0), dtype=torch.uint8, device="cuda")
     x = torch.zeros(16, dtype=torch.float32, device="cuda")
     q = torch.full((16,), 5, dtype=torch.int8, device="cuda")
     assert L.fxp_map(p(x), 0, 16, p(e), p(q), None, 0, 0, 0, 8, None) == 0
