@@ -96,11 +96,15 @@ __global__ __launch_bounds__(256) void k_flip_weights_i8(const int8_t* __restric
     flip_weights_body(Wq, g, WqF, blockIdx.x, gridDim.x);
 }
 
-// colT[(tap*C + c)][m] for a tile of 64 consecutive m x 64 channels of one tap.  Each thread reads a
-// 4 (m) x 4 (c) block as four dwords, transposes it in registers, parks the four "4 consecutive m of one
+// colT[(tap*C + c)][m] for a tile of 128 consecutive m x TCH = 64 channels of one tap (128 bytes of a colT row: whole
+// cache lines; 14.0 -> 12.0 us on the ResNet layer against 64-byte pieces; 128 channels per tile, whole lines on
+// the read side too, or 256 output pixels changed nothing or lost).  Each thread reads
+// 4 (m) x 4 (c) blocks as four dwords each, transposes them in registers, parks the "4 consecutive m of one
 // channel" dwords in LDS and the block then writes 16-byte pieces along m.  Needs C % 4 == 0.
 // Workgroups beyond the tile_blocks tiles flip the weights for the input-gradient convolution (Wq -> WqF;
 // flip_blocks of them, possibly 0): two independent pieces of the backward pass in one launch.
+constexpr int kColTileM = 128;
+template <int TCH>
 __global__ __launch_bounds__(256) void k_im2col_t_i8(const int8_t* __restrict__ Xq, ConvGeo g, int8_t* __restrict__ colT,
                                                      int tiles_m, int tiles_c, unsigned tile_blocks,
                                                      const int8_t* __restrict__ Wq, int8_t* __restrict__ WqF) {
@@ -108,38 +112,51 @@ __global__ __launch_bounds__(256) void k_im2col_t_i8(const int8_t* __restrict__ 
         flip_weights_body(Wq, g, WqF, blockIdx.x - tile_blocks, gridDim.x - tile_blocks);
         return;
     }
-    __shared__ uint32_t t[64 * 17];                              // [channel][16 dwords of m] + 1 pad
+    constexpr int TS = kColTileM / 4 + 1;                        // dwords per staged channel (+ 1 pad)
+    constexpr int CG = TCH / 4, MG = 256 / CG;                   // channel groups x row groups per round
+    constexpr int ROUNDS = kColTileM / 4 / MG;                   // groups of 4 rows per thread
+    __shared__ uint32_t t[TCH * TS];                             // [channel][32 dwords of m]
+    __shared__ PatchRow rows[kColTileM];
     int b = blockIdx.x;
     const int tc = b % tiles_c; b /= tiles_c;
     const int tm = b % tiles_m;
     const int tap = b / tiles_m;
     const int kh = tap / g.KW, kw = tap - kh * g.KW;
-    const int64_t m0 = static_cast<int64_t>(tm) * 64, M = g.M();
-    const int c0 = tc * 64;
-    const int cg = threadIdx.x & 15, mg = threadIdx.x >> 4;     // 16 channel groups x 16 row groups
-    __shared__ PatchRow rows[64];
-    if (threadIdx.x < 64 && m0 + threadIdx.x < M) rows[threadIdx.x] = patch_row(g, static_cast<uint32_t>(m0) + threadIdx.x);
+    const int64_t m0 = static_cast<int64_t>(tm) * kColTileM, M = g.M();
+    const int c0 = tc * TCH;
+    const int cg = threadIdx.x % CG, mg = threadIdx.x / CG;
+    if (threadIdx.x < kColTileM && m0 + threadIdx.x < M) rows[threadIdx.x] = patch_row(g, static_cast<uint32_t>(m0) + threadIdx.x);
     __syncthreads();
     const int64_t tap_off = (static_cast<int64_t>(kh) * g.W + kw) * g.C + c0 + 4 * cg;
-    uint32_t v[4];
+    uint32_t v[ROUNDS][4];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        v[k] = 0;
-        if (m0 + 4 * mg + k < M && c0 + 4 * cg < g.C) {
-            const PatchRow pr = rows[4 * mg + k];
-            const int h = pr.h0 + kh, w = pr.w0 + kw;
-            if (h >= 0 && h < g.H && w >= 0 && w < g.W) v[k] = *reinterpret_cast<const uint32_t*>(Xq + pr.base + tap_off);
+    for (int r = 0; r < ROUNDS; ++r) {
+        const int rg = mg + MG * r;                              // group of 4 rows
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            v[r][k] = 0;
+            if (m0 + 4 * rg + k < M && c0 + 4 * cg < g.C) {
+                const PatchRow pr = rows[4 * rg + k];
+                const int h = pr.h0 + kh, w = pr.w0 + kw;
+                if (h >= 0 && h < g.H && w >= 0 && w < g.W) v[r][k] = *reinterpret_cast<const uint32_t*>(Xq + pr.base + tap_off);
+            }
         }
     }
 #pragma unroll
-    for (int c = 0; c < 4; ++c)
-        t[(4 * cg + c) * 17 + mg] = ((v[0] >> (8 * c)) & 0xffu) | (((v[1] >> (8 * c)) & 0xffu) << 8) |
-                                    (((v[2] >> (8 * c)) & 0xffu) << 16) | (((v[3] >> (8 * c)) & 0xffu) << 24);
+    for (int r = 0; r < ROUNDS; ++r)
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            t[(4 * cg + c) * TS + mg + MG * r] = ((v[r][0] >> (8 * c)) & 0xffu) | (((v[r][1] >> (8 * c)) & 0xffu) << 8) |
+                                                 (((v[r][2] >> (8 * c)) & 0xffu) << 16) | (((v[r][3] >> (8 * c)) & 0xffu) << 24);
     __syncthreads();
-    const int c = threadIdx.x >> 2, ch = threadIdx.x & 3;       // channel row, 16-byte piece along m
-    if (c0 + c < g.C) {
+    constexpr int PIECES = kColTileM / 16;                       // 16-byte pieces of a staged channel
+#pragma unroll
+    for (int it = 0; it < TCH * PIECES / 256; ++it) {
+        const int id = it * 256 + threadIdx.x;
+        const int c = id / PIECES, ch = id % PIECES;             // channel row, 16-byte piece along m
+        if (c0 + c >= g.C) continue;
         int8_t* dst = colT + (static_cast<int64_t>(tap) * g.C + c0 + c) * M + m0 + 16 * ch;
-        const uint32_t* src = t + c * 17 + 4 * ch;
+        const uint32_t* src = t + c * TS + 4 * ch;
         if ((M & 15) == 0 && m0 + 16 * ch + 16 <= M) {
             *reinterpret_cast<uint4*>(dst) = make_uint4(src[0], src[1], src[2], src[3]);
         } else {
@@ -215,7 +232,7 @@ __global__ __launch_bounds__(256) void k_col2im_unmap(const int32_t* __restrict_
                 if (wo >= g.Wo) continue;
                 const int32_t* src = dcol + ((static_cast<int64_t>(n) * g.Ho + ho) * g.Wo + wo) * K +
                                      static_cast<int64_t>(kh * g.KW + kw) * g.C + c;
-                if (VEC == 4) {
+                if constexpr (VEC == 4) {
                     const int4 q = *reinterpret_cast<const int4*>(src);
                     acc[0] += q.x; acc[1] += q.y; acc[2] += q.z; acc[3] += q.w;
                 } else {
@@ -224,7 +241,7 @@ __global__ __launch_bounds__(256) void k_col2im_unmap(const int32_t* __restrict_
             }
         }
         float* dst = dX + ((static_cast<int64_t>(n) * g.H + h) * g.W + w) * g.C + c;
-        if (VEC == 4) {
+        if constexpr (VEC == 4) {
             *reinterpret_cast<float4*>(dst) = make_float4(unmap_value(acc[0], E), unmap_value(acc[1], E),
                                                           unmap_value(acc[2], E), unmap_value(acc[3], E));
         } else {
@@ -365,15 +382,17 @@ extern "C" int fxp_conv2d_bwd(const float* dY, const fxp_conv_saved* saved, cons
     }
     if (dW) {
         int8_t* colT = reinterpret_cast<int8_t*>(area);
-        const int tiles_m = static_cast<int>((M + 63) / 64), tiles_c = (g.C + 63) / 64;
+        const bool quads = g.C % 4 == 0;                        // the dword kernel takes 128 output pixels per tile
+        const int tch = 64;                                     // channels per tile
+        const int tiles_m = static_cast<int>(quads ? (M + kColTileM - 1) / kColTileM : (M + 63) / 64), tiles_c = (g.C + tch - 1) / tch;
         const int64_t blocks = static_cast<int64_t>(g.KH) * g.KW * tiles_m * tiles_c;
         if (blocks >= (int64_t{1} << 31)) return FXP_ERR_DIMS;
         // the flipped weights of the input-gradient convolution ride along in the same launch
         const unsigned flip_blocks = need_flip ? grid_for(static_cast<int64_t>(g.Cout) * K) : 0u;
         if (blocks + flip_blocks >= (int64_t{1} << 31)) return FXP_ERR_DIMS;
         const dim3 tgrid(static_cast<unsigned>(blocks) + flip_blocks);
-        if (g.C % 4 == 0)
-            hipLaunchKernelGGL(k_im2col_t_i8, tgrid, dim3(256), 0, s, saved->Xq, g, colT, tiles_m, tiles_c,
+        if (quads)
+            hipLaunchKernelGGL(k_im2col_t_i8<64>, tgrid, dim3(256), 0, s, saved->Xq, g, colT, tiles_m, tiles_c,
                                static_cast<unsigned>(blocks), saved->Wq, saved->WqF);
         else
             hipLaunchKernelGGL(k_im2col_t_i8_bytes, tgrid, dim3(256), 0, s, saved->Xq, g, colT, tiles_m, tiles_c,
