@@ -32,6 +32,7 @@ def lib():
         L.fxp_ref_random_word.restype = u32
         L.fxp_ref_scale.argtypes = [vp, u64, vp]
         L.fxp_ref_map.argtypes = [vp, i64, i64, i32, vp, vp, u64, u64, c.c_int, c.c_int]
+        L.fxp_ref_map_rows.argtypes = [vp, i64, i64, i64, i32, vp, u64, u64, c.c_int, c.c_int]
         L.fxp_ref_gemm.argtypes = [c.c_int, c.c_int, i64, i64, i64, vp, i64, vp, i64, vp, i64]
         L.fxp_ref_unmap.argtypes = [vp, u64, i32, c.c_int, i32, c.c_int, vp]
         L.fxp_ref_unmap_i8.argtypes = [vp, u64, i32, c.c_int, vp]
@@ -102,6 +103,16 @@ def map(x, e_max, seed=0, stream_id=0, rounding=STOCHASTIC, bits=8, transposed=F
     _check(lib().fxp_ref_map(_ptr(x), rows, cols, int(e_max), _ptr(q), _ptr(qT), seed, stream_id, rounding, bits),
            "map")
     return (q, qT) if transposed else q
+
+
+def map_rows(x_rows, row0, e_max, seed=0, stream_id=0, rounding=STOCHASTIC, bits=8):
+    """q of rows row0 .. row0 + len(x_rows) - 1 of a larger tensor with the same number of columns."""
+    x = _f32(x_rows)
+    assert x.ndim == 2
+    q = np.empty(x.shape, dtype=np.int8)
+    _check(lib().fxp_ref_map_rows(_ptr(x), int(row0), x.shape[0], x.shape[1], int(e_max), _ptr(q), seed, stream_id,
+                                  rounding, bits), "map_rows")
+    return q
 
 
 def gemm(A, B, transA=False, transB=False):

@@ -206,6 +206,24 @@ int fxp_ref_map(const float* x, int64_t rows, int64_t cols, int32_t e_max, int8_
     return 0;
 }
 
+// The same for `nrows` consecutive rows of a larger [*, cols] tensor, starting at row `row0`: x and q hold only
+// those rows, the random word of an element is the one of its index in the whole tensor, (row0 + r) * cols + c.
+// Lets a test check slices of a tensor too large to map whole on the CPU.
+int fxp_ref_map_rows(const float* x, int64_t row0, int64_t nrows, int64_t cols, int32_t e_max, int8_t* q, uint64_t seed,
+                     uint64_t stream_id, int rounding, int bits) {
+    if (row0 < 0 || nrows < 0 || cols < 0 || bad_bits(bits) || rounding < 0 || rounding > 1) return -2;
+    if (nrows * cols > 0 && (!x || !q)) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < nrows; ++r) {
+        for (int64_t c = 0; c < cols; ++c) {
+            const uint64_t local = static_cast<uint64_t>(r) * static_cast<uint64_t>(cols) + static_cast<uint64_t>(c);
+            const uint64_t i = static_cast<uint64_t>(row0 + r) * static_cast<uint64_t>(cols) + static_cast<uint64_t>(c);
+            q[local] = static_cast<int8_t>(map_one(x[local], e_max, random_word(seed, stream_id, i), rounding, bits));
+        }
+    }
+    return 0;
+}
+
 // Sec. 3.3: C[M,N] = op(A)[M,K] * op(B)[K,N], int8 operands, int32 accumulation.
 // transA = 0: A is stored [M,K] (lda >= K); 1: A is stored [K,M] (lda >= M).
 // transB = 0: B is stored [K,N] (ldb >= N); 1: B is stored [N,K] (ldb >= K).

@@ -94,3 +94,76 @@ def test_c4_vit_block_other_linears_fullsize(fxp, layer_index):
 @pytest.mark.parametrize("sigma", synth.C5_SIGMAS)
 def test_c5_square_fullsize(fxp, sigma):
     run_layer_fullsize(fxp, "c5", 0, sigma, 32)
+
+
+# --------------------------------------------------------------------------- beyond 32-bit element counts
+def _need_memory(nbytes):
+    free, _ = torch.cuda.mem_get_info()
+    if free < nbytes + (4 << 30):
+        pytest.skip(f"needs {nbytes >> 30} GiB of device memory, {free >> 30} GiB free")
+
+
+def _row_blocks(rows, cols, extra=()):
+    """Row ranges to compare: both ends, the rows where the element index crosses 2^32 and 2^34, and any extra."""
+    marks = [0, rows - 8] + [b // cols - 4 for b in (1 << 32, 1 << 34) if b // cols + 4 < rows] + list(extra)
+    return sorted({max(0, min(rows - 8, m)) for m in marks})
+
+
+@pytest.mark.parametrize("rows,cols,transposed", [((1 << 18) + 200, 16384 + 128, True), ((1 << 20) + 640, 16384, False)],
+                         ids=["2^32-elements-both-copies", "2^34-elements"])
+def test_scale_and_map_of_tensors_beyond_32_bit_indices(fxp, rows, cols, transposed):
+    """Element counts above 2^32 (64-bit addressing, the transposed copy included) and above 2^34 (the second
+    counter word of the random stream comes into use): the scale against a reduction by torch, the mapped bytes
+    against the oracle on row blocks at both ends and around the 2^32 / 2^34 crossings."""
+    n = rows * cols
+    _need_memory(n * (6 if transposed else 5))
+    say("huge map", rows, cols, "transposed" if transposed else "")
+    gen = torch.Generator(device="cuda").manual_seed(rows)
+    x = torch.empty((rows, cols), dtype=torch.float32, device="cuda")
+    step = 1 << 14
+    for r in range(0, rows, step):
+        x[r:r + step].normal_(generator=gen)
+    x[rows - 3, cols - 5] = -700.0                       # the maximum sits in the last rows
+    bits = x.view(torch.int32)
+    top = max(int((bits[r:r + step] & 0x7FFFFFFF).max()) for r in range(0, rows, step))
+    e = fxp.scale(x)
+    assert int(host(e)[0]) == top >> 23 == 136
+    q, qT = fxp.map(x, e, seed=21, stream_id=(3 << 8) | 1, want_q=True, want_qT=transposed)
+    torch.cuda.synchronize()
+    for r0 in _row_blocks(rows, cols):
+        want = oracle.map_rows(host(x[r0:r0 + 8]), r0, 136, seed=21, stream_id=(3 << 8) | 1)
+        assert np.array_equal(host(q[r0:r0 + 8]), want), r0
+        if transposed:
+            assert np.array_equal(host(qT[:, r0:r0 + 8]).T, want), r0
+    # every row block of 8 agrees between the two copies (device-side, whole tensor)
+    if transposed:
+        for r in range(0, rows, step):
+            assert bool((q[r:r + step] == qT[:, r:r + step].T).all()), r
+
+
+@pytest.mark.parametrize("M,N,K", [((1 << 22) + 300, 1152, 128), ((1 << 25) + 100, 192, 64)],
+                         ids=["wide-output-4.8G", "tall-6.4G"])
+def test_gemm_output_beyond_32_bit_indices(fxp, M, N, K):
+    """Products whose output has more than 2^32 elements: sampled rows at both ends and around the 2^32-element
+    crossing against the oracle, and an exact column-sum identity over the whole output."""
+    _need_memory(M * K + M * N * 4)
+    say("huge gemm", M, N, K)
+    gen = torch.Generator(device="cuda").manual_seed(M)
+    A = torch.randint(-127, 128, (M, K), dtype=torch.int8, device="cuda", generator=gen)
+    B = torch.randint(-127, 128, (N, K), dtype=torch.int8, device="cuda", generator=gen)
+    e = dev(np.array([133, 133], np.int32))               # one unit = 2^0: the output holds the integer sums
+    C = fxp.gemm_unmap(A, B, e[0:1], e[1:2], transB=True)
+    torch.cuda.synchronize()
+    Bh = host(B)
+    for r0 in _row_blocks(M, N):
+        acc = oracle.gemm(host(A[r0:r0 + 8]), Bh, transB=True)
+        assert same_bits(host(C[r0:r0 + 8]), acc.astype(np.float32)), r0
+    # sum over all rows of C = (column sums of A) . B^T, exact in int64 / float64 (|entries| < 2^21)
+    colsum = torch.zeros(K, dtype=torch.int64, device="cuda")
+    total = torch.zeros(N, dtype=torch.float64, device="cuda")
+    step = 1 << 18
+    for r in range(0, M, step):
+        colsum += A[r:r + step].sum(0, dtype=torch.int64)
+        total += C[r:r + step].sum(0, dtype=torch.float64)
+    want = host(colsum) @ Bh.astype(np.int64).T
+    assert np.array_equal(host(total).astype(np.int64), want)

@@ -219,3 +219,22 @@ def test_nearest_rounding_fails_the_same_test_on_tiny_gradients():
     z_rn, _ = _mean_error_z(g, e, oracle.map(g, e, rounding=oracle.NEAREST))
     assert abs(z_sr) < 4.0
     assert abs(z_rn) > 10.0
+
+
+def test_row_slices_carry_the_index_of_the_whole_tensor():
+    """map_rows on slices reassembles map of the whole tensor, and at element indices beyond 2^34 (counter words
+    above the low one in use) every element equals the independent rational model with the same index."""
+    rng = np.random.default_rng(12)
+    x = rng.standard_normal((37, 24)).astype(np.float32)
+    e = oracle.scale(x)
+    whole = oracle.map(x, e, seed=9, stream_id=77)
+    parts = [oracle.map_rows(x[a:b], a, e, seed=9, stream_id=77) for a, b in ((0, 5), (5, 6), (6, 37))]
+    assert np.array_equal(np.concatenate(parts), whole)
+    assert oracle.map_rows(x[:0], 3, e).shape == (0, 24)
+    row0 = (1 << 34) // 24 + 12345                      # first element index above 2^34
+    q = oracle.map_rows(x[:3], row0, e, seed=9, stream_id=77)
+    for r in range(3):
+        for c in range(24):
+            i = (row0 + r) * 24 + c
+            assert i >> 34 and int(q[r, c]) == pymodel.map_one(float(x[r, c]), e, 9, 77, i)
+    assert not np.array_equal(q, whole[:3])              # not the words of rows 0..2
