@@ -112,13 +112,17 @@ __device__ inline void absmax_body(const uint32_t* __restrict__ x, size_t n, uin
 // Philox-4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): counter (c0..c3), key (k0, k1), ten rounds of two
 // 32x32->64 multiplies with the Weyl key schedule.  Element i of a tensor stream uses word i % 4 of the
 // block with counter (i / 4, stream id) and key = seed.
+// a ^ b ^ c in one instruction (three-input bit operation with the parity truth table); the compiler
+// leaves two v_xor_b32 when one input is wave-uniform, and the map kernels are bound by VALU issue
+__device__ inline uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) { return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96); }
+
 __device__ inline uint4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1) {
 #pragma unroll
     for (int r = 0; r < 10; ++r) {
         const uint64_t p0 = static_cast<uint64_t>(0xD2511F53u) * c0;
         const uint64_t p1 = static_cast<uint64_t>(0xCD9E8D57u) * c2;
-        const uint32_t n0 = static_cast<uint32_t>(p1 >> 32) ^ c1 ^ (k0 + 0x9E3779B9u * r);
-        const uint32_t n2 = static_cast<uint32_t>(p0 >> 32) ^ c3 ^ (k1 + 0xBB67AE85u * r);
+        const uint32_t n0 = xor3(static_cast<uint32_t>(p1 >> 32), c1, k0 + 0x9E3779B9u * r);
+        const uint32_t n2 = xor3(static_cast<uint32_t>(p0 >> 32), c3, k1 + 0xBB67AE85u * r);
         c1 = static_cast<uint32_t>(p1);
         c3 = static_cast<uint32_t>(p0);
         c0 = n0;

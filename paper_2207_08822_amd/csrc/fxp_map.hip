@@ -63,12 +63,24 @@ __device__ inline uint32_t with_sign(uint32_t mag, uint32_t b) {
     return (mag ^ sm) - sm;
 }
 
+// byte permute: every byte of the result is byte (sel & 7) of the pair {hi, lo} (0-3 = lo, 4-7 = hi)
+__device__ inline uint32_t perm(uint32_t hi, uint32_t lo, uint32_t sel) { return __builtin_amdgcn_perm(hi, lo, sel); }
+
+// the four signed results of a 16-byte load as one dword, low bytes in element order
 __device__ inline uint32_t pack4(uint32_t q0, uint32_t q1, uint32_t q2, uint32_t q3, const uint4 v) {
-    q0 = with_sign(q0, v.x) & 0xffu;
-    q1 = with_sign(q1, v.y) & 0xffu;
-    q2 = with_sign(q2, v.z) & 0xffu;
-    q3 = with_sign(q3, v.w);
-    return q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
+    const uint32_t p01 = perm(with_sign(q1, v.y), with_sign(q0, v.x), 0x0c0c0400u);
+    const uint32_t p23 = perm(with_sign(q3, v.w), with_sign(q2, v.z), 0x0c0c0400u);
+    return perm(p23, p01, 0x05040100u);
+}
+
+// 4 x 4 byte transpose: o[r] holds columns 0..3 of row r; t[c] receives rows 0..3 of column c
+__device__ inline void transpose4x4(const uint32_t (&o)[4], uint32_t (&t)[4]) {
+    const uint32_t a = perm(o[1], o[0], 0x05010400u), b = perm(o[1], o[0], 0x07030602u);   // rows 0,1: columns 0,1 | 2,3
+    const uint32_t c = perm(o[3], o[2], 0x05010400u), d = perm(o[3], o[2], 0x07030602u);   // rows 2,3
+    t[0] = perm(c, a, 0x05040100u);
+    t[1] = perm(c, a, 0x07060302u);
+    t[2] = perm(d, b, 0x05040100u);
+    t[3] = perm(d, b, 0x07060302u);
 }
 
 __device__ inline MapCfg make_cfg(int e_max, int bits) {
@@ -196,13 +208,10 @@ __device__ inline void map_tile_body(const uint32_t* __restrict__ x, int64_t row
             if (qt != nullptr && col_ok && (!EDGE || lrow + k < rows_here))
                 *reinterpret_cast<uint32_t*>(qt + static_cast<uint32_t>(lrow + k) * ucols + 4 * cg) = o[k];
         if (qT != nullptr) {
-            // 4 x 4 byte transpose: t[c] = column c of the block, rows in ascending byte order
+            uint32_t t[4];                          // t[c] = column c of the block, rows in ascending byte order
+            transpose4x4(o, t);
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const uint32_t t = ((o[0] >> (8 * c)) & 0xffu) | (((o[1] >> (8 * c)) & 0xffu) << 8) |
-                                   (((o[2] >> (8 * c)) & 0xffu) << 16) | (((o[3] >> (8 * c)) & 0xffu) << 24);
-                stage[(4 * cg + c) * TS + rg] = t;
-            }
+            for (int c = 0; c < 4; ++c) stage[(4 * cg + c) * TS + rg] = t[c];
         }
 #pragma unroll
         for (int k = 0; k < 4; ++k) cur[k] = nxt[k];
