@@ -29,6 +29,8 @@ struct MapCfg {
     uint32_t sat;   // 2^(bits-1) - 1
     uint32_t half;  // 2^(cut-1), the nearest-rounding increment
     uint32_t low_mask;  // 2^cut - 1
+    float to_units;     // 2^(150 - e_max): |x| * to_units = the 24-bit mantissa shifted to the scale (e_max in [25, 254])
+    float limit;        // 2^(e_max - 126): magnitudes from here on are above the scale (+Inf for e_max = 254)
 };
 
 // Magnitude of one element, every case: non-finite input, scale below the element.
@@ -44,16 +46,19 @@ __device__ inline uint32_t magnitude_full(uint32_t b, uint32_t word, const MapCf
     return min((mp + add) >> c.cut, c.sat);
 }
 
-// Same for the common case: e_max in [25, 254], no element above the scale, no result above
-// the largest magnitude.  A sub-normal input is then shifted out whatever its hidden bit, so it
-// needs no special case.  r < low  <=>  low + (2^cut - 1 - r) carries out of the cut.  The caller
-// ORs `d` (negative = element above the scale) and the result (bit bits-1 set = needs the
-// saturating path) over its elements and redoes the block with magnitude_full if either fires.
+// Same for the common case: e_max in [25, 254], no element above the scale, no result above the largest
+// magnitude.  The shifted mantissa m >> (e_max - e) is the integer part of |x| * 2^(150 - e_max): the factor is a
+// power of two (a normal float for these scales), so the product is exact whenever it is 1 or more and below 1
+// otherwise, sub-normal inputs included, and the conversion truncates - two instructions for unpack, hidden
+// bit, clamp and shift.  r < low  <=>  low + (2^cut - 1 - r) carries out of the cut.  `bad` collects, as a lane
+// mask (one compare per element, accumulated on the scalar side), the lanes with an element the scale does not
+// cover (exponent above it, Inf, NaN); the caller also ORs the results (a bit above the magnitude bits = needs
+// the saturating path) and redoes the block with magnitude_full if either fires.
 template <bool STOCH>
-__device__ inline uint32_t magnitude_fast(uint32_t b, uint32_t word, const MapCfg& c, uint32_t& d_or) {
-    const uint32_t d = static_cast<uint32_t>(c.e_max) - ((b >> 23) & 0xffu);
-    d_or |= d;
-    const uint32_t mp = ((b & 0x7fffffu) | 0x800000u) >> min(d, 31u);
+__device__ inline uint32_t magnitude_fast(uint32_t b, uint32_t word, const MapCfg& c, uint64_t& bad) {
+    const float ax = fabsf(__uint_as_float(b));
+    bad |= __builtin_amdgcn_ballot_w64(!(ax < c.limit));
+    const uint32_t mp = static_cast<uint32_t>(ax * c.to_units);
     const uint32_t add = STOCH ? ((word >> c.rshift) ^ c.low_mask) : c.half;
     return (mp + add) >> c.cut;
 }
@@ -91,6 +96,9 @@ __device__ inline MapCfg make_cfg(int e_max, int bits) {
     c.sat = (1u << (bits - 1)) - 1u;
     c.half = 1u << (c.cut - 1);
     c.low_mask = (1u << c.cut) - 1u;
+    const int e = min(max(e_max, 25), 254);                       // outside: the fast path is not taken
+    c.to_units = __uint_as_float(static_cast<uint32_t>(277 - e) << 23);
+    c.limit = __uint_as_float(static_cast<uint32_t>(e + 1) << 23);
     return c;
 }
 
@@ -169,7 +177,7 @@ __device__ inline void map_tile_body(const uint32_t* __restrict__ x, int64_t row
     // the scale is resolved (block maxima re-read and reduced) while the first loads are in flight
     const MapCfg cfg = make_cfg(resolve_scale(J.e_in, J.partials, J.n_partials, J.e_out, red, publish), bits);
     const bool scale_ok = cfg.e_max >= 25 && cfg.e_max < 255;
-    const uint32_t over_bit = cfg.sat + 1u;       // a fast-path result with this bit set needs saturation
+    const uint32_t over_bits = ~cfg.sat;          // a fast-path result with any of these set needs saturation
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
         const int rg = p * RGP + rgl;              // group of 4 rows
@@ -182,18 +190,19 @@ __device__ inline void map_tile_body(const uint32_t* __restrict__ x, int64_t row
                          : make_uint4(0, 0, 0, 0);
         };
         uint32_t o[4];
-        uint32_t d_or = 0, q_or = 0;
+        uint32_t q_or = 0;
+        uint64_t bad = 0;                          // wave-uniform: any lane with an uncovered element
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const uint4 w = words_of(k);
-            const uint32_t m0 = magnitude_fast<STOCH>(cur[k].x, w.x, cfg, d_or);
-            const uint32_t m1 = magnitude_fast<STOCH>(cur[k].y, w.y, cfg, d_or);
-            const uint32_t m2 = magnitude_fast<STOCH>(cur[k].z, w.z, cfg, d_or);
-            const uint32_t m3 = magnitude_fast<STOCH>(cur[k].w, w.w, cfg, d_or);
+            const uint32_t m0 = magnitude_fast<STOCH>(cur[k].x, w.x, cfg, bad);
+            const uint32_t m1 = magnitude_fast<STOCH>(cur[k].y, w.y, cfg, bad);
+            const uint32_t m2 = magnitude_fast<STOCH>(cur[k].z, w.z, cfg, bad);
+            const uint32_t m3 = magnitude_fast<STOCH>(cur[k].w, w.w, cfg, bad);
             q_or |= m0 | m1 | m2 | m3;
             o[k] = pack4(m0, m1, m2, m3, cur[k]);
         }
-        if (!scale_ok || (d_or & 0x80000000u) || (q_or & over_bit)) {
+        if (!scale_ok || bad != 0 || (q_or & over_bits)) {
             // rare: an element above the scale, a saturating result, a non-finite input or a tiny
             // scale somewhere in this 4 x 4 block: redo it with the complete per-element path
 #pragma unroll
