@@ -47,16 +47,16 @@ __device__ inline int map16_full(uint32_t b, uint32_t r9, int e_max) {
     return (b >> 31) ? -static_cast<int>(q) : static_cast<int>(q);
 }
 
-// The same without branches for a finite element at or below the scale (d >= 0): the round-up is the carry of
-// low + (511 - r9) out of the 9 dropped bits.  `bad` collects the sign of d and the exponent-255 pattern; the
-// caller redoes the quad with map16_full when any element set it.
+// The same without branches for a finite element at or below the scale: the shifted mantissa m >> (e_max - e) is
+// the integer part of |x| * 2^(150 - e_max) (an exact scaling by a power of two, sub-normal inputs included,
+// then a truncating conversion), and the round-up is the carry of low + (511 - r9) out of the 9 dropped bits.
+// `bad` collects, as a lane mask, the lanes holding an element the scale does not cover (exponent above it, Inf,
+// NaN: everything that is not below `limit` = 2^(e_max - 126)); the caller redoes those quads with map16_full.
 template <bool STOCH>
-__device__ inline int map16_fast(uint32_t b, uint32_t r9, int e_max, uint32_t& bad) {
-    const uint32_t e = (b >> 23) & 0xffu;
-    const int d = e_max - static_cast<int>(max(e, 1u));
-    bad |= static_cast<uint32_t>(d) | (e + 1u) << 23;      // bit 31: d < 0, or e == 255 (256 << 23)
-    const uint32_t m = (b & 0x7fffffu) | (e ? 0x800000u : 0u);
-    const uint32_t ms = m >> min(d, 31);
+__device__ inline int map16_fast(uint32_t b, uint32_t r9, int to_units, float limit, uint64_t& bad) {
+    const float ax = fabsf(__uint_as_float(b));
+    bad |= __builtin_amdgcn_ballot_w64(!(ax < limit));
+    const uint32_t ms = static_cast<uint32_t>(ldexpf(ax, to_units));
     const uint32_t q = min((ms + (STOCH ? (r9 ^ 511u) : 256u)) >> 9, 32767u);
     return (b >> 31) ? -static_cast<int>(q) : static_cast<int>(q);
 }
@@ -162,6 +162,10 @@ __device__ __attribute__((always_inline)) inline void axpy16_body(const uint32_t
             constexpr bool USUAL = decltype(usual_c)::value;
             const int sh = al.right;                                   // USUAL: 1..31
             const float unit = __uint_as_float(static_cast<uint32_t>(Ex + 127) << 23);
+            // scale 255 (a non-finite element somewhere): the limit becomes -0 and every quad takes the full path
+            const int ux = 150 - ex, uy = 150 - ey;
+            const float limx = __uint_as_float(static_cast<uint32_t>(ex + 1) << 23);
+            const float limy = __uint_as_float(static_cast<uint32_t>(ey + 1) << 23);
             uint4 xc = make_uint4(0, 0, 0, 0), yc = xc, xn = xc, yn = xc;
             if (first < quads) {
                 xc = xv[first];
@@ -175,12 +179,12 @@ __device__ __attribute__((always_inline)) inline void axpy16_body(const uint32_t
                 blocks_of(q, rxy, ru);
                 const uint32_t xb[4] = {xc.x, xc.y, xc.z, xc.w}, yb[4] = {yc.x, yc.y, yc.z, yc.w};
                 const uint32_t wxy[4] = {rxy.x, rxy.y, rxy.z, rxy.w}, wu[4] = {ru.x, ru.y, ru.z, ru.w};
-                uint32_t bad = 0;
+                uint64_t bad = 0;                                      // wave-uniform lane mask
                 float zf[4];
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
-                    const int xh = map16_fast<STOCH>(xb[k], wxy[k] >> 23, ex, bad);
-                    const int yh = map16_fast<STOCH>(yb[k], (wxy[k] >> 14) & 511u, ey, bad);
+                    const int xh = map16_fast<STOCH>(xb[k], wxy[k] >> 23, ux, limx, bad);
+                    const int yh = map16_fast<STOCH>(yb[k], (wxy[k] >> 14) & 511u, uy, limy, bad);
                     const int p = a_hat * yh;
                     if (USUAL) {
                         const uint32_t m = static_cast<uint32_t>(p < 0 ? -p : p);
@@ -191,7 +195,7 @@ __device__ __attribute__((always_inline)) inline void axpy16_body(const uint32_t
                         zf[k] = unmap_value(xh + update_on_grid<STOCH>(p, al, wu[k]), Ex);
                     }
                 }
-                if (bad & 0x80000000u) {      // rare: a non-finite element (or one above a scale) in this quad
+                if (bad != 0) {               // rare: a non-finite element (or one above a scale) in this wave's quads
 #pragma unroll
                     for (int k = 0; k < 4; ++k) zf[k] = axpy_one<STOCH>(xb[k], yb[k], wxy[k], wu[k], ex, ey, a_hat, al, Ex);
                 }

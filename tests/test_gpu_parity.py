@@ -94,6 +94,14 @@ def test_map_edge_values(fxp):
     check_map(fxp, (x[1:] * np.float32(1e-38)).astype(np.float32))
     check_map(fxp, (x[1:] * np.float32(1e-38)).astype(np.float32), e_max=24)
     check_map(fxp, (x[1:] * np.float32(1e-38)).astype(np.float32), e_max=25)
+    say("map top of the exponent range, scales just below the tensor's own")
+    big = (x[1:] * np.float32(5e37)).astype(np.float32)
+    assert oracle.scale(big) == 254
+    check_map(fxp, big)
+    check_map(fxp, x[1:], e_max=254)
+    own = oracle.scale(x[1:])
+    check_map(fxp, x[1:], e_max=own - 1)
+    check_map(fxp, x[1:], e_max=own - 3)
     say("map zeros")
     check_map(fxp, np.zeros((128, 128), np.float32))
     say("map huge seed")

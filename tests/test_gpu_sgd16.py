@@ -155,3 +155,22 @@ def test_sgd16_step_multi_resnet18_list(fxp):
     wo, vo = oracle.sgd16_step_multi(ws, gs, vs, 0.1, 0.9, 5e-4, seed=0, step=0)
     for t in range(len(ws)):
         assert same_bits(host(wd_[t]), wo[t]) and same_bits(host(vd[t]), vo[t]), t
+
+
+@pytest.mark.parametrize("rounding", [0, 1])
+def test_axpy16_smallest_scales(fxp, rounding):
+    """Tensors whose scale is at the bottom of the exponent range (all zero: scale 1; sub-normal only; around
+    1e-38): the fast path scales by up to 2^149 and must agree with the oracle bit for bit."""
+    say("axpy16 smallest scales", rounding)
+    rng = np.random.default_rng(17)
+    n = 4096 + 7
+    base = rng.standard_normal(n).astype(np.float32)
+    cases = [(base * np.float32(1e-38), np.zeros(n, np.float32), 0.5),
+             ((base * np.float32(1e-42)).astype(np.float32), (base[::-1] * np.float32(3e-39)).astype(np.float32), -1.5),
+             (np.zeros(n, np.float32), (base * np.float32(1e-30)).astype(np.float32), 1e-8),
+             ((base * np.float32(2e-31)).astype(np.float32), (base[::-1] * np.float32(1e-36)).astype(np.float32), 3.0e5)]
+    for x, y, a in cases:
+        x, y = np.ascontiguousarray(x), np.ascontiguousarray(y)
+        zo, eo = oracle.axpy16(x, y, a, seed=6, step=9, rounding=rounding)
+        z, e = fxp.axpy16(dev(x), dev(y), a, seed=6, step=9, rounding=rounding)
+        assert tuple(host(e).tolist()) == eo and same_bits(host(z), zo), (eo, a)
