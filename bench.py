@@ -383,9 +383,10 @@ def main():
 
     rows = {}   # kernel row -> totals over one step
 
-    def add(row, kernel, dt, nbytes, ops=0.0):
+    def add(row, kernel, dt, nbytes, ops=0.0, tmin=None):
         r = rows.setdefault(row, dict(kernel=kernel, t=0.0, tmin=0.0, launches=0, bytes=0.0, ops=0.0))
-        r["t"] += dt; r["tmin"] += timed.last_min; r["launches"] += 1; r["bytes"] += nbytes; r["ops"] += ops
+        r["t"] += dt; r["tmin"] += timed.last_min if tmin is None else tmin
+        r["launches"] += 1; r["bytes"] += nbytes; r["ops"] += ops
 
     gemm_rows = []
     map_rotating_gbs = None
@@ -393,19 +394,23 @@ def main():
     st = torch.cuda.current_stream().cuda_stream
     for layer, (X, W, dY), buf in zip(layers, dev_inputs, bufs):
         M, K, N = layer.M, layer.K, layer.N
-        ws = torch.empty(max(256, fxp.workspace_bytes(fxp.OP_SCALE, 0)), dtype=torch.uint8, device=dev)
-        # scale: 4 B read per element (k_absmax_partials; the finishing block is negligible)
-        for t, e in ((X, buf.eX), (W, buf.eW), (dY, buf.e_dY)):
-            n = t.numel()
-            add("scale", "k_absmax_partials", timed(lambda: lib.fxp_scale(p(t), n, p(e), p(ws), ws.numel(), st)), 4.0 * n)
         # map: 4 B read + 1 B written per copy (both orientations) per element; launched as the step launches it:
         # activation and weight in one launch, the gradient in one of its own
         outs = [(torch.empty(t.shape, dtype=torch.int8, device=dev),
                  torch.empty((t.shape[1], t.shape[0]), dtype=torch.int8, device=dev)) for t in (X, W, dY)]
         dX_, dW_ = (fxp._desc(t, e, o[0], o[1], tag) for t, e, o, tag in ((X, buf.eX, outs[0], 0), (W, buf.eW, outs[1], 1)))
-        add("map", "k_map_tile<true, *>",
-            timed(lambda: lib.fxp_map2(ctypes.byref(dX_), ctypes.byref(dW_), seed, 0, args.bits, st)),
-            6.0 * (X.numel() + W.numel()))
+        t_map_xw = timed(lambda: lib.fxp_map2(ctypes.byref(dX_), ctypes.byref(dW_), seed, 0, args.bits, st))
+        tmin_map_xw = timed.last_min
+        add("map", "k_map_tile<true, *>", t_map_xw, 6.0 * (X.numel() + W.numel()))
+        # scale: 4 B read per element.  The step launches the reduction (k_absmax_partials, activation and weight in
+        # one launch) and the map kernel, which finishes the reduction, back to back: the row is the time of that
+        # pair of launches minus the time of the map launch alone (the stand-alone fxp_scale would add a finishing
+        # launch per tensor that the step does not have)
+        ws2 = torch.empty(2 * max(256, fxp.workspace_bytes(fxp.OP_SCALE, 0)), dtype=torch.uint8, device=dev)
+        t_pair = timed(lambda: lib.fxp_scale_map2(ctypes.byref(dX_), ctypes.byref(dW_), seed, 0, args.bits, p(ws2),
+                                                  ws2.numel(), st))
+        add("scale", "k_absmax_partials", max(t_pair - t_map_xw, 0.0), 4.0 * (X.numel() + W.numel()),
+            tmin=max(timed.last_min - tmin_map_xw, 0.0))
         if layer is layers[0] and not args.copy_calibration:      # (counter runs keep to the launches of the step)
             # the same launch over a rotating set of inputs larger than the 256 MB Infinity Cache: every launch reads
             # its tensor from HBM ("rotating"); the row above re-reads one tensor ("warm", as inside a training step,
@@ -421,10 +426,14 @@ def main():
 
             map_rotating_gbs = 6.0 * (X.numel() + W.numel()) / timed(rotating) / 1e9
             del Xs, descs
-        add("map", "k_map_tile<true, *>",
-            timed(lambda: lib.fxp_map(p(dY), dY.shape[0], dY.shape[1], p(buf.e_dY), p(outs[2][0]), p(outs[2][1]), seed, 2, 0,
-                                      args.bits, st)), 6.0 * dY.numel())
-        del outs
+        t_map_g = timed(lambda: lib.fxp_map(p(dY), dY.shape[0], dY.shape[1], p(buf.e_dY), p(outs[2][0]), p(outs[2][1]), seed, 2,
+                                            0, args.bits, st))
+        tmin_map_g = timed.last_min
+        add("map", "k_map_tile<true, *>", t_map_g, 6.0 * dY.numel())
+        t_pair = timed(lambda: lib.fxp_scale_map(p(dY), dY.shape[0], dY.shape[1], p(buf.e_dY), p(outs[2][0]), p(outs[2][1]),
+                                                 seed, 2, 0, args.bits, p(ws2), ws2.numel(), st))
+        add("scale", "k_absmax_partials", max(t_pair - t_map_g, 0.0), 4.0 * dY.numel(), tmin=max(timed.last_min - tmin_map_g, 0.0))
+        del outs, ws2
         gemms = [("fwd", M, N, K, buf.Xq, buf.WqT, buf.eX, buf.eW, buf.Y),
                  ("dX", M, K, N, buf.dYq, buf.Wq, buf.e_dY, buf.eW, buf.dX),
                  ("dW", K, N, M, buf.XqT, buf.dYqT, buf.eX, buf.e_dY, buf.dW)]
