@@ -120,6 +120,19 @@ int fxp_map2(const fxp_map_desc* a, const fxp_map_desc* b, uint64_t seed, int ro
 int fxp_scale_map2(const fxp_map_desc* a, const fxp_map_desc* b, uint64_t seed, int rounding, int bits, void* ws,
                    size_t ws_bytes, void* stream);
 
+/* Number of uint32 words of an abs-max area (see fxp_gemm_unmap_absmax). */
+#define FXP_ABSMAX_WORDS 256
+
+/* fxp_map with the scale taken from the largest magnitude of the tensor, given as an abs-max area: device
+ * array of FXP_ABSMAX_WORDS uint32 whose maximum is the IEEE bit pattern of max |x_i| (what
+ * fxp_gemm_unmap_absmax leaves behind for its output).  The scale of Sec. 3.1 is the exponent field of that
+ * maximum, at least 1.  It is written to *e_max (required) and used for the mapping in the same launch, so a
+ * tensor produced by a product of this library is mapped without a reduction pass of its own.  An area below
+ * the tensor's true maximum gives a scale below the tensor (elements above it saturate), as a too small e_max
+ * does for fxp_map. */
+int fxp_map_absmax(const float* x, int64_t rows, int64_t cols, const uint32_t* absmax, int32_t* e_max, int8_t* q, int8_t* qT,
+                   uint64_t seed, uint64_t stream_id, int rounding, int bits, void* stream);
+
 /* Integer GEMM (Sec. 3.3, Fig. 2: int8 x int8 products, int32 accumulation).
  * C[M,N] = op(A)[M,K] * op(B)[K,N], C overwritten.
  * transA = 0: A stored [M,K], lda >= K.  transA = 1: A stored [K,M], lda >= M.
@@ -147,6 +160,17 @@ int fxp_unmap_i8(const int8_t* q, size_t n, const int32_t* eA, int bitsA, float*
 int fxp_gemm_unmap(int transA, int transB, int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda,
                    const int8_t* B, int64_t ldb, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB, float* C,
                    int64_t ldc, void* ws, size_t ws_bytes, void* stream);
+
+/* fxp_gemm_unmap that also leaves the largest output magnitude behind, so that the next layer can map C without
+ * a reduction pass over it (Sec. 3.1's scale is the exponent field of that magnitude).  out_absmax (required):
+ * device array of FXP_ABSMAX_WORDS uint32, 4-byte aligned; the call raises its words by atomic maxima so that
+ * their maximum is at least the IEEE bit pattern of max |C_ij| (several words, so that the workgroups do not
+ * all hit one address).  The caller zeroes the area before the first product that contributes to a tensor
+ * (several products may fill parts of one tensor).  Consumed by fxp_map_absmax.  Everything else as
+ * fxp_gemm_unmap. */
+int fxp_gemm_unmap_absmax(int transA, int transB, int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda,
+                          const int8_t* B, int64_t ldb, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB,
+                          float* C, int64_t ldc, uint32_t* out_absmax, void* ws, size_t ws_bytes, void* stream);
 
 /* Mapped operands a forward call leaves for the backward call (host struct of
  * device pointers, all caller-allocated, 16-byte aligned). */

@@ -62,12 +62,93 @@ __device__ inline int swizzle_of_row(int row) {
     return (row / (16 / CPR)) % CPR;        // period 16 rows: 16 rows x 16 B = all 64 banks once
 }
 
+// The wave's largest output magnitude -> one of the FXP_ABSMAX_WORDS words at amax (IEEE bits of a non-negative
+// float order like unsigned integers): one device-scope atomic per wave, without a returned value and with no
+// load before it - anything a wave has to WAIT for behind its stores keeps it alive until they have drained, which
+// is exactly the overlap the output-bound products live on (a look at the word first, to skip the atomic, cost
+// them a third of their time); consecutive waves use words in different cache lines.
+__device__ inline void publish_absmax(float m, uint32_t* amax) {
+    const uint32_t b = wave_max(__float_as_uint(m));
+    // (block and thread indices only: the launch dimensions would be LOADED, and a wave that waits for a load
+    // behind its stores stays alive until they have drained)
+    const unsigned slot = ((blockIdx.x + blockIdx.y * 37u) * 16u + (threadIdx.x >> 6)) % FXP_ABSMAX_WORDS;
+    if ((threadIdx.x & 63) == 0) atomicMax(amax + (((slot & 7u) << 5) | (slot >> 3)), b);     // 8 lines of 32 words
+}
+
+// Epilogue of every product kernel: the wave's FM x FN fragments of 32 x 32 go to C (top-left element row0, col0
+// of the wave's tile), as inverse-mapped fp32 (non-temporal: the output is not read again here), as int32, or
+// added into int32 with atomics.  Accumulator register r of lane l is row 8 * (r / 4) + 4 * (l / 32) + r % 4,
+// column l % 32 of its fragment.  AMAX: returns the largest magnitude this lane stored.
+// GUARD = false: the wave's tile lies inside C and 2^E is a normal float - no bounds tests, one convert and one
+// multiply per value, row addresses a scalar multiple of ldc away from the lane's base.  The output-bound
+// products spend a fifth of their time issuing this loop, so the tests are hoisted out of it.
+template <int FM, int FN, int MODE, bool AMAX, bool GUARD>
+__device__ inline float store_loop(const v16i (&acc)[FM][FN], void* __restrict__ Cv, int64_t ldc, int M, int N, int row0,
+                                   int col0, int fhalf, int frow, int E) {
+    float m = 0.0f;
+    const float unit = __uint_as_float(static_cast<uint32_t>(GUARD ? 127 : E + 127) << 23);
+    const int64_t base = static_cast<int64_t>(row0 + 4 * fhalf) * ldc + col0 + frow;
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int dr = 32 * i + 8 * (r >> 2) + (r & 3);            // row of this register below the lane's base row
+            if (GUARD && row0 + 4 * fhalf + dr >= M) continue;
+            const int64_t off_row = base + dr * ldc;
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                if (GUARD && col0 + 32 * j + frow >= N) continue;
+                const int64_t off = off_row + 32 * j;
+                if (MODE == kStoreF32) {
+                    const float v = GUARD ? unmap_value(acc[i][j][r], E) : static_cast<float>(acc[i][j][r]) * unit;
+                    __builtin_nontemporal_store(v, static_cast<float*>(Cv) + off);
+                    if (AMAX) m = fmaxf(m, fabsf(v));
+                } else if (MODE == kStoreI32) {
+                    static_cast<int32_t*>(Cv)[off] = acc[i][j][r];
+                } else {
+                    atomicAdd(static_cast<int32_t*>(Cv) + off, acc[i][j][r]);
+                }
+            }
+        }
+    }
+    return m;
+}
+
+template <int FM, int FN, int MODE, bool AMAX>
+__device__ inline float store_fragments(const v16i (&acc)[FM][FN], void* __restrict__ Cv, int64_t ldc, int M, int N, int row0,
+                                        int col0, int fhalf, int frow, int E) {
+    const bool inside = row0 + 32 * FM <= M && col0 + 32 * FN <= N;                     // wave-uniform
+    const bool plain = MODE != kStoreF32 || (E >= -126 && E <= 127);
+    if (inside && plain) {
+        float m = 0.0f;
+        if (AMAX) {
+            // the inverse mapping is monotone: the largest magnitude comes from the largest or the smallest sum,
+            // found on the integers (one three-input max / min per value) before the store loop starts
+            int hi = 0, lo = 0;
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; r += 2) {
+                        hi = max(max(hi, acc[i][j][r]), acc[i][j][r + 1]);
+                        lo = min(min(lo, acc[i][j][r]), acc[i][j][r + 1]);
+                    }
+            const float unit = __uint_as_float(static_cast<uint32_t>(E + 127) << 23);
+            m = fmaxf(static_cast<float>(hi) * unit, -(static_cast<float>(lo) * unit));
+        }
+        store_loop<FM, FN, MODE, false, false>(acc, Cv, ldc, M, N, row0, col0, fhalf, frow, E);
+        return m;
+    }
+    return store_loop<FM, FN, MODE, AMAX, true>(acc, Cv, ldc, M, N, row0, col0, fhalf, frow, E);
+}
+
 template <int BM, int BN, int BK, int WM, int WN, bool VEC, int MODE>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm_nt(
     const int8_t* __restrict__ A, int64_t lda, const int8_t* __restrict__ B, int64_t ldb, void* __restrict__ Cv,
     int64_t ldc, int M, int N, int K, int k_per_split, const int32_t* __restrict__ eA, int bitsA,
     const int32_t* __restrict__ eB, int bitsB, int tiles_m, int tiles_n, int group_m, int64_t split_stride,
-    int64_t batch_a, int64_t batch_b, int64_t batch_c) {
+    int64_t batch_a, int64_t batch_b, int64_t batch_c, uint32_t* __restrict__ amax) {
     constexpr int NT = (BM / WM) * (BN / WN) * 64;
     constexpr int CPR = BK / 16;
     constexpr int NA = BM * CPR / NT, NB = BN * CPR / NT;   // 16-byte pieces per thread per step
@@ -179,26 +260,10 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm_nt(
     // accumulator register r of lane l is row 8 * (r / 4) + 4 * (l / 32) + r % 4, column l % 32
     int E = 0;
     if (MODE == kStoreF32) E = lsb_exponent(eA[0], bitsA) + (eB ? lsb_exponent(eB[0], bitsB) : 0);
-#pragma unroll
-    for (int i = 0; i < FM; ++i) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = m0 + wm0 + 32 * i + 8 * (r >> 2) + 4 * fhalf + (r & 3);
-            if (row >= M) continue;
-#pragma unroll
-            for (int j = 0; j < FN; ++j) {
-                const int col = n0 + wn0 + 32 * j + frow;
-                if (col >= N) continue;
-                const int64_t off = static_cast<int64_t>(row) * ldc + col;
-                if (MODE == kStoreF32)
-                    __builtin_nontemporal_store(unmap_value(acc[i][j][r], E), static_cast<float*>(Cv) + off);
-                else if (MODE == kStoreI32)
-                    static_cast<int32_t*>(Cv)[off] = acc[i][j][r];
-                else
-                    atomicAdd(static_cast<int32_t*>(Cv) + off, acc[i][j][r]);
-            }
-        }
-    }
+    if (MODE == kStoreF32 && amax != nullptr)
+        publish_absmax(store_fragments<FM, FN, MODE, true>(acc, Cv, ldc, M, N, m0 + wm0, n0 + wn0, fhalf, frow, E), amax);
+    else
+        store_fragments<FM, FN, MODE, false>(acc, Cv, ldc, M, N, m0 + wm0, n0 + wn0, fhalf, frow, E);
 }
 
 // s_waitcnt immediate (gfx9 encoding): wait until at most `vm` vector-memory operations
@@ -231,7 +296,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm_nt_dma(
     const int8_t* __restrict__ A, int64_t lda, const int8_t* __restrict__ B, int64_t ldb, void* __restrict__ Cv,
     int64_t ldc, int M, int N, int K, int k_per_split, const int32_t* __restrict__ eA, int bitsA,
     const int32_t* __restrict__ eB, int bitsB, int tiles_m, int tiles_n, int group_m, int64_t split_stride,
-    int64_t batch_a, int64_t batch_b, int64_t batch_c, ConvTaps ct) {
+    int64_t batch_a, int64_t batch_b, int64_t batch_c, ConvTaps ct, uint32_t* __restrict__ amax) {
     constexpr int NW = (BM / WM) * (BN / WN);
     constexpr int CPR = BK / 16;                     // 16-byte pieces per LDS row
     constexpr int RROWS = 64 / CPR;                  // tile rows per 1 KiB region
@@ -432,26 +497,10 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm_nt_dma(
 
     int E = 0;
     if (MODE == kStoreF32) E = lsb_exponent(eA[0], bitsA) + (eB ? lsb_exponent(eB[0], bitsB) : 0);
-#pragma unroll
-    for (int i = 0; i < FM; ++i) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = m0 + wm0 + 32 * i + 8 * (r >> 2) + 4 * fhalf + (r & 3);
-            if (row >= M) continue;
-#pragma unroll
-            for (int j = 0; j < FN; ++j) {
-                const int col = n0 + wn0 + 32 * j + frow;
-                if (col >= N) continue;
-                const int64_t off = static_cast<int64_t>(row) * ldc + col;
-                if (MODE == kStoreF32)
-                    __builtin_nontemporal_store(unmap_value(acc[i][j][r], E), static_cast<float*>(Cv) + off);
-                else if (MODE == kStoreI32)
-                    static_cast<int32_t*>(Cv)[off] = acc[i][j][r];
-                else
-                    atomicAdd(static_cast<int32_t*>(Cv) + off, acc[i][j][r]);
-            }
-        }
-    }
+    if (MODE == kStoreF32 && amax != nullptr)
+        publish_absmax(store_fragments<FM, FN, MODE, true>(acc, Cv, ldc, M, N, m0 + wm0, n0 + wn0, fhalf, frow, E), amax);
+    else
+        store_fragments<FM, FN, MODE, false>(acc, Cv, ldc, M, N, m0 + wm0, n0 + wn0, fhalf, frow, E);
 }
 
 // 256 x 256 x 128 tile with LDS used as a RING of five 32 KiB half-stages instead of two
@@ -468,7 +517,7 @@ __global__ __launch_bounds__((256 / WM) * (256 / WN) * 64) void k_gemm_nt_ring(
     const int8_t* __restrict__ A, int64_t lda, const int8_t* __restrict__ B, int64_t ldb, void* __restrict__ Cv,
     int64_t ldc, int M, int N, int K, int k_per_split, const int32_t* __restrict__ eA, int bitsA,
     const int32_t* __restrict__ eB, int bitsB, int tiles_m, int tiles_n, int group_m, int64_t split_stride,
-    int64_t batch_a, int64_t batch_b, int64_t batch_c) {
+    int64_t batch_a, int64_t batch_b, int64_t batch_c, uint32_t* __restrict__ amax) {
     constexpr int BM = 256, BN = 256, BK = 128;
     constexpr int NW = (BM / WM) * (BN / WN);
     constexpr int SLOT = 256 * BK;                   // bytes of a half-stage
@@ -617,26 +666,10 @@ __global__ __launch_bounds__((256 / WM) * (256 / WN) * 64) void k_gemm_nt_ring(
 
     int E = 0;
     if (MODE == kStoreF32) E = lsb_exponent(eA[0], bitsA) + (eB ? lsb_exponent(eB[0], bitsB) : 0);
-#pragma unroll
-    for (int i = 0; i < FM; ++i) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = m0 + wm0 + 32 * i + 8 * (r >> 2) + 4 * fhalf + (r & 3);
-            if (row >= M) continue;
-#pragma unroll
-            for (int j = 0; j < FN; ++j) {
-                const int col = n0 + wn0 + 32 * j + frow;
-                if (col >= N) continue;
-                const int64_t off = static_cast<int64_t>(row) * ldc + col;
-                if (MODE == kStoreF32)
-                    __builtin_nontemporal_store(unmap_value(acc[i][j][r], E), static_cast<float*>(Cv) + off);
-                else if (MODE == kStoreI32)
-                    static_cast<int32_t*>(Cv)[off] = acc[i][j][r];
-                else
-                    atomicAdd(static_cast<int32_t*>(Cv) + off, acc[i][j][r]);
-            }
-        }
-    }
+    if (MODE == kStoreF32 && amax != nullptr)
+        publish_absmax(store_fragments<FM, FN, MODE, true>(acc, Cv, ldc, M, N, m0 + wm0, n0 + wn0, fhalf, frow, E), amax);
+    else
+        store_fragments<FM, FN, MODE, false>(acc, Cv, ldc, M, N, m0 + wm0, n0 + wn0, fhalf, frow, E);
 }
 
 // split-K helpers over an M x N int32 / fp32 matrix with leading dimension ldc; grid.y walks
@@ -654,8 +687,9 @@ __global__ __launch_bounds__(256) void k_zero_rows(int32_t* __restrict__ C, int6
 
 __global__ __launch_bounds__(256) void k_unmap_rows(int32_t* __restrict__ C, int64_t ldc, int rows, int cols,
                                                     const int32_t* __restrict__ eA, int bitsA,
-                                                    const int32_t* __restrict__ eB, int bitsB) {
+                                                    const int32_t* __restrict__ eB, int bitsB, uint32_t* __restrict__ amax) {
     const int E = lsb_exponent(eA[0], bitsA) + (eB ? lsb_exponent(eB[0], bitsB) : 0);
+    float m = 0.0f;
     for (int r = blockIdx.y; r < rows; r += gridDim.y) {
         int32_t* row = C + static_cast<int64_t>(r) * ldc;
         const bool vec = (reinterpret_cast<uintptr_t>(row) & 15u) == 0;
@@ -668,10 +702,15 @@ __global__ __launch_bounds__(256) void k_unmap_rows(int32_t* __restrict__ C, int
             o.z = unmap_value(a.z, E);
             o.w = unmap_value(a.w, E);
             reinterpret_cast<float4*>(row)[i] = o;
+            m = fmaxf(fmaxf(m, fmaxf(fabsf(o.x), fabsf(o.y))), fmaxf(fabsf(o.z), fabsf(o.w)));
         }
-        for (int i = (nvec << 2) + blockIdx.x * 256 + threadIdx.x; i < cols; i += gridDim.x * 256)
-            reinterpret_cast<float*>(row)[i] = unmap_value(row[i], E);
+        for (int i = (nvec << 2) + blockIdx.x * 256 + threadIdx.x; i < cols; i += gridDim.x * 256) {
+            const float o = unmap_value(row[i], E);
+            reinterpret_cast<float*>(row)[i] = o;
+            m = fmaxf(m, fabsf(o));
+        }
     }
+    if (amax != nullptr) publish_absmax(m, amax);
 }
 
 // launch shape of the two helpers: a dense matrix is treated as one long row
@@ -716,7 +755,7 @@ template <int BM, int BN, int BK, int WM, int WN>
 static int launch_cfg(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                       void* C, int64_t ldc, int mode, bool vec, int splits, const int32_t* eA, int bitsA,
                       const int32_t* eB, int bitsB, hipStream_t s, int64_t split_stride = 0, int* slices = nullptr,
-                      Batch bt = Batch()) {
+                      Batch bt = Batch(), uint32_t* amax = nullptr) {
     constexpr int NT = (BM / WM) * (BN / WN) * 64;
     const int tiles_m = static_cast<int>((M + BM - 1) / BM), tiles_n = static_cast<int>((N + BN - 1) / BN);
     int k_per_split = static_cast<int>((K + splits - 1) / splits);
@@ -729,7 +768,7 @@ static int launch_cfg(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t 
 #define FXP_GEMM_LAUNCH(VEC, MODE)                                                                                 \
     hipLaunchKernelGGL((k_gemm_nt<BM, BN, BK, WM, WN, VEC, MODE>), grid, block, 0, s, A, lda, B, ldb, C, ldc,       \
                        static_cast<int>(M), static_cast<int>(N), static_cast<int>(K), k_per_split, eA, bitsA, eB,   \
-                       bitsB, tiles_m, tiles_n, group_m, split_stride, bt.a, bt.b, bt.c)
+                       bitsB, tiles_m, tiles_n, group_m, split_stride, bt.a, bt.b, bt.c, amax)
     if (vec) {
         if (mode == kStoreI32) FXP_GEMM_LAUNCH(true, kStoreI32);
         else if (mode == kStoreF32) FXP_GEMM_LAUNCH(true, kStoreF32);
@@ -747,7 +786,7 @@ template <int WM, int WN, bool SCHED = true>
 static int launch_ring(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                        void* C, int64_t ldc, int mode, int splits, const int32_t* eA, int bitsA, const int32_t* eB,
                        int bitsB, hipStream_t s, int64_t split_stride = 0, int* slices = nullptr,
-                      Batch bt = Batch()) {
+                      Batch bt = Batch(), uint32_t* amax = nullptr) {
     constexpr int NT = (256 / WM) * (256 / WN) * 64, BK = 128;
     const int tiles_m = static_cast<int>((M + 255) / 256), tiles_n = static_cast<int>((N + 255) / 256);
     int k_per_split = static_cast<int>((K + splits - 1) / splits);
@@ -759,7 +798,7 @@ static int launch_ring(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t
 #define FXP_GEMM_LAUNCH(MODE)                                                                                    \
     hipLaunchKernelGGL((k_gemm_nt_ring<WM, WN, MODE, SCHED>), grid, block, 0, s, A, lda, B, ldb, C, ldc,          \
                        static_cast<int>(M), static_cast<int>(N), static_cast<int>(K), k_per_split, eA, bitsA, eB, \
-                       bitsB, tiles_m, tiles_n, group_m, split_stride, bt.a, bt.b, bt.c)
+                       bitsB, tiles_m, tiles_n, group_m, split_stride, bt.a, bt.b, bt.c, amax)
     if (mode == kStoreI32) FXP_GEMM_LAUNCH(kStoreI32);
     else if (mode == kStoreF32) FXP_GEMM_LAUNCH(kStoreF32);
     else FXP_GEMM_LAUNCH(kAtomicI32);
@@ -771,7 +810,7 @@ template <int BM, int BN, int BK, int WM, int WN, int STAGES, bool SCHED = true>
 static int launch_dma(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                       void* C, int64_t ldc, int mode, int splits, const int32_t* eA, int bitsA, const int32_t* eB,
                       int bitsB, hipStream_t s, int64_t split_stride = 0, int* slices = nullptr,
-                      Batch bt = Batch()) {
+                      Batch bt = Batch(), uint32_t* amax = nullptr) {
     constexpr int NT = (BM / WM) * (BN / WN) * 64;
     const int tiles_m = static_cast<int>((M + BM - 1) / BM), tiles_n = static_cast<int>((N + BN - 1) / BN);
     int k_per_split = static_cast<int>((K + splits - 1) / splits);
@@ -784,7 +823,7 @@ static int launch_dma(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t 
     hipLaunchKernelGGL((k_gemm_nt_dma<BM, BN, BK, WM, WN, STAGES, MODE, SCHED>), grid, block, 0, s, A, lda, B, ldb, C, \
                        ldc,                                                                                        \
                        static_cast<int>(M), static_cast<int>(N), static_cast<int>(K), k_per_split, eA, bitsA, eB,   \
-                       bitsB, tiles_m, tiles_n, group_m, split_stride, bt.a, bt.b, bt.c, ConvTaps())
+                       bitsB, tiles_m, tiles_n, group_m, split_stride, bt.a, bt.b, bt.c, ConvTaps(), amax)
     if (mode == kStoreI32) FXP_GEMM_LAUNCH(kStoreI32);
     else if (mode == kStoreF32) FXP_GEMM_LAUNCH(kStoreF32);
     else FXP_GEMM_LAUNCH(kAtomicI32);
@@ -796,7 +835,8 @@ static int launch_dma(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t 
 __global__ __launch_bounds__(256) void k_splitk_reduce(const int32_t* __restrict__ parts, int splits, int64_t stride,
                                                        int M, int N, void* __restrict__ Cv, int64_t ldc, int fp32_out,
                                                        const int32_t* __restrict__ eA, int bitsA,
-                                                       const int32_t* __restrict__ eB, int bitsB) {
+                                                       const int32_t* __restrict__ eB, int bitsB, uint32_t* __restrict__ amax) {
+    float m = 0.0f;
     int E = 0;
     if (fp32_out) E = lsb_exponent(eA[0], bitsA) + (eB ? lsb_exponent(eB[0], bitsB) : 0);
     const int nvec = N >> 2;                      // the slices are dense M x N: rows start 16-byte aligned when N % 4 == 0
@@ -817,6 +857,7 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const int32_t* __restrict
                     o.x = unmap_value(acc.x, E); o.y = unmap_value(acc.y, E);
                     o.z = unmap_value(acc.z, E); o.w = unmap_value(acc.w, E);
                     reinterpret_cast<float4*>(crow)[i] = o;
+                    m = fmaxf(fmaxf(m, fmaxf(fabsf(o.x), fabsf(o.y))), fmaxf(fabsf(o.z), fabsf(o.w)));
                 } else {
                     reinterpret_cast<int4*>(crow)[i] = acc;
                 }
@@ -825,11 +866,17 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const int32_t* __restrict
             for (int i = blockIdx.x * 256 + threadIdx.x; i < N; i += gridDim.x * 256) {
                 int acc = 0;
                 for (int sidx = 0; sidx < splits; ++sidx) acc += prow[sidx * stride + i];
-                if (fp32_out) reinterpret_cast<float*>(crow)[i] = unmap_value(acc, E);
-                else crow[i] = acc;
+                if (fp32_out) {
+                    const float o = unmap_value(acc, E);
+                    reinterpret_cast<float*>(crow)[i] = o;
+                    m = fmaxf(m, fabsf(o));
+                } else {
+                    crow[i] = acc;
+                }
             }
         }
     }
+    if (fp32_out && amax != nullptr) publish_absmax(m, amax);
 }
 
 // How a product is cut up.  Depends on the shape only, so that workspace sizing and launch agree.
@@ -906,10 +953,14 @@ int gemm_nt_batched_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int
 #undef FXP_BATCHED_TAIL
 }
 
+// amax (fp32_out only, may be null): FXP_ABSMAX_WORDS device words raised so that their maximum is at least the
+// IEEE bits of the largest |C| of this product.
 int gemm_nt_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                    void* C, int64_t ldc, bool fp32_out, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB,
-                   void* ws, size_t ws_bytes, hipStream_t s) {
+                   void* ws, size_t ws_bytes, hipStream_t s, uint32_t* amax) {
     if (M == 0 || N == 0) return FXP_OK;
+    if (!fp32_out) amax = nullptr;
+    uint32_t* amax1 = nullptr;      // the product kernel publishes the maximum itself only when it writes the final fp32
     const bool vec = aligned(A, 16) && aligned(B, 16) && lda % 16 == 0 && ldb % 16 == 0 && K % 16 == 0;
     const bool dma = vec && K >= 64;   // K % 16 == 0: the direct-to-LDS kernels pad a partial last step with zeros
     const GemmPlan plan = plan_gemm(M, N, K);
@@ -928,34 +979,36 @@ int gemm_nt_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda
     int hr, hc;
     dim3 hgrid;
     rows_launch_shape(M, N, ldc, &hr, &hc, &hgrid);
+    if (splits == 1) amax1 = amax;
+    const Batch one{};
     int rc, slices = 1;   // the launchers round a slice up to whole K steps, so fewer slices than planned may run
     if (splits > 1 && !to_ws) {
         hipLaunchKernelGGL(k_zero_rows, hgrid, dim3(256), 0, s, static_cast<int32_t*>(C), ldc, hr, hc);
         if ((rc = launch_status())) return rc;
     }
     if (!dma)
-        rc = launch_cfg<128, 128, 64, 64, 64>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, vec, splits, eA, bitsA, eB, bitsB, s, split_stride, &slices);
+        rc = launch_cfg<128, 128, 64, 64, 64>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, vec, splits, eA, bitsA, eB, bitsB, s, split_stride, &slices, one, amax1);
     else if (use256 && splits == 1 && stream_out)
         // 72 KiB of LDS per workgroup keeps two resident per CU: one stores its tile while the other multiplies
-        rc = launch_dma<128, 256, 64, 64, 64, 3>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, 1, eA, bitsA, eB, bitsB, s);
+        rc = launch_dma<128, 256, 64, 64, 64, 3>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, 1, eA, bitsA, eB, bitsB, s, 0, nullptr, one, amax1);
     else if (use256 && K % 128 == 0 && splits == 1)
-        rc = launch_ring<64, 128>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, 1, eA, bitsA, eB, bitsB, s);
+        rc = launch_ring<64, 128>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, 1, eA, bitsA, eB, bitsB, s, 0, nullptr, one, amax1);
     else if (use256)
-        rc = launch_dma<256, 256, 64, 64, 128, 4>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, splits, eA, bitsA, eB, bitsB, s, split_stride, &slices);
+        rc = launch_dma<256, 256, 64, 64, 128, 4>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, splits, eA, bitsA, eB, bitsB, s, split_stride, &slices, one, amax1);
     else if (K % 128 == 0)
-        rc = launch_dma<128, 128, 128, 64, 32, 4>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, splits, eA, bitsA, eB, bitsB, s, split_stride, &slices);
+        rc = launch_dma<128, 128, 128, 64, 32, 4>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, splits, eA, bitsA, eB, bitsB, s, split_stride, &slices, one, amax1);
     else
-        rc = launch_dma<128, 128, 64, 64, 64, 4>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, splits, eA, bitsA, eB, bitsB, s, split_stride, &slices);
+        rc = launch_dma<128, 128, 64, 64, 64, 4>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, splits, eA, bitsA, eB, bitsB, s, split_stride, &slices, one, amax1);
     if (rc || splits == 1) return rc;
     if (to_ws) {
         const dim3 rgrid(std::max(1, std::min(64, static_cast<int>((N / 4 + 255) / 256))),
                          static_cast<unsigned>(std::min<int64_t>(M, 65535)));
         hipLaunchKernelGGL(k_splitk_reduce, rgrid, dim3(256), 0, s, static_cast<const int32_t*>(ws), slices, M * N,
-                           static_cast<int>(M), static_cast<int>(N), C, ldc, fp32_out ? 1 : 0, eA, bitsA, eB, bitsB);
+                           static_cast<int>(M), static_cast<int>(N), C, ldc, fp32_out ? 1 : 0, eA, bitsA, eB, bitsB, amax);
         return launch_status();
     }
     if (!fp32_out) return rc;
-    hipLaunchKernelGGL(k_unmap_rows, hgrid, dim3(256), 0, s, static_cast<int32_t*>(C), ldc, hr, hc, eA, bitsA, eB, bitsB);
+    hipLaunchKernelGGL(k_unmap_rows, hgrid, dim3(256), 0, s, static_cast<int32_t*>(C), ldc, hr, hc, eA, bitsA, eB, bitsB, amax);
     return launch_status();
 }
 
@@ -971,7 +1024,7 @@ static int conv_gemm_launch_cfg(const ConvTaps& ct, int64_t K, int64_t M, int64_
     hipLaunchKernelGGL((k_gemm_nt_dma<BM, BN, BK, WM, WN, STAGES, kStoreF32, true, true>), grid, block, 0, s, Xq, K, Wq, K,
                        static_cast<void*>(Y), Cout, static_cast<int>(M), static_cast<int>(Cout), static_cast<int>(K),
                        static_cast<int>(K), eA, bitsA, eB, bitsB, tiles_m, tiles_n, 8, int64_t{0}, int64_t{0}, int64_t{0},
-                       int64_t{0}, ct);
+                       int64_t{0}, ct, static_cast<uint32_t*>(nullptr));
     return launch_status();
 }
 
@@ -1010,7 +1063,7 @@ size_t gemm_ws_worst(int64_t M, int64_t N, int64_t K) { return gemm_ws_bytes(1, 
 // Bring any operand form to the native one (transposed copies in ws), then run it.
 static int gemm_any(int transA, int transB, int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda,
                     const int8_t* B, int64_t ldb, void* C, int64_t ldc, bool fp32_out, const int32_t* eA, int bitsA,
-                    const int32_t* eB, int bitsB, void* ws, size_t ws_bytes, hipStream_t s) {
+                    const int32_t* eB, int bitsB, void* ws, size_t ws_bytes, hipStream_t s, uint32_t* amax = nullptr) {
     if (M == 0 || N == 0) return FXP_OK;
     const size_t need = gemm_ws_bytes(transA, transB, M, N, K);
     if (need > 0 && (!ws || ws_bytes < need)) return FXP_ERR_WORKSPACE;
@@ -1032,7 +1085,7 @@ static int gemm_any(int transA, int transB, int64_t M, int64_t N, int64_t K, con
     // what is left of the workspace serves the split-K slices (atomics are used if it is too small)
     const size_t used = static_cast<size_t>(w - static_cast<int8_t*>(ws));
     return gemm_nt_launch(M, N, K, A, lda, B, ldb, C, ldc, fp32_out, eA, bitsA, eB, bitsB, ws ? w : nullptr,
-                          ws_bytes > used ? ws_bytes - used : 0, s);
+                          ws_bytes > used ? ws_bytes - used : 0, s, amax);
 }
 
 }  // namespace fxp
@@ -1054,6 +1107,19 @@ extern "C" int fxp_gemm_unmap(int transA, int transB, int64_t M, int64_t N, int6
     if (bitsA < 2 || bitsA > 8 || (eB && (bitsB < 2 || bitsB > 8))) return FXP_ERR_BITS;
     return fxp::gemm_any(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, true, eA, bitsA, eB, bitsB, ws, ws_bytes,
                          static_cast<hipStream_t>(stream));
+}
+
+extern "C" int fxp_gemm_unmap_absmax(int transA, int transB, int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda,
+                                     const int8_t* B, int64_t ldb, const int32_t* eA, int bitsA, const int32_t* eB,
+                                     int bitsB, float* C, int64_t ldc, uint32_t* out_absmax, void* ws, size_t ws_bytes,
+                                     void* stream) {
+    int rc = fxp::check_gemm_args(M, N, K, A, lda, transA, B, ldb, transB, C, ldc);
+    if (rc) return rc;
+    if (!eA || !out_absmax) return FXP_ERR_NULL;
+    if (!fxp::aligned(out_absmax, 4)) return FXP_ERR_ALIGN;
+    if (bitsA < 2 || bitsA > 8 || (eB && (bitsB < 2 || bitsB > 8))) return FXP_ERR_BITS;
+    return fxp::gemm_any(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, true, eA, bitsA, eB, bitsB, ws, ws_bytes,
+                         static_cast<hipStream_t>(stream), out_absmax);
 }
 
 // Batched products for the attention matmuls (Q K^T and P V with per-tensor scales): `batch` independent

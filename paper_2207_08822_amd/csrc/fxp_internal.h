@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "../../include/fxp.h"
 
 namespace fxp {
@@ -45,7 +47,7 @@ int gemm_nt_batched_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int
                            hipStream_t s);
 int gemm_nt_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                    void* C, int64_t ldc, bool fp32_out, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB,
-                   void* ws, size_t ws_bytes, hipStream_t s);
+                   void* ws, size_t ws_bytes, hipStream_t s, uint32_t* amax = nullptr);
 size_t gemm_split_ws_bytes(int64_t M, int64_t N, int64_t K);
 // geometry of the patches an implicit-convolution GEMM reads: image H x W x C (channels-last), filter width
 // KW, stride, padding (rows / columns), output Ho x Wo
@@ -58,10 +60,23 @@ int conv_gemm_launch(const ConvTaps& ct, int KH, int64_t M, int64_t Cout, const 
 size_t gemm_ws_worst(int64_t M, int64_t N, int64_t K);
 int transpose_i8_launch(const int8_t* src, int64_t rows, int64_t cols, int64_t ld, int8_t* dst, hipStream_t s);
 
+// max over the 64 lanes of a wave, the same value in every lane.  Data-parallel-primitive moves inside the
+// vector ALU (within quads, within rows of 16, then row to row) instead of six round trips through the LDS
+// crossbar; the total arrives in lane 63 and is read from there.
 __device__ inline uint32_t wave_max(uint32_t v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = max(v, static_cast<uint32_t>(__shfl_xor(static_cast<int>(v), off)));
-    return v;
+    auto step = [](uint32_t x, auto ctrl, auto rows) {
+        const int t = __builtin_amdgcn_update_dpp(static_cast<int>(x), static_cast<int>(x), decltype(ctrl)::value,
+                                                  decltype(rows)::value, 0xf, false);
+        return max(x, static_cast<uint32_t>(t));
+    };
+    using std::integral_constant;
+    v = step(v, integral_constant<int, 0xB1>{}, integral_constant<int, 0xf>{});     // quad_perm [1,0,3,2]
+    v = step(v, integral_constant<int, 0x4E>{}, integral_constant<int, 0xf>{});     // quad_perm [2,3,0,1]
+    v = step(v, integral_constant<int, 0x141>{}, integral_constant<int, 0xf>{});    // row_half_mirror
+    v = step(v, integral_constant<int, 0x140>{}, integral_constant<int, 0xf>{});    // row_mirror: every row of 16 done
+    v = step(v, integral_constant<int, 0x142>{}, integral_constant<int, 0xa>{});    // row_bcast:15 into rows 1 and 3
+    v = step(v, integral_constant<int, 0x143>{}, integral_constant<int, 0xc>{});    // row_bcast:31 into rows 2 and 3
+    return static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(v), 63));
 }
 
 // max over a block of up to 1024 threads; lds holds blockDim.x / 64 words

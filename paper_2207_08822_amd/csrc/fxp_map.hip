@@ -434,6 +434,19 @@ extern "C" int fxp_map(const float* x, int64_t rows, int64_t cols, const int32_t
     return fxp::map_launch(t, seed, rounding, bits, static_cast<hipStream_t>(stream));
 }
 
+extern "C" int fxp_map_absmax(const float* x, int64_t rows, int64_t cols, const uint32_t* absmax, int32_t* e_max, int8_t* q,
+                              int8_t* qT, uint64_t seed, uint64_t stream_id, int rounding, int bits, void* stream) {
+    int rc = fxp::check_map_args(x, rows, cols, e_max, q, qT, rounding, bits);
+    if (rc) return rc;
+    if (!absmax) return FXP_ERR_NULL;
+    if (!fxp::aligned(absmax, 4)) return FXP_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (rows * cols == 0) return fxp::scale_finish(absmax, FXP_ABSMAX_WORDS, e_max, s);     // only the scale
+    // the words are a list of block maxima: the map kernel turns them into the scale and publishes it
+    const fxp::MapTensor t{x, rows, cols, nullptr, absmax, FXP_ABSMAX_WORDS, e_max, q, qT, stream_id};
+    return fxp::map_launch(t, seed, rounding, bits, s);
+}
+
 extern "C" int fxp_scale_map(const float* x, int64_t rows, int64_t cols, int32_t* e_max, int8_t* q, int8_t* qT,
                              uint64_t seed, uint64_t stream_id, int rounding, int bits, void* ws, size_t ws_bytes,
                              void* stream) {

@@ -15,6 +15,7 @@ from . import build as _build
 STOCHASTIC, NEAREST = 0, 1
 OP_SCALE, OP_GEMM, OP_LINEAR_FWD, OP_LINEAR_BWD, OP_BMM_FWD, OP_BMM_BWD = 0, 1, 2, 3, 4, 5
 TAG_X, TAG_W, TAG_DY = 0, 1, 2
+ABSMAX_WORDS = 256      # uint32 words of an abs-max area (FXP_ABSMAX_WORDS)
 
 
 class FxpError(RuntimeError):
@@ -71,6 +72,8 @@ def lib():
     L.fxp_unmap.argtypes = [vp, sz, vp, ci, vp, ci, vp, vp]
     L.fxp_unmap_i8.argtypes = [vp, sz, vp, ci, vp, vp]
     L.fxp_gemm_unmap.argtypes = [ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, ci, vp, ci, vp, i64, vp, sz, vp]
+    L.fxp_gemm_unmap_absmax.argtypes = [ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, ci, vp, ci, vp, i64, vp, vp, sz, vp]
+    L.fxp_map_absmax.argtypes = [vp, i64, i64, vp, vp, vp, vp, u64, u64, ci, ci, vp]
     L.fxp_linear_fwd.argtypes = [vp, vp, i64, i64, i64, vp, c.POINTER(_Saved), u64, u64, ci, ci, vp, sz, vp]
     L.fxp_linear_bwd.argtypes = [vp, c.POINTER(_Saved), i64, i64, i64, vp, vp, vp, vp, vp, u64, u64, ci, ci, vp, sz, vp]
     L.fxp_conv2d_workspace_bytes.restype = sz
@@ -100,6 +103,7 @@ def lib():
     L.fxp_axpy16.restype = ci
     L.fxp_sgd16_step.restype = ci
     for name in ("fxp_scale", "fxp_map", "fxp_scale_map", "fxp_gemm", "fxp_unmap", "fxp_unmap_i8", "fxp_gemm_unmap",
+                 "fxp_gemm_unmap_absmax", "fxp_map_absmax",
                  "fxp_linear_fwd", "fxp_linear_bwd", "fxp_gemm_batched", "fxp_gemm_unmap_batched", "fxp_bmm_fwd",
                  "fxp_bmm_bwd"):
         getattr(L, name).restype = ci
@@ -217,6 +221,29 @@ def gemm_unmap(A, B, eA, eB, transA=False, transB=False, bitsA=8, bitsB=8, ws=No
     _check(lib().fxp_gemm_unmap(int(transA), int(transB), M, N, K, _p(A), A.shape[1], _p(B), B.shape[1], _p(eA), bitsA,
                                 _p(eB), bitsB, _p(C), N, _p(ws), ws.numel(), _stream()), "fxp_gemm_unmap")
     return C
+
+
+def gemm_unmap_absmax(A, B, eA, eB, absmax, transA=False, transB=False, bitsA=8, bitsB=8, ws=None):
+    """gemm_unmap that also raises the abs-max area `absmax` (ABSMAX_WORDS int32 words, bits of max |C|) for map_absmax."""
+    A, B = _dev(A, torch.int8, "A"), _dev(B, torch.int8, "B")
+    M, N, K = _gemm_dims(A, B, transA, transB)
+    C = torch.empty((M, N), dtype=torch.float32, device=A.device)
+    ws = ws if ws is not None else _ws(OP_GEMM, M, N, K, device=A.device)
+    _check(lib().fxp_gemm_unmap_absmax(int(transA), int(transB), M, N, K, _p(A), A.shape[1], _p(B), B.shape[1], _p(eA), bitsA,
+                                   _p(eB), bitsB, _p(C), N, _p(absmax), _p(ws), ws.numel(), _stream()),
+           "fxp_gemm_unmap_absmax")
+    return C
+
+
+def map_absmax(x, absmax, seed=0, stream_id=0, rounding=STOCHASTIC, bits=8, want_q=True, want_qT=False):
+    """(e_max, q, qT) of x with the scale taken from the abs-max area `absmax` (its maximum = bits of max |x|)."""
+    x = _dev(x, torch.float32, "x")
+    assert x.dim() == 2
+    e = torch.empty(1, dtype=torch.int32, device=x.device)
+    q, qT = _map_outputs(x, want_q, want_qT)
+    _check(lib().fxp_map_absmax(_p(x), x.shape[0], x.shape[1], _p(absmax), _p(e), _p(q), _p(qT), seed, stream_id, rounding,
+                            bits, _stream()), "fxp_map_absmax")
+    return e, q, qT
 
 
 class LayerBuffers:

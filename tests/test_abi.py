@@ -53,6 +53,16 @@ def test_host_only_entry_points_and_argument_errors():
     assert L.fxp_gemm(0, 0, 4, 4, 16, fake, 16, fake, 16, fake, 4, None, 0, None) == -4    # needs workspace
     L.fxp_scale.argtypes = [vp, sz, vp, vp, sz, vp]
     assert L.fxp_scale(fake, 16, fake, None, 0, None) == -4
+    # the abs-max chain: a product that leaves its output's largest magnitude, and the map that takes its scale from it
+    L.fxp_gemm_unmap_absmax.argtypes = [ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, ci, vp, ci, vp, i64, vp, vp, sz, vp]
+    assert L.fxp_gemm_unmap_absmax(0, 1, 4, 4, 16, fake, 16, fake, 16, fake, 8, fake, 8, fake, 4, None, None, 0, None) == -1
+    assert L.fxp_gemm_unmap_absmax(0, 1, 4, 4, 16, fake, 16, fake, 16, fake, 8, fake, 8, fake, 4, ctypes.c_void_p(4098), None, 0,
+                                   None) == -3
+    assert L.fxp_gemm_unmap_absmax(0, 1, 4, 4, 16, fake, 16, fake, 16, fake, 9, fake, 8, fake, 4, fake, None, 0, None) == -6
+    L.fxp_map_absmax.argtypes = [vp, i64, i64, vp, vp, vp, vp, u64, u64, ci, ci, vp]
+    assert L.fxp_map_absmax(fake, 4, 4, None, fake, fake, None, 0, 0, 0, 8, None) == -1
+    assert L.fxp_map_absmax(fake, 4, 4, fake, None, fake, None, 0, 0, 0, 8, None) == -1      # the scale is always written
+    assert L.fxp_map_absmax(fake, 4, 4, fake, fake, fake, None, 0, 0, 5, 8, None) == -5
 
 
 def test_argument_errors_of_the_layer_level_entry_points():

@@ -290,6 +290,46 @@ def layer_check_full(fxp, X, W, dY, seed, step, rounding=0, bits=8):
     return buf
 
 
+ABSMAX_SHAPES = [(2560, 2560, 256), (4096, 1536, 128), (300, 200, 160), (100, 90, 50), (256, 128, 8192), (17, 5, 7)]
+
+
+@pytest.mark.parametrize("M,N,K", ABSMAX_SHAPES)
+def test_product_leaves_its_absmax_for_the_next_map(fxp, M, N, K):
+    """fxp_gemm_unmap_absmax: same output as fxp_gemm_unmap, and the word it raises is the bit pattern of the
+    largest |C|, from which fxp_map_absmax takes the scale the reduction pass would have found (every kernel
+    family: 256-tiles, output-streaming tile, 128-tiles, element-wise loader, split along K with and without
+    workspace)."""
+    say("gemm absmax", M, N, K)
+    rng = np.random.default_rng(M + N + K)
+    A, B = rand_i8(rng, (M, K)), rand_i8(rng, (N, K))
+    eA, eB = 128, 121
+    want = oracle.unmap(oracle.gemm(A, B, transB=True), eA, eB)
+    top = int(np.abs(want).max().view(np.uint32))
+    e = dev(np.array([eA, eB], np.int32))
+    for ws in (None, torch.empty(256, dtype=torch.uint8, device="cuda")):      # second: no room for split-K slices
+        word = torch.zeros(fxp.ABSMAX_WORDS, dtype=torch.int32, device="cuda")
+        C = fxp.gemm_unmap_absmax(dev(A), dev(B), e[0:1], e[1:2], word, transB=True, ws=ws)
+        assert same_bits(host(C), want)
+        assert int(host(word).max()) == top
+        es, q, qT = fxp.map_absmax(C, word, seed=3, stream_id=515, want_q=True, want_qT=True)
+        e_ref = oracle.scale(want)
+        wq = oracle.map(want, e_ref, seed=3, stream_id=515)
+        assert int(host(es)[0]) == e_ref
+        assert np.array_equal(host(q), wq) and np.array_equal(host(qT), wq.T)
+    # the word only ever rises: a larger value stays, and a second product adds its own maximum
+    word = torch.full((fxp.ABSMAX_WORDS,), 0x7F000000, dtype=torch.int32, device="cuda")
+    fxp.gemm_unmap_absmax(dev(A), dev(B), e[0:1], e[1:2], word, transB=True)
+    assert bool((word == 0x7F000000).all())
+    word = torch.full((fxp.ABSMAX_WORDS,), 5, dtype=torch.int32, device="cuda")
+    fxp.gemm_unmap_absmax(dev(A), dev(B), e[0:1], e[1:2], word, transB=True)
+    assert int(host(word).max()) == top and int(host(word).min()) >= 5
+    # an output that overflows to Inf reports the bits of Inf: scale 255, as the reduction pass would
+    big = dev(np.array([254, 254], np.int32))
+    word = torch.zeros(fxp.ABSMAX_WORDS, dtype=torch.int32, device="cuda")
+    C = fxp.gemm_unmap_absmax(dev(A), dev(B), big[0:1], big[1:2], word, transB=True)
+    assert same_bits(host(C), oracle.unmap(oracle.gemm(A, B, transB=True), 254, 254)) and int(host(word).max()) == 0x7F800000
+
+
 def test_layer_c1_full(fxp):
     say("layer c1 256^3, seed 0")
     X, W, dY = synth.layer_tensors("c1")
