@@ -970,7 +970,7 @@ int gemm_nt_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda
     // contraction or an output of 128 MB and more (measured: c2 dX 26.6 -> 25.0 us, ViT fc1 forward 59 -> 53 us; the
     // 256 x 256 ring kernel stays ahead on the narrower and smaller outputs)
     const bool hbm_bound = 2.0 * M * N * K < 625.0 * (static_cast<double>(M) * K + static_cast<double>(N) * K + 4.0 * M * N);
-    const bool stream_out = hbm_bound && N >= 1024 && (K <= 256 || 4.0 * M * N >= 128.0 * 1024 * 1024);
+    const bool stream_out = hbm_bound && N >= 1024 && (K <= 256 || 4.0 * M * N >= 96.0 * 1024 * 1024);
     const bool to_ws = splits > 1 && ws != nullptr && aligned(ws, 16) && ws_bytes >= gemm_split_ws_bytes(M, N, K);
     const int first_mode = splits > 1 ? (to_ws ? kStoreI32 : kAtomicI32) : (fp32_out ? kStoreF32 : kStoreI32);
     void* dst = to_ws ? ws : C;
@@ -988,8 +988,12 @@ int gemm_nt_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda
     }
     if (!dma)
         rc = launch_cfg<128, 128, 64, 64, 64>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, vec, splits, eA, bitsA, eB, bitsB, s, split_stride, &slices, one, amax1);
+    else if (use256 && splits == 1 && stream_out && K % 128 == 0 && (K <= 256 || 4.0 * M * N < 128.0 * 1024 * 1024))
+        // 64 KiB of LDS per workgroup keeps two resident per CU: one stores its tile while the other multiplies
+        // (ResNet dX 25088 x 1152 x 128: 22.5 us against 27.3 with the 128 x 256 tile and 24.4 with the ring kernel;
+        // ViT qkv forward 36.7 / 38.3 / 40.5; fc1 forward 48.1 / 46.9 / 54.7)
+        rc = launch_dma<128, 128, 128, 64, 64, 2>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, 1, eA, bitsA, eB, bitsB, s, 0, nullptr, one, amax1);
     else if (use256 && splits == 1 && stream_out)
-        // 72 KiB of LDS per workgroup keeps two resident per CU: one stores its tile while the other multiplies
         rc = launch_dma<128, 256, 64, 64, 64, 3>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, 1, eA, bitsA, eB, bitsB, s, 0, nullptr, one, amax1);
     else if (use256 && K % 128 == 0 && splits == 1)
         rc = launch_ring<64, 128>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, 1, eA, bitsA, eB, bitsB, s, 0, nullptr, one, amax1);
