@@ -108,6 +108,25 @@ def test_map_edge_values(fxp):
     check_map(fxp, x[1:], seed=2**64 - 1, sid=2**63 + 12345)
 
 
+def test_map_random_magnitudes_scales_and_widths(fxp):
+    """Seeded random tensors over the whole exponent range: values spread over up to 60 binades (so that shifts
+    of every size occur, sub-normals and zeros included), the tensor's own scale and scales a few steps above and
+    below it, every width and both roundings."""
+    rng = np.random.default_rng(2024)
+    for case in range(40):
+        rows, cols = int(rng.integers(1, 200)), int(rng.integers(1, 70)) * 4
+        centre = int(rng.integers(-125, 120))
+        spread = int(rng.integers(1, 60))
+        expo = rng.integers(centre - spread, centre + 1, size=(rows, cols))
+        x = (rng.standard_normal((rows, cols)) * np.exp2(expo.astype(np.float64))).astype(np.float32)
+        x[rng.random((rows, cols)) < 0.1] = 0.0
+        own = oracle.scale(x)
+        e_max = int(np.clip(own + int(rng.integers(-3, 4)), 1, 254))
+        bits, rounding = int(rng.integers(2, 9)), int(rng.integers(0, 2))
+        say("map random", case, (rows, cols), "own scale", own, "used", e_max, "bits", bits, "rounding", rounding)
+        check_map(fxp, x, e_max=e_max, seed=case, sid=(case << 8) | 2, rounding=rounding, bits=bits)
+
+
 def test_map_random_index_beyond_32_bits_is_keyed_by_element(fxp):
     """Row-major element index drives the random word, independent of the tiling."""
     say("map reshape invariance")
