@@ -375,6 +375,7 @@ extern "C" int fxp_conv2d_bwd(const float* dY, const fxp_conv_saved* saved, cons
                             reinterpret_cast<uint32_t*>(w8), s)))
         return rc;
     const bool need_flip = dX && dx_as_conv(g);
+    ReduceRider pending;                 // the weight gradient's split-K reduction while it waits for a launch to ride in
     if (need_flip && !dW) {
         hipLaunchKernelGGL(k_flip_weights_i8, dim3(grid_for(static_cast<int64_t>(g.Cout) * K)), dim3(256), 0, s, saved->Wq, g,
                            saved->WqF);
@@ -400,8 +401,10 @@ extern "C" int fxp_conv2d_bwd(const float* dY, const fxp_conv_saved* saved, cons
         if ((rc = launch_status())) return rc;
         const size_t used = round_up(static_cast<size_t>(K) * M, 256);
         // dW[Cout, K] = dYqT[Cout, M] * colT[K, M]^T, contraction over all output pixels
+        // (split along K: the sum of its slices rides in the launch of the input-gradient convolution when that
+        // one reads its patches in the loader and leaves the workspace alone)
         if ((rc = gemm_nt_launch(g.Cout, K, M, dYqT, M, colT, M, dW, K, true, e_dY, bits, saved->eX, bits, area + used,
-                                 area_bytes - used, s)))
+                                 area_bytes - used, s, nullptr, nullptr, dX && dx_as_conv(g) ? &pending : nullptr)))
             return rc;
     }
     if (dX && dx_as_conv(g)) {
@@ -409,8 +412,16 @@ extern "C" int fxp_conv2d_bwd(const float* dY, const fxp_conv_saved* saved, cons
         const ConvGeo d = dx_geo(g);
         int8_t* colg = reinterpret_cast<int8_t*>(area);
         const int64_t Md = d.M(), Kd = d.K();
-        rc = conv_gemm_launch(taps_of(d), d.KH, Md, g.C, dYq, saved->WqF, dX, e_dY, bits, saved->eW, bits, s);
-        if (rc != kNotApplicable) return rc;
+        rc = conv_gemm_launch(taps_of(d), d.KH, Md, g.C, dYq, saved->WqF, dX, e_dY, bits, saved->eW, bits, s, &pending);
+        if (rc != kNotApplicable) {
+            if (rc == FXP_OK && pending.blocks != 0) rc = splitk_reduce_launch(pending, s);
+            return rc;
+        }
+        // the explicit path below reuses the workspace: the weight gradient's slices are summed first
+        if (pending.blocks != 0) {
+            if ((rc = splitk_reduce_launch(pending, s))) return rc;
+            pending.blocks = 0;
+        }
         if (d.C % 16 == 0)
             hipLaunchKernelGGL(k_im2col_i8<16>, dim3(static_cast<unsigned>((Md + 31) / 32)), dim3(256), 0, s, dYq, d, colg);
         else

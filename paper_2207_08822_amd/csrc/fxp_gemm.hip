@@ -143,12 +143,82 @@ __device__ inline float store_fragments(const v16i (&acc)[FM][FN], void* __restr
     return store_loop<FM, FN, MODE, AMAX, true>(acc, Cv, ldc, M, N, row0, col0, fhalf, frow, E);
 }
 
+// Sum of the split-K slices of a product (int32, exact in any order) -> int32 or inverse-mapped fp32, by workgroup
+// `b` of `nb`.  The slices are dense M x N matrices `stride` elements apart.  A dense, 16-byte aligned output is
+// walked as one flat run of 16-byte pieces, anything else row by row.
+__device__ inline void splitk_reduce_body(const ReduceRider& r, unsigned b, unsigned nb) {
+    const unsigned nt = blockDim.x;                  // 256 stand-alone; the host product's workgroup size when riding
+    float m = 0.0f;
+    int E = 0;
+    if (r.fp32_out) E = lsb_exponent(r.eA[0], r.bitsA) + (r.eB ? lsb_exponent(r.eB[0], r.bitsB) : 0);
+    const int32_t* __restrict__ parts = r.parts;
+    const int64_t stride = r.stride;
+    const int splits = r.splits;
+    auto one = [&](int acc, int32_t* dst) {
+        if (r.fp32_out) {
+            const float o = unmap_value(acc, E);
+            *reinterpret_cast<float*>(dst) = o;
+            m = fmaxf(m, fabsf(o));
+        } else {
+            *dst = acc;
+        }
+    };
+    const int64_t total = static_cast<int64_t>(r.M) * r.N;
+    const bool flat = r.ldc == r.N && (reinterpret_cast<uintptr_t>(r.C) & 15u) == 0;
+    if (flat) {
+        const int64_t nvec = total >> 2;
+        for (int64_t i = static_cast<int64_t>(b) * nt + threadIdx.x; i < nvec; i += static_cast<int64_t>(nb) * nt) {
+            int4 acc = make_int4(0, 0, 0, 0);
+#pragma unroll 8
+            for (int sidx = 0; sidx < splits; ++sidx) {
+                const int4 v = reinterpret_cast<const int4*>(parts + sidx * stride)[i];
+                acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+            }
+            if (r.fp32_out) {
+                float4 o;
+                o.x = unmap_value(acc.x, E); o.y = unmap_value(acc.y, E);
+                o.z = unmap_value(acc.z, E); o.w = unmap_value(acc.w, E);
+                reinterpret_cast<float4*>(r.C)[i] = o;
+                m = fmaxf(fmaxf(m, fmaxf(fabsf(o.x), fabsf(o.y))), fmaxf(fabsf(o.z), fabsf(o.w)));
+            } else {
+                reinterpret_cast<int4*>(r.C)[i] = acc;
+            }
+        }
+        if (b == 0 && threadIdx.x < (total & 3)) {                 // the slices are 16-byte aligned, the tail is not a piece
+            const int64_t i = (nvec << 2) + threadIdx.x;
+            int acc = 0;
+            for (int sidx = 0; sidx < splits; ++sidx) acc += parts[sidx * stride + i];
+            one(acc, static_cast<int32_t*>(r.C) + i);
+        }
+    } else {
+        for (int row = static_cast<int>(b); row < r.M; row += static_cast<int>(nb)) {
+            const int32_t* prow = parts + static_cast<int64_t>(row) * r.N;
+            int32_t* crow = static_cast<int32_t*>(r.C) + static_cast<int64_t>(row) * r.ldc;
+            for (int i = threadIdx.x; i < r.N; i += static_cast<int>(nt)) {
+                int acc = 0;
+                for (int sidx = 0; sidx < splits; ++sidx) acc += prow[sidx * stride + i];
+                one(acc, crow + i);
+            }
+        }
+    }
+    if (r.fp32_out && r.amax != nullptr) publish_absmax(m, r.amax);
+}
+
 template <int BM, int BN, int BK, int WM, int WN, bool VEC, int MODE>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm_nt(
     const int8_t* __restrict__ A, int64_t lda, const int8_t* __restrict__ B, int64_t ldb, void* __restrict__ Cv,
     int64_t ldc, int M, int N, int K, int k_per_split, const int32_t* __restrict__ eA, int bitsA,
     const int32_t* __restrict__ eB, int bitsB, int tiles_m, int tiles_n, int group_m, int64_t split_stride,
-    int64_t batch_a, int64_t batch_b, int64_t batch_c, uint32_t* __restrict__ amax) {
+    int64_t batch_a, int64_t batch_b, int64_t batch_c, uint32_t* __restrict__ amax, ReduceRider rider) {
+    int tile_block = static_cast<int>(blockIdx.x);
+    if (rider.blocks != 0) {                                      // workgroup-uniform
+        const unsigned first = rider.front ? 0u : rider.tiles;    // the riders are the first or the last workgroups
+        if (blockIdx.x >= first && blockIdx.x < first + rider.blocks) {
+            splitk_reduce_body(rider, blockIdx.x - first, rider.blocks);
+            return;
+        }
+        if (rider.front) tile_block -= static_cast<int>(rider.blocks);
+    }
     constexpr int NT = (BM / WM) * (BN / WN) * 64;
     constexpr int CPR = BK / 16;
     constexpr int NA = BM * CPR / NT, NB = BN * CPR / NT;   // 16-byte pieces per thread per step
@@ -158,7 +228,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm_nt(
     __shared__ __attribute__((aligned(16))) int8_t lds[2][(BM + BN) * BK];
 
     int tm, tn;
-    tile_of_block(blockIdx.x, tiles_m, tiles_n, group_m, &tm, &tn);
+    tile_of_block(tile_block, tiles_m, tiles_n, group_m, &tm, &tn);
     const int m0 = tm * BM, n0 = tn * BN;
     const int kb = blockIdx.y * k_per_split;
     // split-K into a workspace: slice y owns its own M x N int32 matrix (split_stride elements apart)
@@ -296,7 +366,16 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm_nt_dma(
     const int8_t* __restrict__ A, int64_t lda, const int8_t* __restrict__ B, int64_t ldb, void* __restrict__ Cv,
     int64_t ldc, int M, int N, int K, int k_per_split, const int32_t* __restrict__ eA, int bitsA,
     const int32_t* __restrict__ eB, int bitsB, int tiles_m, int tiles_n, int group_m, int64_t split_stride,
-    int64_t batch_a, int64_t batch_b, int64_t batch_c, ConvTaps ct, uint32_t* __restrict__ amax) {
+    int64_t batch_a, int64_t batch_b, int64_t batch_c, ConvTaps ct, uint32_t* __restrict__ amax, ReduceRider rider) {
+    int tile_block = static_cast<int>(blockIdx.x);
+    if (rider.blocks != 0) {                                      // workgroup-uniform
+        const unsigned first = rider.front ? 0u : rider.tiles;    // the riders are the first or the last workgroups
+        if (blockIdx.x >= first && blockIdx.x < first + rider.blocks) {
+            splitk_reduce_body(rider, blockIdx.x - first, rider.blocks);
+            return;
+        }
+        if (rider.front) tile_block -= static_cast<int>(rider.blocks);
+    }
     constexpr int NW = (BM / WM) * (BN / WN);
     constexpr int CPR = BK / 16;                     // 16-byte pieces per LDS row
     constexpr int RROWS = 64 / CPR;                  // tile rows per 1 KiB region
@@ -319,7 +398,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm_nt_dma(
     int tm, tn, slice = 0, matrix = 0;
     const int outer = static_cast<int>(gridDim.y * gridDim.z);     // never both: a batch is not split
     if (outer == 1) {
-        tile_of_block(blockIdx.x, tiles_m, tiles_n, group_m, &tm, &tn);
+        tile_of_block(tile_block, tiles_m, tiles_n, group_m, &tm, &tn);
     } else {
         const int64_t tiles = static_cast<int64_t>(tiles_m) * tiles_n, total = tiles * outer;
         const int64_t v = (static_cast<int64_t>(blockIdx.z) * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
@@ -517,7 +596,16 @@ __global__ __launch_bounds__((256 / WM) * (256 / WN) * 64) void k_gemm_nt_ring(
     const int8_t* __restrict__ A, int64_t lda, const int8_t* __restrict__ B, int64_t ldb, void* __restrict__ Cv,
     int64_t ldc, int M, int N, int K, int k_per_split, const int32_t* __restrict__ eA, int bitsA,
     const int32_t* __restrict__ eB, int bitsB, int tiles_m, int tiles_n, int group_m, int64_t split_stride,
-    int64_t batch_a, int64_t batch_b, int64_t batch_c, uint32_t* __restrict__ amax) {
+    int64_t batch_a, int64_t batch_b, int64_t batch_c, uint32_t* __restrict__ amax, ReduceRider rider) {
+    int tile_block = static_cast<int>(blockIdx.x);
+    if (rider.blocks != 0) {                                      // workgroup-uniform
+        const unsigned first = rider.front ? 0u : rider.tiles;    // the riders are the first or the last workgroups
+        if (blockIdx.x >= first && blockIdx.x < first + rider.blocks) {
+            splitk_reduce_body(rider, blockIdx.x - first, rider.blocks);
+            return;
+        }
+        if (rider.front) tile_block -= static_cast<int>(rider.blocks);
+    }
     constexpr int BM = 256, BN = 256, BK = 128;
     constexpr int NW = (BM / WM) * (BN / WN);
     constexpr int SLOT = 256 * BK;                   // bytes of a half-stage
@@ -528,7 +616,7 @@ __global__ __launch_bounds__((256 / WM) * (256 / WN) * 64) void k_gemm_nt_ring(
     __shared__ __attribute__((aligned(1024))) int8_t lds[5 * SLOT];
 
     int tm, tn;
-    tile_of_block(blockIdx.x, tiles_m, tiles_n, group_m, &tm, &tn);
+    tile_of_block(tile_block, tiles_m, tiles_n, group_m, &tm, &tn);
     const int m0 = tm * BM, n0 = tn * BN;
     const int kb = blockIdx.y * k_per_split;
     // split-K into a workspace: slice y owns its own M x N int32 matrix (split_stride elements apart)
@@ -755,7 +843,7 @@ template <int BM, int BN, int BK, int WM, int WN>
 static int launch_cfg(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                       void* C, int64_t ldc, int mode, bool vec, int splits, const int32_t* eA, int bitsA,
                       const int32_t* eB, int bitsB, hipStream_t s, int64_t split_stride = 0, int* slices = nullptr,
-                      Batch bt = Batch(), uint32_t* amax = nullptr) {
+                      Batch bt = Batch(), uint32_t* amax = nullptr, ReduceRider* ride = nullptr) {
     constexpr int NT = (BM / WM) * (BN / WN) * 64;
     const int tiles_m = static_cast<int>((M + BM - 1) / BM), tiles_n = static_cast<int>((N + BN - 1) / BN);
     int k_per_split = static_cast<int>((K + splits - 1) / splits);
@@ -763,12 +851,19 @@ static int launch_cfg(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t 
     if (k_per_split == 0) k_per_split = BK;
     const int ny = K > 0 ? static_cast<int>((K + k_per_split - 1) / k_per_split) : 1;
     if (slices) *slices = ny;
-    const dim3 grid(static_cast<unsigned>(tiles_m) * tiles_n, ny, bt.count), block(NT);
+    ReduceRider rider;                                          // rides only in an unsplit, unbatched launch
+    if (ride != nullptr && ride->blocks != 0 && ny == 1 && bt.count == 1) {
+        rider = *ride;
+        rider.tiles = static_cast<unsigned>(tiles_m) * tiles_n;
+        rider.front = rider.tiles >= 512;                       // several rounds of tiles: ride in the first one
+        ride->blocks = 0;                                       // taken
+    }
+    const dim3 grid(static_cast<unsigned>(tiles_m) * tiles_n + rider.blocks, ny, bt.count), block(NT);
     const int group_m = 8;
 #define FXP_GEMM_LAUNCH(VEC, MODE)                                                                                 \
     hipLaunchKernelGGL((k_gemm_nt<BM, BN, BK, WM, WN, VEC, MODE>), grid, block, 0, s, A, lda, B, ldb, C, ldc,       \
                        static_cast<int>(M), static_cast<int>(N), static_cast<int>(K), k_per_split, eA, bitsA, eB,   \
-                       bitsB, tiles_m, tiles_n, group_m, split_stride, bt.a, bt.b, bt.c, amax)
+                       bitsB, tiles_m, tiles_n, group_m, split_stride, bt.a, bt.b, bt.c, amax, rider)
     if (vec) {
         if (mode == kStoreI32) FXP_GEMM_LAUNCH(true, kStoreI32);
         else if (mode == kStoreF32) FXP_GEMM_LAUNCH(true, kStoreF32);
@@ -786,19 +881,26 @@ template <int WM, int WN, bool SCHED = true>
 static int launch_ring(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                        void* C, int64_t ldc, int mode, int splits, const int32_t* eA, int bitsA, const int32_t* eB,
                        int bitsB, hipStream_t s, int64_t split_stride = 0, int* slices = nullptr,
-                      Batch bt = Batch(), uint32_t* amax = nullptr) {
+                      Batch bt = Batch(), uint32_t* amax = nullptr, ReduceRider* ride = nullptr) {
     constexpr int NT = (256 / WM) * (256 / WN) * 64, BK = 128;
     const int tiles_m = static_cast<int>((M + 255) / 256), tiles_n = static_cast<int>((N + 255) / 256);
     int k_per_split = static_cast<int>((K + splits - 1) / splits);
     k_per_split = (k_per_split + BK - 1) / BK * BK;
     const int ny = static_cast<int>((K + k_per_split - 1) / k_per_split);
     if (slices) *slices = ny;
-    const dim3 grid(static_cast<unsigned>(tiles_m) * tiles_n, ny, bt.count), block(NT);
+    ReduceRider rider;                                          // rides only in an unsplit, unbatched launch
+    if (ride != nullptr && ride->blocks != 0 && ny == 1 && bt.count == 1) {
+        rider = *ride;
+        rider.tiles = static_cast<unsigned>(tiles_m) * tiles_n;
+        rider.front = rider.tiles >= 512;                       // several rounds of tiles: ride in the first one
+        ride->blocks = 0;                                       // taken
+    }
+    const dim3 grid(static_cast<unsigned>(tiles_m) * tiles_n + rider.blocks, ny, bt.count), block(NT);
     const int group_m = 8;
 #define FXP_GEMM_LAUNCH(MODE)                                                                                    \
     hipLaunchKernelGGL((k_gemm_nt_ring<WM, WN, MODE, SCHED>), grid, block, 0, s, A, lda, B, ldb, C, ldc,          \
                        static_cast<int>(M), static_cast<int>(N), static_cast<int>(K), k_per_split, eA, bitsA, eB, \
-                       bitsB, tiles_m, tiles_n, group_m, split_stride, bt.a, bt.b, bt.c, amax)
+                       bitsB, tiles_m, tiles_n, group_m, split_stride, bt.a, bt.b, bt.c, amax, rider)
     if (mode == kStoreI32) FXP_GEMM_LAUNCH(kStoreI32);
     else if (mode == kStoreF32) FXP_GEMM_LAUNCH(kStoreF32);
     else FXP_GEMM_LAUNCH(kAtomicI32);
@@ -810,20 +912,27 @@ template <int BM, int BN, int BK, int WM, int WN, int STAGES, bool SCHED = true>
 static int launch_dma(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                       void* C, int64_t ldc, int mode, int splits, const int32_t* eA, int bitsA, const int32_t* eB,
                       int bitsB, hipStream_t s, int64_t split_stride = 0, int* slices = nullptr,
-                      Batch bt = Batch(), uint32_t* amax = nullptr) {
+                      Batch bt = Batch(), uint32_t* amax = nullptr, ReduceRider* ride = nullptr) {
     constexpr int NT = (BM / WM) * (BN / WN) * 64;
     const int tiles_m = static_cast<int>((M + BM - 1) / BM), tiles_n = static_cast<int>((N + BN - 1) / BN);
     int k_per_split = static_cast<int>((K + splits - 1) / splits);
     k_per_split = (k_per_split + BK - 1) / BK * BK;
     const int ny = static_cast<int>((K + k_per_split - 1) / k_per_split);
     if (slices) *slices = ny;
-    const dim3 grid(static_cast<unsigned>(tiles_m) * tiles_n, ny, bt.count), block(NT);
+    ReduceRider rider;                                          // rides only in an unsplit, unbatched launch
+    if (ride != nullptr && ride->blocks != 0 && ny == 1 && bt.count == 1) {
+        rider = *ride;
+        rider.tiles = static_cast<unsigned>(tiles_m) * tiles_n;
+        rider.front = rider.tiles >= 512;                       // several rounds of tiles: ride in the first one
+        ride->blocks = 0;                                       // taken
+    }
+    const dim3 grid(static_cast<unsigned>(tiles_m) * tiles_n + rider.blocks, ny, bt.count), block(NT);
     const int group_m = 8;
 #define FXP_GEMM_LAUNCH(MODE)                                                                                      \
     hipLaunchKernelGGL((k_gemm_nt_dma<BM, BN, BK, WM, WN, STAGES, MODE, SCHED>), grid, block, 0, s, A, lda, B, ldb, C, \
                        ldc,                                                                                        \
                        static_cast<int>(M), static_cast<int>(N), static_cast<int>(K), k_per_split, eA, bitsA, eB,   \
-                       bitsB, tiles_m, tiles_n, group_m, split_stride, bt.a, bt.b, bt.c, ConvTaps(), amax)
+                       bitsB, tiles_m, tiles_n, group_m, split_stride, bt.a, bt.b, bt.c, ConvTaps(), amax, rider)
     if (mode == kStoreI32) FXP_GEMM_LAUNCH(kStoreI32);
     else if (mode == kStoreF32) FXP_GEMM_LAUNCH(kStoreF32);
     else FXP_GEMM_LAUNCH(kAtomicI32);
@@ -831,52 +940,16 @@ static int launch_dma(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t 
     return launch_status();
 }
 
-// sum of the split-K slices (int32, exact in any order) -> int32 or inverse-mapped fp32
-__global__ __launch_bounds__(256) void k_splitk_reduce(const int32_t* __restrict__ parts, int splits, int64_t stride,
-                                                       int M, int N, void* __restrict__ Cv, int64_t ldc, int fp32_out,
-                                                       const int32_t* __restrict__ eA, int bitsA,
-                                                       const int32_t* __restrict__ eB, int bitsB, uint32_t* __restrict__ amax) {
-    float m = 0.0f;
-    int E = 0;
-    if (fp32_out) E = lsb_exponent(eA[0], bitsA) + (eB ? lsb_exponent(eB[0], bitsB) : 0);
-    const int nvec = N >> 2;                      // the slices are dense M x N: rows start 16-byte aligned when N % 4 == 0
-    const bool vec = (N & 3) == 0 && (ldc & 3) == 0 && (reinterpret_cast<uintptr_t>(Cv) & 15u) == 0;
-    for (int r = blockIdx.y; r < M; r += gridDim.y) {
-        const int32_t* prow = parts + static_cast<int64_t>(r) * N;
-        int32_t* crow = static_cast<int32_t*>(Cv) + static_cast<int64_t>(r) * ldc;
-        if (vec) {
-            for (int i = blockIdx.x * 256 + threadIdx.x; i < nvec; i += gridDim.x * 256) {
-                int4 acc = make_int4(0, 0, 0, 0);
-#pragma unroll 8
-                for (int sidx = 0; sidx < splits; ++sidx) {
-                    const int4 v = reinterpret_cast<const int4*>(prow + sidx * stride)[i];
-                    acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
-                }
-                if (fp32_out) {
-                    float4 o;
-                    o.x = unmap_value(acc.x, E); o.y = unmap_value(acc.y, E);
-                    o.z = unmap_value(acc.z, E); o.w = unmap_value(acc.w, E);
-                    reinterpret_cast<float4*>(crow)[i] = o;
-                    m = fmaxf(fmaxf(m, fmaxf(fabsf(o.x), fabsf(o.y))), fmaxf(fabsf(o.z), fabsf(o.w)));
-                } else {
-                    reinterpret_cast<int4*>(crow)[i] = acc;
-                }
-            }
-        } else {
-            for (int i = blockIdx.x * 256 + threadIdx.x; i < N; i += gridDim.x * 256) {
-                int acc = 0;
-                for (int sidx = 0; sidx < splits; ++sidx) acc += prow[sidx * stride + i];
-                if (fp32_out) {
-                    const float o = unmap_value(acc, E);
-                    reinterpret_cast<float*>(crow)[i] = o;
-                    m = fmaxf(m, fabsf(o));
-                } else {
-                    crow[i] = acc;
-                }
-            }
-        }
-    }
-    if (fp32_out && amax != nullptr) publish_absmax(m, amax);
+__global__ __launch_bounds__(256) void k_splitk_reduce(ReduceRider r) { splitk_reduce_body(r, blockIdx.x, gridDim.x); }
+
+// workgroups a reduction wants: 16-byte pieces of the output over 256 threads, a few pieces each
+static unsigned reduce_blocks(int64_t M, int64_t N) {
+    return static_cast<unsigned>(std::max<int64_t>(1, std::min<int64_t>(1024, (M * N / 4 + 511) / 512)));
+}
+
+int splitk_reduce_launch(const ReduceRider& r, hipStream_t s) {
+    hipLaunchKernelGGL(k_splitk_reduce, dim3(r.blocks), dim3(256), 0, s, r);
+    return launch_status();
 }
 
 // How a product is cut up.  Depends on the shape only, so that workspace sizing and launch agree.
@@ -955,9 +1028,14 @@ int gemm_nt_batched_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int
 
 // amax (fp32_out only, may be null): FXP_ABSMAX_WORDS device words raised so that their maximum is at least the
 // IEEE bits of the largest |C| of this product.
+// ride (may be null): a pending reduction of another product; if this product is launched unsplit it takes the
+// reduction along (ride->blocks becomes 0), otherwise the caller still has to launch it.
+// defer (may be null): if this product is split along K into workspace slices, its reduction is not launched but
+// described in *defer (blocks != 0) for the caller to send along with a later launch or to launch by itself;
+// the slices in ws must stay untouched until then.
 int gemm_nt_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                    void* C, int64_t ldc, bool fp32_out, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB,
-                   void* ws, size_t ws_bytes, hipStream_t s, uint32_t* amax) {
+                   void* ws, size_t ws_bytes, hipStream_t s, uint32_t* amax, ReduceRider* ride, ReduceRider* defer) {
     if (M == 0 || N == 0) return FXP_OK;
     if (!fp32_out) amax = nullptr;
     uint32_t* amax1 = nullptr;      // the product kernel publishes the maximum itself only when it writes the final fp32
@@ -987,29 +1065,41 @@ int gemm_nt_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda
         if ((rc = launch_status())) return rc;
     }
     if (!dma)
-        rc = launch_cfg<128, 128, 64, 64, 64>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, vec, splits, eA, bitsA, eB, bitsB, s, split_stride, &slices, one, amax1);
+        rc = launch_cfg<128, 128, 64, 64, 64>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, vec, splits, eA, bitsA, eB, bitsB, s, split_stride, &slices, one, amax1, ride);
     else if (use256 && splits == 1 && stream_out && K % 128 == 0 && (K <= 256 || 4.0 * M * N < 128.0 * 1024 * 1024))
         // 64 KiB of LDS per workgroup keeps two resident per CU: one stores its tile while the other multiplies
         // (ResNet dX 25088 x 1152 x 128: 22.5 us against 27.3 with the 128 x 256 tile and 24.4 with the ring kernel;
         // ViT qkv forward 36.7 / 38.3 / 40.5; fc1 forward 48.1 / 46.9 / 54.7)
-        rc = launch_dma<128, 128, 128, 64, 64, 2>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, 1, eA, bitsA, eB, bitsB, s, 0, nullptr, one, amax1);
+        rc = launch_dma<128, 128, 128, 64, 64, 2>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, 1, eA, bitsA, eB, bitsB, s, 0, nullptr, one, amax1, ride);
     else if (use256 && splits == 1 && stream_out)
-        rc = launch_dma<128, 256, 64, 64, 64, 3>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, 1, eA, bitsA, eB, bitsB, s, 0, nullptr, one, amax1);
+        rc = launch_dma<128, 256, 64, 64, 64, 3>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, 1, eA, bitsA, eB, bitsB, s, 0, nullptr, one, amax1, ride);
     else if (use256 && K % 128 == 0 && splits == 1)
-        rc = launch_ring<64, 128>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, 1, eA, bitsA, eB, bitsB, s, 0, nullptr, one, amax1);
+        rc = launch_ring<64, 128>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, 1, eA, bitsA, eB, bitsB, s, 0, nullptr, one, amax1, ride);
     else if (use256)
-        rc = launch_dma<256, 256, 64, 64, 128, 4>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, splits, eA, bitsA, eB, bitsB, s, split_stride, &slices, one, amax1);
+        rc = launch_dma<256, 256, 64, 64, 128, 4>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, splits, eA, bitsA, eB, bitsB, s, split_stride, &slices, one, amax1, ride);
     else if (K % 128 == 0)
-        rc = launch_dma<128, 128, 128, 64, 32, 4>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, splits, eA, bitsA, eB, bitsB, s, split_stride, &slices, one, amax1);
+        rc = launch_dma<128, 128, 128, 64, 32, 4>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, splits, eA, bitsA, eB, bitsB, s, split_stride, &slices, one, amax1, ride);
     else
-        rc = launch_dma<128, 128, 64, 64, 64, 4>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, splits, eA, bitsA, eB, bitsB, s, split_stride, &slices, one, amax1);
+        rc = launch_dma<128, 128, 64, 64, 64, 4>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, splits, eA, bitsA, eB, bitsB, s, split_stride, &slices, one, amax1, ride);
     if (rc || splits == 1) return rc;
     if (to_ws) {
-        const dim3 rgrid(std::max(1, std::min(64, static_cast<int>((N / 4 + 255) / 256))),
-                         static_cast<unsigned>(std::min<int64_t>(M, 65535)));
-        hipLaunchKernelGGL(k_splitk_reduce, rgrid, dim3(256), 0, s, static_cast<const int32_t*>(ws), slices, M * N,
-                           static_cast<int>(M), static_cast<int>(N), C, ldc, fp32_out ? 1 : 0, eA, bitsA, eB, bitsB, amax);
-        return launch_status();
+        ReduceRider r;
+        r.parts = static_cast<const int32_t*>(ws);
+        r.splits = slices;
+        r.stride = M * N;
+        r.M = static_cast<int>(M);
+        r.N = static_cast<int>(N);
+        r.C = C;
+        r.ldc = ldc;
+        r.fp32_out = fp32_out ? 1 : 0;
+        r.eA = eA; r.bitsA = bitsA; r.eB = eB; r.bitsB = bitsB;
+        r.amax = amax;
+        r.blocks = reduce_blocks(M, N);
+        if (defer != nullptr) {
+            *defer = r;
+            return FXP_OK;
+        }
+        return splitk_reduce_launch(r, s);
     }
     if (!fp32_out) return rc;
     hipLaunchKernelGGL(k_unmap_rows, hgrid, dim3(256), 0, s, static_cast<int32_t*>(C), ldc, hr, hc, eA, bitsA, eB, bitsB, amax);
@@ -1021,26 +1111,34 @@ int gemm_nt_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda
 // multiple of 64 (the smallest K step), a product that plan_gemm would split along K or give 256 x 256 tiles.
 template <int BK, int WN>
 static int conv_gemm_launch_cfg(const ConvTaps& ct, int64_t K, int64_t M, int64_t Cout, const int8_t* Xq, const int8_t* Wq,
-                                float* Y, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB, hipStream_t s) {
+                                float* Y, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB, hipStream_t s,
+                                ReduceRider* ride) {
     constexpr int BM = 128, BN = 128, WM = 64, STAGES = 4;
     const int tiles_m = static_cast<int>((M + BM - 1) / BM), tiles_n = static_cast<int>((Cout + BN - 1) / BN);
-    const dim3 grid(static_cast<unsigned>(tiles_m) * tiles_n), block((BM / WM) * (BN / WN) * 64);
+    ReduceRider rider;
+    if (ride != nullptr && ride->blocks != 0) {
+        rider = *ride;
+        rider.tiles = static_cast<unsigned>(tiles_m) * tiles_n;
+        rider.front = rider.tiles >= 512;                       // several rounds of tiles: ride in the first one
+        ride->blocks = 0;                                       // taken
+    }
+    const dim3 grid(static_cast<unsigned>(tiles_m) * tiles_n + rider.blocks), block((BM / WM) * (BN / WN) * 64);
     hipLaunchKernelGGL((k_gemm_nt_dma<BM, BN, BK, WM, WN, STAGES, kStoreF32, true, true>), grid, block, 0, s, Xq, K, Wq, K,
                        static_cast<void*>(Y), Cout, static_cast<int>(M), static_cast<int>(Cout), static_cast<int>(K),
                        static_cast<int>(K), eA, bitsA, eB, bitsB, tiles_m, tiles_n, 8, int64_t{0}, int64_t{0}, int64_t{0},
-                       int64_t{0}, ct, static_cast<uint32_t*>(nullptr));
+                       int64_t{0}, ct, static_cast<uint32_t*>(nullptr), rider);
     return launch_status();
 }
 
 int conv_gemm_launch(const ConvTaps& ct, int KH, int64_t M, int64_t Cout, const int8_t* Xq, const int8_t* Wq, float* Y,
-                     const int32_t* eA, int bitsA, const int32_t* eB, int bitsB, hipStream_t s) {
+                     const int32_t* eA, int bitsA, const int32_t* eB, int bitsB, hipStream_t s, ReduceRider* ride) {
     const int64_t K = static_cast<int64_t>(KH) * ct.KW * ct.C;
     if (ct.C % 64 != 0 || !aligned(Xq, 16) || !aligned(Wq, 16) || M <= 0 || Cout <= 0) return kNotApplicable;
     const GemmPlan plan = plan_gemm(M, Cout, K);
     if (plan.splits != 1 || plan.use256) return kNotApplicable;
     // one K step = one run of channels of one filter tap: 128 channels (8 waves) where C allows, else 64 (4 waves)
-    if (ct.C % 128 == 0) return conv_gemm_launch_cfg<128, 32>(ct, K, M, Cout, Xq, Wq, Y, eA, bitsA, eB, bitsB, s);
-    return conv_gemm_launch_cfg<64, 64>(ct, K, M, Cout, Xq, Wq, Y, eA, bitsA, eB, bitsB, s);
+    if (ct.C % 128 == 0) return conv_gemm_launch_cfg<128, 32>(ct, K, M, Cout, Xq, Wq, Y, eA, bitsA, eB, bitsB, s, ride);
+    return conv_gemm_launch_cfg<64, 64>(ct, K, M, Cout, Xq, Wq, Y, eA, bitsA, eB, bitsB, s, ride);
 }
 
 static int check_gemm_args(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, int transA, const void* B,
@@ -1089,7 +1187,7 @@ static int gemm_any(int transA, int transB, int64_t M, int64_t N, int64_t K, con
     // what is left of the workspace serves the split-K slices (atomics are used if it is too small)
     const size_t used = static_cast<size_t>(w - static_cast<int8_t*>(ws));
     return gemm_nt_launch(M, N, K, A, lda, B, ldb, C, ldc, fp32_out, eA, bitsA, eB, bitsB, ws ? w : nullptr,
-                          ws_bytes > used ? ws_bytes - used : 0, s, amax);
+                          ws_bytes > used ? ws_bytes - used : 0, s, amax, nullptr, nullptr);
 }
 
 }  // namespace fxp

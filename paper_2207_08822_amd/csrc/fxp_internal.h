@@ -45,9 +45,37 @@ int gemm_nt_batched_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int
                            const int8_t* B, int64_t ldb, int64_t strideB, void* C, int64_t ldc, int64_t strideC,
                            int64_t batch, bool fp32_out, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB,
                            hipStream_t s);
+// The reduction that finishes a product split along K (sum of its int32 slices, inverse mapping), as a piece of
+// work that can ride in the launch of ANOTHER product: `blocks` workgroups of that launch's grid.x do it instead
+// of a tile.  A dependent launch costs about 4.5 us on this machine and the reduction is a few microseconds of
+// reading, so the backward pass sends the weight gradient's reduction along with the input-gradient product.
+// Where the product has several rounds of tiles the riders are its FIRST workgroups (they run beside the first
+// round; as the last ones they were a tail of their own: ResNet layer 0.116 -> 0.110 ms); where its tiles leave
+// CUs idle (150 tiles of 256 x 256 in the ViT layers) they are the LAST ones and run on the idle CUs at once - a
+// rider occupies a whole workgroup slot of the product's kernel, so in front they would hold the tiles back.
+// blocks = 0: nothing rides.
+struct ReduceRider {
+    const int32_t* parts = nullptr;
+    int splits = 0;
+    int64_t stride = 0;
+    int M = 0, N = 0;
+    void* C = nullptr;
+    int64_t ldc = 0;
+    int fp32_out = 0;
+    const int32_t* eA = nullptr;
+    int bitsA = 8;
+    const int32_t* eB = nullptr;
+    int bitsB = 8;
+    uint32_t* amax = nullptr;
+    unsigned blocks = 0;
+    unsigned tiles = 0;      // set by the launcher: workgroups of the host product
+    bool front = false;      // set by the launcher: riders before the tiles
+};
+
 int gemm_nt_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                    void* C, int64_t ldc, bool fp32_out, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB,
-                   void* ws, size_t ws_bytes, hipStream_t s, uint32_t* amax = nullptr);
+                   void* ws, size_t ws_bytes, hipStream_t s, uint32_t* amax = nullptr, ReduceRider* ride = nullptr,
+                   ReduceRider* defer = nullptr);
 size_t gemm_split_ws_bytes(int64_t M, int64_t N, int64_t K);
 // geometry of the patches an implicit-convolution GEMM reads: image H x W x C (channels-last), filter width
 // KW, stride, padding (rows / columns), output Ho x Wo
@@ -56,7 +84,8 @@ struct ConvTaps {
 };
 constexpr int kNotApplicable = 1;
 int conv_gemm_launch(const ConvTaps& ct, int KH, int64_t M, int64_t Cout, const int8_t* Xq, const int8_t* Wq, float* Y,
-                     const int32_t* eA, int bitsA, const int32_t* eB, int bitsB, hipStream_t s);
+                     const int32_t* eA, int bitsA, const int32_t* eB, int bitsB, hipStream_t s, ReduceRider* ride = nullptr);
+int splitk_reduce_launch(const ReduceRider& r, hipStream_t s);
 size_t gemm_ws_worst(int64_t M, int64_t N, int64_t K);
 int transpose_i8_launch(const int8_t* src, int64_t rows, int64_t cols, int64_t ld, int8_t* dst, hipStream_t s);
 

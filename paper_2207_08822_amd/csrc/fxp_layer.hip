@@ -96,12 +96,18 @@ extern "C" int fxp_linear_bwd(const float* dY, const fxp_saved* saved, int64_t M
         return rc;
     uint8_t* rest = static_cast<uint8_t*>(ws) + round_up(kScaleWsBytes, 256);
     const size_t rest_bytes = ws_bytes - round_up(kScaleWsBytes, 256);
-    if (dX && (rc = gemm_nt_launch(M, K, N, dYq, N, saved->Wq, N, dX, K, true, e_dY, bits, saved->eW, bits, rest,
-                                   rest_bytes, s)))
-        return rc;
+    // The weight gradient first: when it is split along K, the sum of its slices does not get a launch of its own
+    // but rides in the launch of the input-gradient product (whose last workgroups do it) - unless that product
+    // is split too and needs the slice area for itself.
+    ReduceRider pending;
+    const bool rides = dX != nullptr && gemm_split_ws_bytes(M, K, N) == 0;
     if (dW && (rc = gemm_nt_launch(K, N, M, saved->XqT, M, dYqT, M, dW, N, true, saved->eX, bits, e_dY, bits, rest,
-                                   rest_bytes, s)))
+                                   rest_bytes, s, nullptr, nullptr, rides ? &pending : nullptr)))
         return rc;
+    if (dX && (rc = gemm_nt_launch(M, K, N, dYq, N, saved->Wq, N, dX, K, true, e_dY, bits, saved->eW, bits, rest,
+                                   rest_bytes, s, nullptr, &pending, nullptr)))
+        return rc;
+    if (pending.blocks != 0) return splitk_reduce_launch(pending, s);      // nobody took it along
     return FXP_OK;
 }
 
