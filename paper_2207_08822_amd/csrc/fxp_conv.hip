@@ -96,6 +96,33 @@ __global__ __launch_bounds__(256) void k_flip_weights_i8(const int8_t* __restric
     flip_weights_body(Wq, g, WqF, blockIdx.x, gridDim.x);
 }
 
+// The launch that writes the transposed patches carries two more pieces of the backward pass that depend on
+// nothing it writes: its first side.blocks workgroups reduce the block maxima of the incoming gradient (the
+// scale reduction that would otherwise be a launch of its own, and the first one of the pass), and the workgroups
+// beyond the tile_blocks tiles flip the weights for the input-gradient convolution (Wq -> WqF; possibly none).
+struct SideScale {
+    const uint32_t* x = nullptr;      // the gradient, as bit patterns
+    size_t n = 0;
+    uint32_t* partials = nullptr;     // side.blocks block maxima
+    unsigned blocks = 0;
+};
+
+// true: this workgroup had one of the side roles and is done
+__device__ inline bool side_roles(const SideScale& side, unsigned tile_blocks, const int8_t* __restrict__ Wq, const ConvGeo& g,
+                                  int8_t* __restrict__ WqF) {
+    if (blockIdx.x < side.blocks) {
+        __shared__ uint32_t red[4];
+        absmax_body(side.x, side.n, side.partials, blockIdx.x, side.blocks, red);
+        return true;
+    }
+    const unsigned b = blockIdx.x - side.blocks;
+    if (b >= tile_blocks) {
+        flip_weights_body(Wq, g, WqF, b - tile_blocks, gridDim.x - side.blocks - tile_blocks);
+        return true;
+    }
+    return false;
+}
+
 // colT[(tap*C + c)][m] for a tile of 128 consecutive m x TCH = 64 channels of one tap (128 bytes of a colT row: whole
 // cache lines; 14.0 -> 12.0 us on the ResNet layer against 64-byte pieces; 128 channels per tile, whole lines on
 // the read side too, or 256 output pixels changed nothing or lost).  Each thread reads
@@ -107,17 +134,14 @@ constexpr int kColTileM = 128;
 template <int TCH>
 __global__ __launch_bounds__(256) void k_im2col_t_i8(const int8_t* __restrict__ Xq, ConvGeo g, int8_t* __restrict__ colT,
                                                      int tiles_m, int tiles_c, unsigned tile_blocks,
-                                                     const int8_t* __restrict__ Wq, int8_t* __restrict__ WqF) {
-    if (blockIdx.x >= tile_blocks) {
-        flip_weights_body(Wq, g, WqF, blockIdx.x - tile_blocks, gridDim.x - tile_blocks);
-        return;
-    }
+                                                     const int8_t* __restrict__ Wq, int8_t* __restrict__ WqF, SideScale side) {
+    if (side_roles(side, tile_blocks, Wq, g, WqF)) return;
     constexpr int TS = kColTileM / 4 + 1;                        // dwords per staged channel (+ 1 pad)
     constexpr int CG = TCH / 4, MG = 256 / CG;                   // channel groups x row groups per round
     constexpr int ROUNDS = kColTileM / 4 / MG;                   // groups of 4 rows per thread
     __shared__ uint32_t t[TCH * TS];                             // [channel][32 dwords of m]
     __shared__ PatchRow rows[kColTileM];
-    int b = blockIdx.x;
+    int b = static_cast<int>(blockIdx.x - side.blocks);
     const int tc = b % tiles_c; b /= tiles_c;
     const int tm = b % tiles_m;
     const int tap = b / tiles_m;
@@ -169,13 +193,10 @@ __global__ __launch_bounds__(256) void k_im2col_t_i8(const int8_t* __restrict__ 
 // same, one byte at a time, for C % 4 != 0
 __global__ __launch_bounds__(256) void k_im2col_t_i8_bytes(const int8_t* __restrict__ Xq, ConvGeo g, int8_t* __restrict__ colT,
                                                            int tiles_m, int tiles_c, unsigned tile_blocks,
-                                                           const int8_t* __restrict__ Wq, int8_t* __restrict__ WqF) {
-    if (blockIdx.x >= tile_blocks) {
-        flip_weights_body(Wq, g, WqF, blockIdx.x - tile_blocks, gridDim.x - tile_blocks);
-        return;
-    }
+                                                           const int8_t* __restrict__ Wq, int8_t* __restrict__ WqF, SideScale side) {
+    if (side_roles(side, tile_blocks, Wq, g, WqF)) return;
     __shared__ int8_t t[64][65];
-    int b = blockIdx.x;
+    int b = static_cast<int>(blockIdx.x - side.blocks);
     const int tc = b % tiles_c; b /= tiles_c;
     const int tm = b % tiles_m;
     const int tap = b / tiles_m;
@@ -371,9 +392,18 @@ extern "C" int fxp_conv2d_bwd(const float* dY, const fxp_conv_saved* saved, cons
     uint8_t* area = w8 + round_up(kScaleWsBytes, 256);
     const size_t area_bytes = ws_bytes - round_up(kScaleWsBytes, 256);
     const int64_t M = g.M(), K = g.K();
-    if ((rc = scale_and_map(dY, M, g.Cout, e_dY, dYq, dYqT, seed, (step << 8) | FXP_TAG_DY, rounding, bits,
-                            reinterpret_cast<uint32_t*>(w8), s)))
+    // With a weight gradient to compute, the block maxima of dY are reduced by the launch that writes the
+    // transposed patches (below) and the map of dY follows it; otherwise the usual pair of launches.
+    SideScale side;
+    if (dW) {
+        side.x = reinterpret_cast<const uint32_t*>(dY);
+        side.n = static_cast<size_t>(M) * static_cast<size_t>(g.Cout);
+        side.partials = reinterpret_cast<uint32_t*>(w8);
+        side.blocks = static_cast<unsigned>(scale_partial_count(side.n));
+    } else if ((rc = scale_and_map(dY, M, g.Cout, e_dY, dYq, dYqT, seed, (step << 8) | FXP_TAG_DY, rounding, bits,
+                                   reinterpret_cast<uint32_t*>(w8), s))) {
         return rc;
+    }
     const bool need_flip = dX && dx_as_conv(g);
     ReduceRider pending;                 // the weight gradient's split-K reduction while it waits for a launch to ride in
     if (need_flip && !dW) {
@@ -390,15 +420,19 @@ extern "C" int fxp_conv2d_bwd(const float* dY, const fxp_conv_saved* saved, cons
         if (blocks >= (int64_t{1} << 31)) return FXP_ERR_DIMS;
         // the flipped weights of the input-gradient convolution ride along in the same launch
         const unsigned flip_blocks = need_flip ? grid_for(static_cast<int64_t>(g.Cout) * K) : 0u;
-        if (blocks + flip_blocks >= (int64_t{1} << 31)) return FXP_ERR_DIMS;
-        const dim3 tgrid(static_cast<unsigned>(blocks) + flip_blocks);
+        if (blocks + flip_blocks + side.blocks >= (int64_t{1} << 31)) return FXP_ERR_DIMS;
+        const dim3 tgrid(side.blocks + static_cast<unsigned>(blocks) + flip_blocks);
         if (quads)
             hipLaunchKernelGGL(k_im2col_t_i8<64>, tgrid, dim3(256), 0, s, saved->Xq, g, colT, tiles_m, tiles_c,
-                               static_cast<unsigned>(blocks), saved->Wq, saved->WqF);
+                               static_cast<unsigned>(blocks), saved->Wq, saved->WqF, side);
         else
             hipLaunchKernelGGL(k_im2col_t_i8_bytes, tgrid, dim3(256), 0, s, saved->Xq, g, colT, tiles_m, tiles_c,
-                               static_cast<unsigned>(blocks), saved->Wq, saved->WqF);
+                               static_cast<unsigned>(blocks), saved->Wq, saved->WqF, side);
         if ((rc = launch_status())) return rc;
+        // dY: the map kernel finishes the reduction from the block maxima just written
+        const MapTensor tdY{dY, M, g.Cout, nullptr, side.partials, static_cast<int>(side.blocks), e_dY, dYq, dYqT,
+                            (step << 8) | FXP_TAG_DY};
+        if ((rc = map_launch(tdY, seed, rounding, bits, s))) return rc;
         const size_t used = round_up(static_cast<size_t>(K) * M, 256);
         // dW[Cout, K] = dYqT[Cout, M] * colT[K, M]^T, contraction over all output pixels
         // (split along K: the sum of its slices rides in the launch of the input-gradient convolution when that

@@ -24,6 +24,7 @@ int scale_partials(const float* x, size_t n, uint32_t* partials, int* n_partials
 int scale_partials2(const float* x0, size_t n0, uint32_t* partials0, int* n_partials0, const float* x1, size_t n1,
                     uint32_t* partials1, int* n_partials1, hipStream_t s);
 int scale_finish(const uint32_t* partials, int n_partials, int32_t* e_max, hipStream_t s);
+int scale_partial_count(size_t n);     // block maxima a reduction over n elements leaves (<= kMaxPartials)
 
 // One tensor to map: x[rows, cols] fp32 -> q (row-major) and / or qT (transposed), either may be null.  The
 // scale comes from e_in (device) or, when partials is given, from the block maxima of a scale reduction, in

@@ -30,13 +30,13 @@ __global__ __launch_bounds__(kScaleThreads) void k_absmax_finish(const uint32_t*
 }
 
 // 16K elements or more per block (the map kernel re-reads every block maximum), at most kMaxPartials
-static int partial_count(size_t n) {
+int scale_partial_count(size_t n) {
     const size_t want = (n + 16383) / 16384;
     return static_cast<int>(want < 1 ? 1 : (want > kMaxPartials ? kMaxPartials : want));
 }
 
 int scale_partials(const float* x, size_t n, uint32_t* partials, int* n_partials, hipStream_t s) {
-    const int grid = partial_count(n);
+    const int grid = scale_partial_count(n);
     hipLaunchKernelGGL(k_absmax_partials, dim3(grid), dim3(kScaleThreads), 0, s, reinterpret_cast<const uint32_t*>(x), n,
                        partials, static_cast<unsigned>(grid), static_cast<const uint32_t*>(nullptr), size_t{0},
                        static_cast<uint32_t*>(nullptr));
@@ -46,7 +46,7 @@ int scale_partials(const float* x, size_t n, uint32_t* partials, int* n_partials
 
 int scale_partials2(const float* x0, size_t n0, uint32_t* partials0, int* n_partials0, const float* x1, size_t n1,
                     uint32_t* partials1, int* n_partials1, hipStream_t s) {
-    const int g0 = partial_count(n0), g1 = partial_count(n1);
+    const int g0 = scale_partial_count(n0), g1 = scale_partial_count(n1);
     hipLaunchKernelGGL(k_absmax_partials, dim3(g0 + g1), dim3(kScaleThreads), 0, s, reinterpret_cast<const uint32_t*>(x0),
                        n0, partials0, static_cast<unsigned>(g0), reinterpret_cast<const uint32_t*>(x1), n1, partials1);
     *n_partials0 = g0;
