@@ -64,9 +64,10 @@ __device__ inline int swizzle_of_row(int row) {
 
 // The wave's largest output magnitude -> one of the FXP_ABSMAX_WORDS words at amax (IEEE bits of a non-negative
 // float order like unsigned integers): one device-scope atomic per wave, without a returned value and with no
-// load before it - anything a wave has to WAIT for behind its stores keeps it alive until they have drained, which
-// is exactly the overlap the output-bound products live on (a look at the word first, to skip the atomic, cost
-// them a third of their time); consecutive waves use words in different cache lines.
+// load before it - vector memory operations complete in order, so anything a wave has to WAIT for behind its
+// stores (a look at the word first, to skip the atomic) keeps it alive until they have drained, and the
+// output-bound products live on waves ending while their stores are still in flight; consecutive waves use
+// words in different cache lines.
 __device__ inline void publish_absmax(float m, uint32_t* amax) {
     const uint32_t b = wave_max(__float_as_uint(m));
     // (block and thread indices only: the launch dimensions would be LOADED, and a wave that waits for a load
