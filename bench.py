@@ -128,7 +128,7 @@ def bench_conv(args, torch, fxp, synth, dev):
                            "transposed int8 patches + GEMM for the weight gradient",
                    "rounding": "stochastic (Philox-4x32-10)", "bits": args.bits},
         "roofline": dict(bound="hbm", achieved=round(gbs, 1), peak=PEAK_HBM_GBS, unit="GB/s",
-                         frac=round(gbs / PEAK_HBM_GBS, 4), kernel="whole step (9 kernels, all HBM-bound)",
+                         frac=round(gbs / PEAK_HBM_GBS, 4), kernel="whole step (7 launches, all HBM- or launch-bound)",
                          algorithmic_per_launch=step_bytes, traffic=None),
         "cpu_baseline": cpu,
     }))
