@@ -80,14 +80,15 @@ __device__ inline void publish_absmax(float m, uint32_t* amax) {
 // of the wave's tile), as inverse-mapped fp32 (non-temporal: the output is not read again here), as int32, or
 // added into int32 with atomics.  Accumulator register r of lane l is row 8 * (r / 4) + 4 * (l / 32) + r % 4,
 // column l % 32 of its fragment.  AMAX: returns the largest magnitude this lane stored.
-// GUARD = false: the wave's tile lies inside C and 2^E is a normal float - no bounds tests, one convert and one
-// multiply per value, row addresses a scalar multiple of ldc away from the lane's base.  The output-bound
-// products spend a fifth of their time issuing this loop, so the tests are hoisted out of it.
-template <int FM, int FN, int MODE, bool AMAX, bool GUARD>
+// GUARD = false: the wave's tile lies inside C - no bounds tests, row addresses a scalar multiple of ldc away from
+// the lane's base.  PLAIN: 2^E is a normal float (or the output is int32) - one convert and one multiply per
+// value.  The output-bound products spend a fifth of their time issuing this loop, so both tests are made once
+// per wave, outside it.
+template <int FM, int FN, int MODE, bool AMAX, bool GUARD, bool PLAIN>
 __device__ inline float store_loop(const v16i (&acc)[FM][FN], void* __restrict__ Cv, int64_t ldc, int M, int N, int row0,
                                    int col0, int fhalf, int frow, int E) {
     float m = 0.0f;
-    const float unit = __uint_as_float(static_cast<uint32_t>(GUARD ? 127 : E + 127) << 23);
+    const float unit = __uint_as_float(static_cast<uint32_t>(PLAIN ? E + 127 : 127) << 23);
     const int64_t base = static_cast<int64_t>(row0 + 4 * fhalf) * ldc + col0 + frow;
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
@@ -101,7 +102,7 @@ __device__ inline float store_loop(const v16i (&acc)[FM][FN], void* __restrict__
                 if (GUARD && col0 + 32 * j + frow >= N) continue;
                 const int64_t off = off_row + 32 * j;
                 if (MODE == kStoreF32) {
-                    const float v = GUARD ? unmap_value(acc[i][j][r], E) : static_cast<float>(acc[i][j][r]) * unit;
+                    const float v = PLAIN ? static_cast<float>(acc[i][j][r]) * unit : unmap_value(acc[i][j][r], E);
                     __builtin_nontemporal_store(v, static_cast<float*>(Cv) + off);
                     if (AMAX) m = fmaxf(m, fabsf(v));
                 } else if (MODE == kStoreI32) {
@@ -138,10 +139,11 @@ __device__ inline float store_fragments(const v16i (&acc)[FM][FN], void* __restr
             const float unit = __uint_as_float(static_cast<uint32_t>(E + 127) << 23);
             m = fmaxf(static_cast<float>(hi) * unit, -(static_cast<float>(lo) * unit));
         }
-        store_loop<FM, FN, MODE, false, false>(acc, Cv, ldc, M, N, row0, col0, fhalf, frow, E);
+        store_loop<FM, FN, MODE, false, false, true>(acc, Cv, ldc, M, N, row0, col0, fhalf, frow, E);
         return m;
     }
-    return store_loop<FM, FN, MODE, AMAX, true>(acc, Cv, ldc, M, N, row0, col0, fhalf, frow, E);
+    if (plain) return store_loop<FM, FN, MODE, AMAX, true, true>(acc, Cv, ldc, M, N, row0, col0, fhalf, frow, E);
+    return store_loop<FM, FN, MODE, AMAX, true, false>(acc, Cv, ldc, M, N, row0, col0, fhalf, frow, E);
 }
 
 // Sum of the split-K slices of a product (int32, exact in any order) -> int32 or inverse-mapped fp32, by workgroup
