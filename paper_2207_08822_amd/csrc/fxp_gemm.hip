@@ -945,9 +945,10 @@ static int launch_dma(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t 
 
 __global__ __launch_bounds__(256) void k_splitk_reduce(ReduceRider r) { splitk_reduce_body(r, blockIdx.x, gridDim.x); }
 
-// workgroups a reduction wants: 16-byte pieces of the output over 256 threads, a few pieces each
+// workgroups a reduction wants: one 16-byte piece of the output per thread (its loads over the slices are
+// independent of each other), 256 threads per workgroup, at most 2048 workgroups
 static unsigned reduce_blocks(int64_t M, int64_t N) {
-    return static_cast<unsigned>(std::max<int64_t>(1, std::min<int64_t>(1024, (M * N / 4 + 511) / 512)));
+    return static_cast<unsigned>(std::max<int64_t>(1, std::min<int64_t>(2048, (M * N / 4 + 255) / 256)));
 }
 
 int splitk_reduce_launch(const ReduceRider& r, hipStream_t s) {
@@ -959,6 +960,7 @@ int splitk_reduce_launch(const ReduceRider& r, hipStream_t s) {
 struct GemmPlan {
     bool use256;   // 256 x 256 tiles, else 128 x 128
     int splits;    // slices of the contraction (grid.y)
+    bool tall;     // split products only: 128 x 256 tiles (use256 is false then)
 };
 
 static GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K) {
@@ -966,12 +968,22 @@ static GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K) {
     const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
     const int64_t t128 = ((M + 127) / 128) * ((N + 127) / 128);
     const bool wide = M >= 256 && N >= 256;
-    GemmPlan p{wide && t256 >= 96, 1};
+    GemmPlan p{wide && t256 >= 96, 1, false};
     if (K >= 2048 && t256 < 64) {
         // small output, long contraction (a weight gradient): fill the chip along K, slices of 1024 or more
-        p.use256 = wide && t256 >= 16;
-        const int64_t tiles = p.use256 ? t256 : t128;
-        p.splits = static_cast<int>(std::max<int64_t>(1, std::min<int64_t>((num_cu + tiles / 2) / tiles, K / 1024)));
+        if (wide && t256 >= 16) {
+            // 128 x 256 tiles, about one workgroup per CU: measured on the ViT weight gradients (contraction 12608)
+            // 768 x 2304: 30.8 us (4 slices) against 31.9 with 256 x 256 tiles and 7 slices; 768 x 3072: 39.0 (3)
+            // against 39.5 (7) - and fewer slices to write and to sum afterwards.  Smaller outputs (768 x 768) stay
+            // with 128 x 128 tiles: 19.6 us with the sum of their 7 slices against 22.0 (12 slices).
+            const int64_t tiles = ((M + 127) / 128) * ((N + 255) / 256);
+            p.use256 = false;
+            p.tall = true;
+            p.splits = static_cast<int>(std::max<int64_t>(1, std::min<int64_t>(num_cu / tiles, K / 1024)));
+            return p;
+        }
+        p.use256 = false;
+        p.splits = static_cast<int>(std::max<int64_t>(1, std::min<int64_t>((num_cu + t128 / 2) / t128, K / 1024)));
     }
     return p;
 }
@@ -1078,6 +1090,8 @@ int gemm_nt_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda
         rc = launch_dma<128, 256, 64, 64, 64, 3>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, 1, eA, bitsA, eB, bitsB, s, 0, nullptr, one, amax1, ride);
     else if (use256 && K % 128 == 0 && splits == 1)
         rc = launch_ring<64, 128>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, 1, eA, bitsA, eB, bitsB, s, 0, nullptr, one, amax1, ride);
+    else if (plan.tall)
+        rc = launch_dma<128, 256, 64, 64, 64, 3>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, splits, eA, bitsA, eB, bitsB, s, split_stride, &slices, one, amax1, ride);
     else if (use256)
         rc = launch_dma<256, 256, 64, 64, 128, 4>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, splits, eA, bitsA, eB, bitsB, s, split_stride, &slices, one, amax1, ride);
     else if (K % 128 == 0)
