@@ -139,12 +139,15 @@ __device__ inline void absmax_body(const uint32_t* __restrict__ x, size_t n, uin
     const uint4* xv = reinterpret_cast<const uint4*>(x + head);
     const size_t tid = static_cast<size_t>(bid) * kScaleThreads + threadIdx.x;
     const size_t stride = static_cast<size_t>(nblocks) * kScaleThreads;
+    // back to front: the map kernel that follows reads front to back, and what the last-level cache still
+    // holds of a tensor near its size is what was read last here
+    const uint4* xe = xv + nvec - 1;
     size_t i = tid;
     for (; i + 3 * stride < nvec; i += 4 * stride) {
-        const uint4 a = xv[i], b = xv[i + stride], c = xv[i + 2 * stride], d = xv[i + 3 * stride];
+        const uint4 a = *(xe - i), b = *(xe - (i + stride)), c = *(xe - (i + 2 * stride)), d = *(xe - (i + 3 * stride));
         m = max(max(m, absmax4(a)), max(absmax4(b), max(absmax4(c), absmax4(d))));
     }
-    for (; i < nvec; i += stride) m = max(m, absmax4(xv[i]));
+    for (; i < nvec; i += stride) m = max(m, absmax4(*(xe - i)));
     if (bid == 0) {
         if (threadIdx.x < head) m = max(m, x[threadIdx.x] & kAbs);
         const size_t tail0 = head + (nvec << 2);
