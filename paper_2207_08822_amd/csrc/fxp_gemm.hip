@@ -8,15 +8,19 @@
 // consecutive contraction bytes of one row (A) or one column (B); integer addition is
 // order-free, so only "same bytes on both sides" matters for the contraction index.
 //
-//   * block tile BM x BN x BK through LDS, double-buffered, global loads for step k+1
-//     issued before the MFMAs of step k (register staging), one barrier per step;
+//   * three kernels share the tile scheme and the epilogue: k_gemm_nt stages tiles through registers (two LDS
+//     buffers, any alignment and leading dimension: the fallback), k_gemm_nt_dma loads global -> LDS directly in a
+//     multi-stage pipeline (the workhorse for every tile shape but the largest), k_gemm_nt_ring keeps a five-slot
+//     ring of 256 x 256 x 128 tiles for the MFMA-bound shapes;
 //   * LDS rows are BK bytes; 16-byte pieces are XOR-swizzled by the row so that the
 //     64-lane ds_read_b128 of a fragment (32 rows x 2 pieces) spreads over all banks;
 //   * accumulator lanes run along N: each store instruction writes 128-byte runs;
 //   * workgroups are renumbered so that each XCD (own L2) works on a compact patch of
 //     tiles instead of every 8th tile;
-//   * long-contraction / small-output shapes split K across grid.y and add int32
-//     partial sums with atomics (exact: integer addition is associative).
+//   * long-contraction / small-output shapes split K across grid.y: every slice stores its int32 tile into a
+//     workspace slice and a reduction (its own launch, or riding in the next product's) sums them and applies the
+//     inverse mapping; without workspace the slices add into C with int32 atomics (exact either way: integer
+//     addition is associative).
 // Roofline: MFMA-bound when 2MNK / (MK + NK + 4MN bytes) is above ~630 ops/B, else HBM.
 #include <algorithm>
 #include <type_traits>
@@ -348,6 +352,10 @@ __device__ inline void wait_loads_and_lds() {
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(VM));
 }
 
+// 256 zero bytes: where the patch rows of an implicit convolution read their padding from, and a partial last K step
+// the pieces beyond the end of the contraction
+__device__ __attribute__((aligned(256))) const uint8_t g_zero_page[256] = {0};
+
 // Same product, fast path: K a multiple of BK, operands 16-byte aligned.  Global loads go
 // straight into LDS (global_load_lds_dwordx4: each wave fills one contiguous 1 KiB region
 // per instruction, no register staging, no ds_write), STAGES buffers deep, so loads for
@@ -356,9 +364,7 @@ __device__ inline void wait_loads_and_lds() {
 // that belongs in slot p.  One s_barrier per step, no fence: the only cross-wave traffic
 // is LDS written by the loads (waited for with vmcnt before the barrier) and read by
 // ds_read (waited for with lgkmcnt before the next barrier lets the buffer be refilled).
-// 256 zero bytes: where the patch rows of an implicit convolution read their padding from
-__device__ __attribute__((aligned(256))) const uint8_t g_zero_page[256] = {0};
-
+//
 // CONV: the A operand is not a stored matrix but the patch matrix of a channels-last int8 image tensor
 // (A points at X[N,H,W,C]; row m is output pixel m, contraction index (kh*KW + kw)*C + c): the loader
 // works out, per K step, which input pixel a row reads (one tap of the filter, since C % BK == 0) and takes
@@ -993,19 +999,7 @@ size_t gemm_split_ws_bytes(int64_t M, int64_t N, int64_t K) {
     return p.splits > 1 ? round_up(static_cast<size_t>(p.splits) * M * N * sizeof(int32_t), 256) : 0;
 }
 
-// C = A[M,K] * B[N,K]^T.  fp32_out: C receives the inverse-mapped fp32 values (eA, eB on
-// the device), else the int32 sums.  C is overwritten in both cases.
-//
-// Kernel choice (measured on MI355X with mapped Gaussian operands):
-//   * operands 16-byte aligned and K a multiple of 64 -> direct-to-LDS kernels, else the
-//     register-staged 128 x 128 x 64 kernel with its element-wise loader;
-//   * enough 256 x 256 tiles to fill the chip -> the ring kernel (K % 128 == 0) or the
-//     four-stage 256 x 256 x 64 kernel; otherwise 128 x 128 tiles;
-//   * long contraction and a small output (the weight gradient) -> split K over grid.y.
-//     With workspace every slice stores its own int32 matrix and one pass sums the slices
-//     and applies the inverse mapping; without it the slices add into the zeroed output
-//     with int32 atomics (device-scope atomics are served at the memory side on this
-//     multi-die part, about 4x slower) and a pass converts in place.  Both are exact.
+// `batch` products of one shape in one launch (grid.z), never split along K.
 int gemm_nt_batched_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, int64_t strideA,
                            const int8_t* B, int64_t ldb, int64_t strideB, void* C, int64_t ldc, int64_t strideC,
                            int64_t batch, bool fp32_out, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB,
@@ -1041,6 +1035,22 @@ int gemm_nt_batched_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int
 #undef FXP_BATCHED_TAIL
 }
 
+// C = A[M,K] * B[N,K]^T.  fp32_out: C receives the inverse-mapped fp32 values (eA, eB on
+// the device), else the int32 sums.  C is overwritten in both cases.
+//
+// Kernel choice (measured on MI355X with mapped Gaussian operands):
+//   * operands 16-byte aligned and K a multiple of 64 -> direct-to-LDS kernels, else the
+//     register-staged 128 x 128 x 64 kernel with its element-wise loader;
+//   * enough 256 x 256 tiles to fill the chip -> the ring kernel (K % 128 == 0) or the
+//     four-stage 256 x 256 x 64 kernel; otherwise 128 x 128 tiles;
+//   * output-bound products (below the ridge, wide and large output or a very short contraction) -> 128-row tiles
+//     of 64 or 96 KiB of LDS, so that two workgroups are resident per CU and one stores while the other multiplies;
+//   * long contraction and a small output (the weight gradient) -> split K over grid.y.
+//     With workspace every slice stores its own int32 matrix and one pass sums the slices
+//     and applies the inverse mapping; without it the slices add into the zeroed output
+//     with int32 atomics (device-scope atomics are served at the memory side on this
+//     multi-die part, about 4x slower) and a pass converts in place.  Both are exact.
+//
 // amax (fp32_out only, may be null): FXP_ABSMAX_WORDS device words raised so that their maximum is at least the
 // IEEE bits of the largest |C| of this product.
 // ride (may be null): a pending reduction of another product; if this product is launched unsplit it takes the
