@@ -126,8 +126,11 @@ __device__ inline bool side_roles(const SideScale& side, unsigned tile_blocks, c
 // colT[(tap*C + c)][m] for a tile of 128 consecutive m x TCH = 64 channels of one tap (128 bytes of a colT row: whole
 // cache lines; 14.0 -> 12.0 us on the ResNet layer against 64-byte pieces; 128 channels per tile, whole lines on
 // the read side too, or 256 output pixels changed nothing or lost).  Each thread reads
-// 4 (m) x 4 (c) blocks as four dwords each, transposes them in registers, parks the "4 consecutive m of one
+// 4 (m) x 4 (c) blocks as four dwords each, transposes them in registers (byte permutes), parks the "4 consecutive m of one
 // channel" dwords in LDS and the block then writes 16-byte pieces along m.  Needs C % 4 == 0.
+// A workgroup walks the KW taps of one filter row for its tile (the rows' patch coordinates are worked out once, and
+// the loads of the next tap are in flight while this one is written out: 0.0645 -> 0.0633 ms per layer step on the
+// ResNet layer; all KH * KW taps per workgroup leave too few workgroups: 0.071 ms).
 // Workgroups beyond the tile_blocks tiles flip the weights for the input-gradient convolution (Wq -> WqF;
 // flip_blocks of them, possibly 0): two independent pieces of the backward pass in one launch.
 constexpr int kColTileM = 128;
@@ -144,49 +147,57 @@ __global__ __launch_bounds__(256) void k_im2col_t_i8(const int8_t* __restrict__ 
     int b = static_cast<int>(blockIdx.x - side.blocks);
     const int tc = b % tiles_c; b /= tiles_c;
     const int tm = b % tiles_m;
-    const int tap = b / tiles_m;
-    const int kh = tap / g.KW, kw = tap - kh * g.KW;
+    const int kh = b / tiles_m;                                  // one filter row per workgroup, its KW taps in turn
     const int64_t m0 = static_cast<int64_t>(tm) * kColTileM, M = g.M();
     const int c0 = tc * TCH;
     const int cg = threadIdx.x % CG, mg = threadIdx.x / CG;
     if (threadIdx.x < kColTileM && m0 + threadIdx.x < M) rows[threadIdx.x] = patch_row(g, static_cast<uint32_t>(m0) + threadIdx.x);
     __syncthreads();
-    const int64_t tap_off = (static_cast<int64_t>(kh) * g.W + kw) * g.C + c0 + 4 * cg;
     uint32_t v[ROUNDS][4];
+    auto load_tap = [&](int kw) {
+        const int64_t tap_off = (static_cast<int64_t>(kh) * g.W + kw) * g.C + c0 + 4 * cg;
 #pragma unroll
-    for (int r = 0; r < ROUNDS; ++r) {
-        const int rg = mg + MG * r;                              // group of 4 rows
+        for (int r = 0; r < ROUNDS; ++r) {
+            const int rg = mg + MG * r;                          // group of 4 rows
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            v[r][k] = 0;
-            if (m0 + 4 * rg + k < M && c0 + 4 * cg < g.C) {
-                const PatchRow pr = rows[4 * rg + k];
-                const int h = pr.h0 + kh, w = pr.w0 + kw;
-                if (h >= 0 && h < g.H && w >= 0 && w < g.W) v[r][k] = *reinterpret_cast<const uint32_t*>(Xq + pr.base + tap_off);
+            for (int k = 0; k < 4; ++k) {
+                v[r][k] = 0;
+                if (m0 + 4 * rg + k < M && c0 + 4 * cg < g.C) {
+                    const PatchRow pr = rows[4 * rg + k];
+                    const int h = pr.h0 + kh, w = pr.w0 + kw;
+                    if (h >= 0 && h < g.H && w >= 0 && w < g.W) v[r][k] = *reinterpret_cast<const uint32_t*>(Xq + pr.base + tap_off);
+                }
             }
         }
-    }
+    };
+    load_tap(0);
+    for (int kw = 0; kw < g.KW; ++kw) {
 #pragma unroll
-    for (int r = 0; r < ROUNDS; ++r)
+        for (int r = 0; r < ROUNDS; ++r) {
+            uint32_t col[4];                                     // col[c] = 4 consecutive m of channel 4 * cg + c
+            transpose4x4(v[r], col);
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
-            t[(4 * cg + c) * TS + mg + MG * r] = ((v[r][0] >> (8 * c)) & 0xffu) | (((v[r][1] >> (8 * c)) & 0xffu) << 8) |
-                                                 (((v[r][2] >> (8 * c)) & 0xffu) << 16) | (((v[r][3] >> (8 * c)) & 0xffu) << 24);
-    __syncthreads();
-    constexpr int PIECES = kColTileM / 16;                       // 16-byte pieces of a staged channel
-#pragma unroll
-    for (int it = 0; it < TCH * PIECES / 256; ++it) {
-        const int id = it * 256 + threadIdx.x;
-        const int c = id / PIECES, ch = id % PIECES;             // channel row, 16-byte piece along m
-        if (c0 + c >= g.C) continue;
-        int8_t* dst = colT + (static_cast<int64_t>(tap) * g.C + c0 + c) * M + m0 + 16 * ch;
-        const uint32_t* src = t + c * TS + 4 * ch;
-        if ((M & 15) == 0 && m0 + 16 * ch + 16 <= M) {
-            *reinterpret_cast<uint4*>(dst) = make_uint4(src[0], src[1], src[2], src[3]);
-        } else {
-            for (int j = 0; j < 16; ++j)
-                if (m0 + 16 * ch + j < M) dst[j] = static_cast<int8_t>((src[j >> 2] >> (8 * (j & 3))) & 0xffu);
+            for (int c = 0; c < 4; ++c) t[(4 * cg + c) * TS + mg + MG * r] = col[c];
         }
+        __syncthreads();
+        if (kw + 1 < g.KW) load_tap(kw + 1);                     // in flight while this tap is written out
+        const int tap = kh * g.KW + kw;
+        constexpr int PIECES = kColTileM / 16;                   // 16-byte pieces of a staged channel
+#pragma unroll
+        for (int it = 0; it < TCH * PIECES / 256; ++it) {
+            const int id = it * 256 + threadIdx.x;
+            const int c = id / PIECES, ch = id % PIECES;         // channel row, 16-byte piece along m
+            if (c0 + c >= g.C) continue;
+            int8_t* dst = colT + (static_cast<int64_t>(tap) * g.C + c0 + c) * M + m0 + 16 * ch;
+            const uint32_t* src = t + c * TS + 4 * ch;
+            if ((M & 15) == 0 && m0 + 16 * ch + 16 <= M) {
+                *reinterpret_cast<uint4*>(dst) = make_uint4(src[0], src[1], src[2], src[3]);
+            } else {
+                for (int j = 0; j < 16; ++j)
+                    if (m0 + 16 * ch + j < M) dst[j] = static_cast<int8_t>((src[j >> 2] >> (8 * (j & 3))) & 0xffu);
+            }
+        }
+        __syncthreads();                                         // the staging area is free for the next tap
     }
 }
 
@@ -416,7 +427,8 @@ extern "C" int fxp_conv2d_bwd(const float* dY, const fxp_conv_saved* saved, cons
         const bool quads = g.C % 4 == 0;                        // the dword kernel takes 128 output pixels per tile
         const int tch = 64;                                     // channels per tile
         const int tiles_m = static_cast<int>(quads ? (M + kColTileM - 1) / kColTileM : (M + 63) / 64), tiles_c = (g.C + tch - 1) / tch;
-        const int64_t blocks = static_cast<int64_t>(g.KH) * g.KW * tiles_m * tiles_c;
+        // the dword kernel walks the KW taps of a filter row inside a workgroup, the byte kernel takes one tap
+        const int64_t blocks = static_cast<int64_t>(g.KH) * (quads ? 1 : g.KW) * tiles_m * tiles_c;
         if (blocks >= (int64_t{1} << 31)) return FXP_ERR_DIMS;
         // the flipped weights of the input-gradient convolution ride along in the same launch
         const unsigned flip_blocks = need_flip ? grid_for(static_cast<int64_t>(g.Cout) * K) : 0u;

@@ -157,6 +157,19 @@ __device__ inline void absmax_body(const uint32_t* __restrict__ x, size_t n, uin
     if (threadIdx.x == 0) partials[bid] = m;
 }
 
+// byte permute: every byte of the result is byte (sel & 7) of the pair {hi, lo} (0-3 = lo, 4-7 = hi)
+__device__ inline uint32_t perm(uint32_t hi, uint32_t lo, uint32_t sel) { return __builtin_amdgcn_perm(hi, lo, sel); }
+
+// 4 x 4 byte transpose: o[r] holds columns 0..3 of row r; t[c] receives rows 0..3 of column c
+__device__ inline void transpose4x4(const uint32_t (&o)[4], uint32_t (&t)[4]) {
+    const uint32_t a = perm(o[1], o[0], 0x05010400u), b = perm(o[1], o[0], 0x07030602u);   // rows 0,1: columns 0,1 | 2,3
+    const uint32_t c = perm(o[3], o[2], 0x05010400u), d = perm(o[3], o[2], 0x07030602u);   // rows 2,3
+    t[0] = perm(c, a, 0x05040100u);
+    t[1] = perm(c, a, 0x07060302u);
+    t[2] = perm(d, b, 0x05040100u);
+    t[3] = perm(d, b, 0x07060302u);
+}
+
 // Philox-4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): counter (c0..c3), key (k0, k1), ten rounds of two
 // 32x32->64 multiplies with the Weyl key schedule.  Element i of a tensor stream uses word i % 4 of the
 // block with counter (i / 4, stream id) and key = seed.

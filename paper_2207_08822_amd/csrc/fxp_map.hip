@@ -68,9 +68,6 @@ __device__ inline uint32_t with_sign(uint32_t mag, uint32_t b) {
     return (mag ^ sm) - sm;
 }
 
-// byte permute: every byte of the result is byte (sel & 7) of the pair {hi, lo} (0-3 = lo, 4-7 = hi)
-__device__ inline uint32_t perm(uint32_t hi, uint32_t lo, uint32_t sel) { return __builtin_amdgcn_perm(hi, lo, sel); }
-
 // the four signed results of a 16-byte load as one dword, low bytes in element order
 __device__ inline uint32_t pack4(uint32_t q0, uint32_t q1, uint32_t q2, uint32_t q3, const uint4 v) {
     const uint32_t p01 = perm(with_sign(q1, v.y), with_sign(q0, v.x), 0x0c0c0400u);
@@ -78,15 +75,6 @@ __device__ inline uint32_t pack4(uint32_t q0, uint32_t q1, uint32_t q2, uint32_t
     return perm(p23, p01, 0x05040100u);
 }
 
-// 4 x 4 byte transpose: o[r] holds columns 0..3 of row r; t[c] receives rows 0..3 of column c
-__device__ inline void transpose4x4(const uint32_t (&o)[4], uint32_t (&t)[4]) {
-    const uint32_t a = perm(o[1], o[0], 0x05010400u), b = perm(o[1], o[0], 0x07030602u);   // rows 0,1: columns 0,1 | 2,3
-    const uint32_t c = perm(o[3], o[2], 0x05010400u), d = perm(o[3], o[2], 0x07030602u);   // rows 2,3
-    t[0] = perm(c, a, 0x05040100u);
-    t[1] = perm(c, a, 0x07060302u);
-    t[2] = perm(d, b, 0x05040100u);
-    t[3] = perm(d, b, 0x07060302u);
-}
 
 __device__ inline MapCfg make_cfg(int e_max, int bits) {
     MapCfg c;
