@@ -234,6 +234,28 @@ def test_gemm_extreme_values_longest_contraction(fxp):
     assert np.array_equal(got, want) and abs(int(got[0, 0])) == 16129 * K
 
 
+@pytest.mark.parametrize("K", [133144, 133136, 133120])
+def test_gemm_longest_contraction_the_interface_allows(fxp, K):
+    """127 * 127 * 133144 is the last sum below 2^31: extreme operands at the documented maximum of K (and at
+    the nearest multiples of 16 and of 128, which take the other loaders), whole or split along K, through
+    workspace slices and through atomics."""
+    say("gemm extremes at the largest K", K)
+    A = np.full((70, K), 127, np.int8)
+    B = np.full((130, K), -127, np.int8)
+    A[::2] = -127
+    want = oracle.gemm(A, B, transB=True)
+    assert int(np.abs(want.astype(np.int64)).max()) <= 2**31 - 1
+    assert abs(int(want[0, 0])) == 16129 * K and int(want[0, 0]) == -int(want[1, 0])
+    tiny = torch.empty(256, dtype=torch.uint8, device="cuda")
+    for ws in (None, tiny):
+        got = host(fxp.gemm(dev(A), dev(B), transB=True, ws=ws))
+        assert np.array_equal(got, want)
+    e = dev(np.array([140, 99], np.int32))
+    assert same_bits(host(fxp.gemm_unmap(dev(A), dev(B), e[0:1], e[1:2], transB=True)), oracle.unmap(want, 140, 99))
+    with pytest.raises(Exception):
+        fxp.gemm(dev(np.zeros((8, 133145), np.int8)), dev(np.zeros((8, 133145), np.int8)), transB=True)
+
+
 def test_gemm_split_k_both_ways_and_deterministic(fxp):
     """Long contraction, small output: slices of K go to the workspace and are summed by a
     second pass; with no room for the slices they add into the output with int32 atomics."""
