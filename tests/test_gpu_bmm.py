@@ -21,9 +21,11 @@ def fxp():
     return binding
 
 
-# batch, M, N, K: aligned (direct-to-LDS kernels, 128 and 256 tiles), K tails, unaligned (general loads), tiny
+# batch, M, N, K: aligned (direct-to-LDS kernels, 128 and 256 tiles), K tails, unaligned (general loads), tiny,
+# and the largest batch the interface accepts (through both kinds of kernel)
 GEMM_CASES = [(3, 128, 128, 64), (5, 208, 208, 64), (4, 208, 64, 208), (2, 300, 260, 128), (3, 512, 512, 256),
-              (40, 256, 256, 128), (7, 197, 197, 64), (6, 197, 64, 197), (9, 5, 3, 7), (1, 130, 70, 48), (2, 64, 64, 0)]
+              (40, 256, 256, 128), (7, 197, 197, 64), (6, 197, 64, 197), (9, 5, 3, 7), (1, 130, 70, 48), (2, 64, 64, 0),
+              (65535, 16, 16, 16), (65535, 16, 24, 64)]
 
 
 @pytest.mark.parametrize("batch,M,N,K", GEMM_CASES)
