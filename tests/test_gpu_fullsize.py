@@ -109,12 +109,15 @@ def _row_blocks(rows, cols, extra=()):
     return sorted({max(0, min(rows - 8, m)) for m in marks})
 
 
-@pytest.mark.parametrize("rows,cols,transposed", [((1 << 18) + 200, 16384 + 128, True), ((1 << 20) + 640, 16384, False)],
-                         ids=["2^32-elements-both-copies", "2^34-elements"])
+@pytest.mark.parametrize("rows,cols,transposed", [((1 << 18) + 200, 16384 + 128, True), ((1 << 20) + 640, 16384, False),
+                                                  (272, (1 << 22) - 4, True), (130, 1 << 22, True)],
+                         ids=["2^32-elements-both-copies", "2^34-elements", "widest-rows-of-the-tiled-kernel",
+                              "rows-too-wide-for-the-tiled-kernel"])
 def test_scale_and_map_of_tensors_beyond_32_bit_indices(fxp, rows, cols, transposed):
     """Element counts above 2^32 (64-bit addressing, the transposed copy included) and above 2^34 (the second
-    counter word of the random stream comes into use): the scale against a reduction by torch, the mapped bytes
-    against the oracle on row blocks at both ends and around the 2^32 / 2^34 crossings."""
+    counter word of the random stream comes into use), and rows of 2^22 elements, where the tiled kernel's 32-bit
+    offsets inside a tile end and the one-element-per-thread kernel takes over: the scale against a reduction by
+    torch, the mapped bytes against the oracle on row blocks at both ends and around the 2^32 / 2^34 crossings."""
     n = rows * cols
     _need_memory(n * (6 if transposed else 5))
     say("huge map", rows, cols, "transposed" if transposed else "")
