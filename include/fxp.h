@@ -45,7 +45,8 @@ typedef enum fxp_status {
     FXP_ERR_ROUNDING = -5,  /* unknown rounding mode */
     FXP_ERR_BITS = -6,      /* bits outside [2, 8] */
     FXP_ERR_LAUNCH = -7,    /* the HIP runtime refused a launch */
-    FXP_ERR_OVERFLOW = -8   /* contraction so long that int32 accumulation could overflow (> 133144) */
+    FXP_ERR_OVERFLOW = -8   /* contraction longer than an int32 sum is sure to hold (> 133144 terms) where the call has no
+                               64-bit path for it: int32 output, a batched product, or no room in ws for the slices */
 } fxp_status;
 
 /* Rounding of the 24-bit shifted mantissa to bits-1 magnitude bits. */
@@ -138,7 +139,8 @@ int fxp_map_absmax(const float* x, int64_t rows, int64_t cols, const uint32_t* a
  * transA = 0: A stored [M,K], lda >= K.  transA = 1: A stored [K,M], lda >= M.
  * transB = 0: B stored [K,N], ldb >= N.  transB = 1: B stored [N,K], ldb >= K.
  * Native form is (transA, transB) = (0, 1), both operands contiguous along the
- * contraction; other forms first transpose the operand into ws.  K <= 133144.
+ * contraction; other forms first transpose the operand into ws.  K <= 133144 (127^2 * K < 2^31: the int32
+ * sums cannot wrap).
  * Fast loads need A, B 16-byte aligned and lda, ldb, K multiples of 16; other
  * shapes take a slower loader with identical results.  C 4-byte aligned. */
 int fxp_gemm(int transA, int transB, int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, const int8_t* B,
@@ -156,7 +158,11 @@ int fxp_unmap(const int32_t* acc, size_t n, const int32_t* eA, int bitsA, const 
 int fxp_unmap_i8(const int8_t* q, size_t n, const int32_t* eA, int bitsA, float* out, void* stream);
 
 /* fxp_gemm with the inverse mapping fused into its epilogue: C is fp32 and
- * receives what fxp_unmap would make of the int32 result. */
+ * receives what fxp_unmap would make of the int32 result.
+ * K may exceed 133144 here: the contraction then runs as slices of at most 133120 terms, each summed exactly
+ * in int32 into ws, and the slices are added in 64 bits before the one rounding of the inverse mapping - C is
+ * the exact integer sum times 2^E, rounded once, at any K < 2^31.  That needs the ws of
+ * fxp_workspace_bytes(FXP_OP_GEMM, M, N, K); with less, FXP_ERR_OVERFLOW. */
 int fxp_gemm_unmap(int transA, int transB, int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda,
                    const int8_t* B, int64_t ldb, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB, float* C,
                    int64_t ldc, void* ws, size_t ws_bytes, void* stream);
@@ -193,7 +199,9 @@ int fxp_linear_fwd(const float* X, const float* W, int64_t M, int64_t K, int64_t
  * dL/dX = G_hat W_hat^T): scale + map dY ONCE (FXP_TAG_DY; both GEMMs use the
  * same rounded gradient), then dX[M,K] and dW[K,N] as fp32.  dX or dW may be
  * NULL to skip it.  dYq [M,N], dYqT [N,M] and e_dY (1 int32) are caller-
- * allocated outputs/scratch.  Uses saved->XqT, saved->Wq, saved->eX, saved->eW. */
+ * allocated outputs/scratch.  Uses saved->XqT, saved->Wq, saved->eX, saved->eW.
+ * M, K, N are not limited by the int32 accumulator: a contraction of more than 133144 terms (the weight
+ * gradient of a layer applied to more rows than that) runs as slices, see fxp_gemm_unmap. */
 int fxp_linear_bwd(const float* dY, const fxp_saved* saved, int64_t M, int64_t K, int64_t N, float* dX, float* dW,
                    int8_t* dYq, int8_t* dYqT, int32_t* e_dY, uint64_t seed, uint64_t step, int rounding, int bits,
                    void* ws, size_t ws_bytes, void* stream);
@@ -310,11 +318,12 @@ size_t fxp_conv2d_workspace_bytes(const fxp_conv2d_shape* shape, int backward);
 /* Forward: the activation tensor is mapped once as a whole (element index = its channels-last flat index,
  * FXP_TAG_X), the weights likewise (FXP_TAG_W); the int8 patches are multiplied on the matrix cores - read
  * straight from the int8 activation by the GEMM loader when C is a multiple of 64, gathered into scratch
- * first otherwise - and Y receives the inverse-mapped fp32 result.  Contraction KH*KW*C <= 133144. */
+ * first otherwise - and Y receives the inverse-mapped fp32 result.  Contractions KH*KW*C and KH*KW*Cout <= 133144. */
 int fxp_conv2d_fwd(const float* X, const float* W, const fxp_conv2d_shape* shape, float* Y, const fxp_conv_saved* saved,
                    uint64_t seed, uint64_t step, int rounding, int bits, void* ws, size_t ws_bytes, void* stream);
 
-/* Backward: dY is mapped once (FXP_TAG_DY); dW[Cout,KH,KW,C] sums over all N*Ho*Wo output pixels (<= 133144),
+/* Backward: dY is mapped once (FXP_TAG_DY); dW[Cout,KH,KW,C] sums over all N*Ho*Wo output pixels (any number: beyond
+ * 133144 the sum runs as int32 slices added in 64 bits, like the long contractions of fxp_gemm_unmap),
  * dX[N,H,W,C] sums, per input pixel, the patch entries that read it (exact int32, then one inverse mapping).
  * dX or dW may be NULL.  dYq [N*Ho*Wo, Cout], dYqT [Cout, N*Ho*Wo] and e_dY are caller-allocated. */
 int fxp_conv2d_bwd(const float* dY, const fxp_conv_saved* saved, const fxp_conv2d_shape* shape, float* dX, float* dW,

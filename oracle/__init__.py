@@ -35,6 +35,8 @@ def lib():
         L.fxp_ref_map_rows.argtypes = [vp, i64, i64, i64, i32, vp, u64, u64, c.c_int, c.c_int]
         L.fxp_ref_gemm.argtypes = [c.c_int, c.c_int, i64, i64, i64, vp, i64, vp, i64, vp, i64]
         L.fxp_ref_unmap.argtypes = [vp, u64, i32, c.c_int, i32, c.c_int, vp]
+        L.fxp_ref_gemm64.argtypes = L.fxp_ref_gemm.argtypes
+        L.fxp_ref_unmap64.argtypes = L.fxp_ref_unmap.argtypes
         L.fxp_ref_unmap_i8.argtypes = [vp, u64, i32, c.c_int, vp]
         L.fxp_ref_linear_fwd.argtypes = [vp, vp, i64, i64, i64, vp, vp, vp, vp, vp, u64, u64, c.c_int, c.c_int]
         L.fxp_ref_linear_bwd.argtypes = [vp, vp, vp, i32, i32, i64, i64, i64, vp, vp, vp, vp, u64, u64, c.c_int,
@@ -51,6 +53,7 @@ def lib():
         L.fxp_ref_conv2d_fwd_acc.argtypes = [vp, i64, i64, i64, i64, vp, i64, i64, i64, i64, i64, vp]
         L.fxp_ref_conv2d_bwd_input_acc.argtypes = [vp, vp] + cd + [vp]
         L.fxp_ref_conv2d_bwd_weight_acc.argtypes = [vp, vp] + cd + [vp]
+        L.fxp_ref_conv2d_bwd_weight_acc64.argtypes = [vp, vp] + cd + [vp]
         L.fxp_ref_conv2d_fwd.argtypes = [vp, vp] + cd + [vp, vp, vp, vp, vp, u64, u64, c.c_int, c.c_int]
         L.fxp_ref_conv2d_bwd.argtypes = [vp, vp, vp, i32, i32] + cd + [vp, vp, vp, vp, u64, u64, c.c_int, c.c_int]
         _lib = L
@@ -121,15 +124,39 @@ def gemm(A, B, transA=False, transB=False):
     M, K = (A.shape[1], A.shape[0]) if transA else A.shape
     Kb, N = (B.shape[1], B.shape[0]) if transB else B.shape
     assert K == Kb, "contraction lengths differ"
+    if K > INT32_TERMS:
+        return gemm64(A, B, transA, transB)
     C = np.empty((M, N), dtype=np.int32)
     _check(lib().fxp_ref_gemm(int(transA), int(transB), M, N, K, _ptr(A), A.shape[1], _ptr(B), B.shape[1], _ptr(C),
                               N), "gemm")
     return C
 
 
+INT32_TERMS = 133144      # the longest contraction whose sums an int32 always holds (127^2 * 133144 < 2^31)
+
+
+def gemm64(A, B, transA=False, transB=False):
+    """The same product with exact int64 sums (what gemm returns for contractions beyond INT32_TERMS)."""
+    A = np.ascontiguousarray(A, dtype=np.int8)
+    B = np.ascontiguousarray(B, dtype=np.int8)
+    M, K = (A.shape[1], A.shape[0]) if transA else A.shape
+    Kb, N = (B.shape[1], B.shape[0]) if transB else B.shape
+    assert K == Kb, "contraction lengths differ"
+    C = np.empty((M, N), dtype=np.int64)
+    _check(lib().fxp_ref_gemm64(int(transA), int(transB), M, N, K, _ptr(A), A.shape[1], _ptr(B), B.shape[1], _ptr(C),
+                                N), "gemm64")
+    return C
+
+
 def unmap(acc, eA, eB=None, bitsA=8, bitsB=8):
-    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    """int32 sums, or int64 sums (of a contraction beyond INT32_TERMS), to fp32."""
+    acc = np.ascontiguousarray(acc)
     out = np.empty(acc.shape, dtype=np.float32)
+    if acc.dtype == np.int64:
+        _check(lib().fxp_ref_unmap64(_ptr(acc), acc.size, int(eA), bitsA, int(eB) if eB is not None else 0,
+                                     bitsB if eB is not None else 0, _ptr(out)), "unmap64")
+        return out
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
     _check(lib().fxp_ref_unmap(_ptr(acc), acc.size, int(eA), bitsA, int(eB) if eB is not None else 0,
                                bitsB if eB is not None else 0, _ptr(out)), "unmap")
     return out
@@ -208,6 +235,12 @@ def conv2d_bwd_weight_acc(Xq, Gq, w_shape, stride=1, pad=0):
     Xq, Gq = _i8(Xq), _i8(Gq)
     N, H, W, C = Xq.shape
     Cout, KH, KW, _ = w_shape
+    Ho, Wo = conv_out_hw(H, W, KH, KW, stride, pad)
+    if N * Ho * Wo > INT32_TERMS:            # more output pixels than an int32 sum is sure to hold: exact int64 sums
+        acc = np.empty((Cout, KH, KW, C), dtype=np.int64)
+        _check(lib().fxp_ref_conv2d_bwd_weight_acc64(_ptr(Xq), _ptr(Gq), N, H, W, C, Cout, KH, KW, stride, pad, _ptr(acc)),
+               "conv2d_bwd_weight_acc64")
+        return acc
     acc = np.empty((Cout, KH, KW, C), dtype=np.int32)
     _check(lib().fxp_ref_conv2d_bwd_weight_acc(_ptr(Xq), _ptr(Gq), N, H, W, C, Cout, KH, KW, stride, pad, _ptr(acc)),
            "conv2d_bwd_weight_acc")

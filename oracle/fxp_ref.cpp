@@ -12,7 +12,11 @@
 //   map    — Sec. 3.1 + App. A.1 (Fig. 4): unpack, shift the 24-bit mantissa
 //            right by e_max-e_i, round the result stochastically to 7 bits by
 //            comparing a random number with the low 17 bits, attach the sign.
-//   gemm   — Sec. 3.3 (Fig. 2): int8 x int8 products accumulated in int32.
+//   gemm   — Sec. 3.3 (Fig. 2): int8 x int8 products accumulated in int32.  An int32 sum holds any
+//            contraction of up to 133144 terms (127^2 * 133144 < 2^31).  For longer ones (the weight
+//            gradient of a layer applied to more rows than that) the paper gives nothing; this build
+//            takes what the int32 sum is an instance of, the exact integer sum, held in int64
+//            (gemm64), and the inverse mapping rounds it once (unmap64).
 //   unmap  — Sec. 3.2 (Fig. 1b): shared exponent (sum of the operand
 //            exponents, Sec. 3.3) + integer mantissa -> rounded, normalised,
 //            packed fp32.
@@ -270,6 +274,63 @@ int fxp_ref_unmap_i8(const int8_t* q, uint64_t n, int32_t eA, int bitsA, float* 
     return 0;
 }
 
+// The longest contraction whose sums an int32 accumulator always holds.
+static const int64_t kInt32Terms = 133144;
+
+// The same product with the exact sum held in int64: for contractions beyond kInt32Terms.
+int fxp_ref_gemm64(int transA, int transB, int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda,
+                   const int8_t* B, int64_t ldb, int64_t* C, int64_t ldc) {
+    if (M < 0 || N < 0 || K < 0 || ldc < N) return -2;
+    if (M * N > 0 && !C) return -1;
+    if (M * K > 0 && !A) return -1;
+    if (N * K > 0 && !B) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i) {
+        for (int64_t j = 0; j < N; ++j) {
+            int64_t acc = 0;
+            for (int64_t k = 0; k < K; ++k) {
+                const int64_t a = transA ? A[k * lda + i] : A[i * lda + k];
+                const int64_t b = transB ? B[j * ldb + k] : B[k * ldb + j];
+                acc += a * b;
+            }
+            C[i * ldc + j] = acc;
+        }
+    }
+    return 0;
+}
+
+// Inverse mapping of such a sum: |acc| < 2^53 (127^2 * 2^31 terms at most), so the conversion to double
+// and the scaling are exact and the value is rounded once, to fp32.
+int fxp_ref_unmap64(const int64_t* acc, uint64_t n, int32_t eA, int bitsA, int32_t eB, int bitsB, float* out) {
+    if (n && (!acc || !out)) return -1;
+    if (bad_bits(bitsA) || (bitsB != 0 && bad_bits(bitsB))) return -2;
+    const int32_t E = lsb_exponent(eA, bitsA) + (bitsB ? lsb_exponent(eB, bitsB) : 0);
+    for (int64_t i = 0; i < static_cast<int64_t>(n); ++i) {
+        if (acc[i] >= (int64_t{1} << 53) || acc[i] <= -(int64_t{1} << 53)) return -2;
+        out[i] = static_cast<float>(std::ldexp(static_cast<double>(acc[i]), E));
+    }
+    return 0;
+}
+
+// product + inverse mapping of a layer: int32 sums where they are sure to fit, int64 sums beyond
+static int product_unmap(int transA, int transB, int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda,
+                         const int8_t* B, int64_t ldb, int32_t eA, int32_t eB, int bits, float* out) {
+    const size_t n = static_cast<size_t>(M * N);
+    int rc;
+    if (K <= kInt32Terms) {
+        int32_t* acc = new int32_t[n + 1];
+        rc = fxp_ref_gemm(transA, transB, M, N, K, A, lda, B, ldb, acc, N);
+        if (!rc) rc = fxp_ref_unmap(acc, n, eA, bits, eB, bits, out);
+        delete[] acc;
+    } else {
+        int64_t* acc = new int64_t[n + 1];
+        rc = fxp_ref_gemm64(transA, transB, M, N, K, A, lda, B, ldb, acc, N);
+        if (!rc) rc = fxp_ref_unmap64(acc, n, eA, bits, eB, bits, out);
+        delete[] acc;
+    }
+    return rc;
+}
+
 // App. A.2, forward: Y = unmap(map(X) * map(W)).  X[M,K], W[K,N], Y[M,N].
 // Xq[M,K], Wq[K,N] and the two scales are returned for the backward pass.
 // Random streams: (step << 8) | tag with tag 0 for X and 1 for W.
@@ -281,11 +342,7 @@ int fxp_ref_linear_fwd(const float* X, const float* W, int64_t M, int64_t K, int
     if ((rc = fxp_ref_scale(W, static_cast<uint64_t>(K * N), eW))) return rc;
     if ((rc = fxp_ref_map(X, M, K, *eX, Xq, nullptr, seed, (step << 8) | 0u, rounding, bits))) return rc;
     if ((rc = fxp_ref_map(W, K, N, *eW, Wq, nullptr, seed, (step << 8) | 1u, rounding, bits))) return rc;
-    int32_t* acc = new int32_t[static_cast<size_t>(M * N) + 1];
-    rc = fxp_ref_gemm(0, 0, M, N, K, Xq, K, Wq, N, acc, N);
-    if (!rc) rc = fxp_ref_unmap(acc, static_cast<uint64_t>(M * N), *eX, bits, *eW, bits, Y);
-    delete[] acc;
-    return rc;
+    return product_unmap(0, 0, M, N, K, Xq, K, Wq, N, *eX, *eW, bits, Y);
 }
 
 // App. A.2, backward: G = map(dY) once (stream tag 2); dX = unmap(G * Wq^T)
@@ -297,20 +354,8 @@ int fxp_ref_linear_bwd(const float* dY, const int8_t* Xq, const int8_t* Wq, int3
     int rc;
     if ((rc = fxp_ref_scale(dY, static_cast<uint64_t>(M * N), eG))) return rc;
     if ((rc = fxp_ref_map(dY, M, N, *eG, dYq, nullptr, seed, (step << 8) | 2u, rounding, bits))) return rc;
-    if (dX) {
-        int32_t* acc = new int32_t[static_cast<size_t>(M * K) + 1];
-        rc = fxp_ref_gemm(0, 1, M, K, N, dYq, N, Wq, N, acc, K);
-        if (!rc) rc = fxp_ref_unmap(acc, static_cast<uint64_t>(M * K), *eG, bits, eW, bits, dX);
-        delete[] acc;
-        if (rc) return rc;
-    }
-    if (dW) {
-        int32_t* acc = new int32_t[static_cast<size_t>(K * N) + 1];
-        rc = fxp_ref_gemm(1, 0, K, N, M, Xq, K, dYq, N, acc, N);
-        if (!rc) rc = fxp_ref_unmap(acc, static_cast<uint64_t>(K * N), eX, bits, *eG, bits, dW);
-        delete[] acc;
-        if (rc) return rc;
-    }
+    if (dX && (rc = product_unmap(0, 1, M, K, N, dYq, N, Wq, N, *eG, eW, bits, dX))) return rc;
+    if (dW && (rc = product_unmap(1, 0, K, N, M, Xq, K, dYq, N, eX, *eG, bits, dW))) return rc;
     return 0;
 }
 
@@ -381,8 +426,11 @@ int fxp_ref_conv2d_bwd_input_acc(const int8_t* Gq, const int8_t* Wq, int64_t N, 
 }
 
 // dL/dW[co,kh,kw,c] = sum over (n,ho,wo) of X[n, ho*stride+kh-pad, wo*stride+kw-pad, c] * G[n,ho,wo,co]
-int fxp_ref_conv2d_bwd_weight_acc(const int8_t* Xq, const int8_t* Gq, int64_t N, int64_t H, int64_t W, int64_t C,
-                                  int64_t Cout, int64_t KH, int64_t KW, int64_t stride, int64_t pad, int32_t* dWacc) {
+// (Acc = int32_t, or int64_t when more than kInt32Terms output pixels are summed)
+}  // extern "C"
+template <typename Acc>
+static int conv2d_bwd_weight_acc(const int8_t* Xq, const int8_t* Gq, int64_t N, int64_t H, int64_t W, int64_t C,
+                                 int64_t Cout, int64_t KH, int64_t KW, int64_t stride, int64_t pad, Acc* dWacc) {
     int64_t Ho, Wo;
     if (!conv_dims_ok(N, H, W, C, Cout, KH, KW, stride, pad, &Ho, &Wo)) return -2;
     if (!Xq || !Gq || !dWacc) return -1;
@@ -391,7 +439,7 @@ int fxp_ref_conv2d_bwd_weight_acc(const int8_t* Xq, const int8_t* Gq, int64_t N,
         for (int64_t kh = 0; kh < KH; ++kh)
             for (int64_t kw = 0; kw < KW; ++kw)
                 for (int64_t c = 0; c < C; ++c) {
-                    int32_t sum = 0;
+                    Acc sum = 0;
                     for (int64_t n = 0; n < N; ++n)
                         for (int64_t ho = 0; ho < Ho; ++ho) {
                             const int64_t h = ho * stride + kh - pad;
@@ -399,13 +447,24 @@ int fxp_ref_conv2d_bwd_weight_acc(const int8_t* Xq, const int8_t* Gq, int64_t N,
                             for (int64_t wo = 0; wo < Wo; ++wo) {
                                 const int64_t w = wo * stride + kw - pad;
                                 if (w < 0 || w >= W) continue;
-                                sum += static_cast<int32_t>(Xq[((n * H + h) * W + w) * C + c]) *
-                                       static_cast<int32_t>(Gq[((n * Ho + ho) * Wo + wo) * Cout + co]);
+                                sum += static_cast<Acc>(Xq[((n * H + h) * W + w) * C + c]) *
+                                       static_cast<Acc>(Gq[((n * Ho + ho) * Wo + wo) * Cout + co]);
                             }
                         }
                     dWacc[((co * KH + kh) * KW + kw) * C + c] = sum;
                 }
     return 0;
+}
+
+extern "C" {
+int fxp_ref_conv2d_bwd_weight_acc(const int8_t* Xq, const int8_t* Gq, int64_t N, int64_t H, int64_t W, int64_t C,
+                                  int64_t Cout, int64_t KH, int64_t KW, int64_t stride, int64_t pad, int32_t* dWacc) {
+    return conv2d_bwd_weight_acc<int32_t>(Xq, Gq, N, H, W, C, Cout, KH, KW, stride, pad, dWacc);
+}
+
+int fxp_ref_conv2d_bwd_weight_acc64(const int8_t* Xq, const int8_t* Gq, int64_t N, int64_t H, int64_t W, int64_t C,
+                                    int64_t Cout, int64_t KH, int64_t KW, int64_t stride, int64_t pad, int64_t* dWacc) {
+    return conv2d_bwd_weight_acc<int64_t>(Xq, Gq, N, H, W, C, Cout, KH, KW, stride, pad, dWacc);
 }
 
 // Integer convolution layer, forward: the activation tensor is mapped ONCE as a whole (one scale,
@@ -449,10 +508,17 @@ int fxp_ref_conv2d_bwd(const float* dY, const int8_t* Xq, const int8_t* Wq, int3
     }
     if (dW) {
         const size_t n = static_cast<size_t>(Cout * KH * KW * C);
-        int32_t* acc = new int32_t[n + 1];
-        rc = fxp_ref_conv2d_bwd_weight_acc(Xq, dYq, N, H, W, C, Cout, KH, KW, stride, pad, acc);
-        if (!rc) rc = fxp_ref_unmap(acc, n, eX, bits, *eG, bits, dW);
-        delete[] acc;
+        if (N * Ho * Wo <= kInt32Terms) {
+            int32_t* acc = new int32_t[n + 1];
+            rc = fxp_ref_conv2d_bwd_weight_acc(Xq, dYq, N, H, W, C, Cout, KH, KW, stride, pad, acc);
+            if (!rc) rc = fxp_ref_unmap(acc, n, eX, bits, *eG, bits, dW);
+            delete[] acc;
+        } else {
+            int64_t* acc = new int64_t[n + 1];
+            rc = fxp_ref_conv2d_bwd_weight_acc64(Xq, dYq, N, H, W, C, Cout, KH, KW, stride, pad, acc);
+            if (!rc) rc = fxp_ref_unmap64(acc, n, eX, bits, *eG, bits, dW);
+            delete[] acc;
+        }
         if (rc) return rc;
     }
     return 0;

@@ -320,7 +320,9 @@ static int geo_of(const fxp_conv2d_shape* s, ConvGeo* g) {
     g->Wo = (g->W + 2 * g->pad - g->KW) / g->stride + 1;
     if (g->M() >= (int64_t{1} << 31) || g->K() >= (int64_t{1} << 31) || static_cast<int64_t>(g->N) * g->H * g->W >= (int64_t{1} << 31))
         return FXP_ERR_DIMS;
-    if (g->K() > kMaxContraction || g->M() > kMaxContraction || g->Cout > kMaxContraction) return FXP_ERR_OVERFLOW;
+    // contractions of the forward and input-gradient products; the weight gradient sums over the M output pixels,
+    // and beyond this many its workspace slices are added in 64 bits
+    if (g->K() > kMaxContraction || static_cast<int64_t>(g->KH) * g->KW * g->Cout > kMaxContraction) return FXP_ERR_OVERFLOW;
     return FXP_OK;
 }
 

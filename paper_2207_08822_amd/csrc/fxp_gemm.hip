@@ -172,7 +172,16 @@ __device__ inline void splitk_reduce_body(const ReduceRider& r, unsigned b, unsi
     };
     const int64_t total = static_cast<int64_t>(r.M) * r.N;
     const bool flat = r.ldc == r.N && (reinterpret_cast<uintptr_t>(r.C) & 15u) == 0;
-    if (flat) {
+    if (r.wide) {
+        // contraction beyond what one int32 sum holds: 64-bit sum of the slices, one element per thread and round
+        for (int64_t i = static_cast<int64_t>(b) * nt + threadIdx.x; i < total; i += static_cast<int64_t>(nb) * nt) {
+            int64_t acc = 0;
+            for (int sidx = 0; sidx < splits; ++sidx) acc += parts[sidx * stride + i];
+            const float o = unmap_value64(acc, E);
+            static_cast<float*>(r.C)[(i / r.N) * r.ldc + i % r.N] = o;
+            m = fmaxf(m, fabsf(o));
+        }
+    } else if (flat) {
         const int64_t nvec = total >> 2;
         for (int64_t i = static_cast<int64_t>(b) * nt + threadIdx.x; i < nvec; i += static_cast<int64_t>(nb) * nt) {
             int4 acc = make_int4(0, 0, 0, 0);
@@ -969,6 +978,12 @@ struct GemmPlan {
     bool tall;     // split products only: 128 x 256 tiles (use256 is false then)
 };
 
+// no slice longer than one int32 sum can hold
+static GemmPlan long_contraction(GemmPlan p, int64_t K) {
+    if (K > kMaxContraction) p.splits = static_cast<int>(std::max<int64_t>(p.splits, (K + kMaxSlice - 1) / kMaxSlice));
+    return p;
+}
+
 static GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K) {
     const int num_cu = 256;
     const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
@@ -986,12 +1001,12 @@ static GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K) {
             p.use256 = false;
             p.tall = true;
             p.splits = static_cast<int>(std::max<int64_t>(1, std::min<int64_t>(num_cu / tiles, K / 1024)));
-            return p;
+            return long_contraction(p, K);
         }
         p.use256 = false;
         p.splits = static_cast<int>(std::max<int64_t>(1, std::min<int64_t>((num_cu + t128 / 2) / t128, K / 1024)));
     }
-    return p;
+    return long_contraction(p, K);
 }
 
 size_t gemm_split_ws_bytes(int64_t M, int64_t N, int64_t K) {
@@ -1079,6 +1094,8 @@ int gemm_nt_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda
     void* dst = to_ws ? ws : C;
     const int64_t dst_ld = to_ws ? N : ldc;
     const int64_t split_stride = to_ws ? M * N : 0;
+    // beyond kMaxContraction only the 64-bit sum of workspace slices is exact
+    if (K > kMaxContraction && !(to_ws && fp32_out)) return FXP_ERR_OVERFLOW;
     int hr, hc;
     dim3 hgrid;
     rows_launch_shape(M, N, ldc, &hr, &hc, &hgrid);
@@ -1121,6 +1138,7 @@ int gemm_nt_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda
         r.fp32_out = fp32_out ? 1 : 0;
         r.eA = eA; r.bitsA = bitsA; r.eB = eB; r.bitsB = bitsB;
         r.amax = amax;
+        r.wide = K > kMaxContraction ? 1 : 0;
         r.blocks = reduce_blocks(M, N);
         if (defer != nullptr) {
             *defer = r;
@@ -1168,11 +1186,12 @@ int conv_gemm_launch(const ConvTaps& ct, int KH, int64_t M, int64_t Cout, const 
     return conv_gemm_launch_cfg<64, 64>(ct, K, M, Cout, Xq, Wq, Y, eA, bitsA, eB, bitsB, s, ride);
 }
 
+// long_k: the caller can take a contraction beyond kMaxContraction (fp32 output through workspace slices)
 static int check_gemm_args(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, int transA, const void* B,
-                           int64_t ldb, int transB, const void* C, int64_t ldc) {
+                           int64_t ldb, int transB, const void* C, int64_t ldc, bool long_k = false) {
     if (M < 0 || N < 0 || K < 0) return FXP_ERR_DIMS;
-    if (M >= (int64_t{1} << 31) || N >= (int64_t{1} << 31)) return FXP_ERR_DIMS;
-    if (K > kMaxContraction) return FXP_ERR_OVERFLOW;
+    if (M >= (int64_t{1} << 31) || N >= (int64_t{1} << 31) || K >= (int64_t{1} << 31)) return FXP_ERR_DIMS;
+    if (K > kMaxContraction && !long_k) return FXP_ERR_OVERFLOW;
     if (lda < (transA ? M : K) || ldb < (transB ? K : N) || ldc < N) return FXP_ERR_DIMS;
     if ((M * N > 0 && !C) || (M * K > 0 && !A) || (N * K > 0 && !B)) return FXP_ERR_NULL;
     if (!aligned(C, 4)) return FXP_ERR_ALIGN;
@@ -1197,6 +1216,8 @@ static int gemm_any(int transA, int transB, int64_t M, int64_t N, int64_t K, con
     const size_t need = gemm_ws_bytes(transA, transB, M, N, K);
     if (need > 0 && (!ws || ws_bytes < need)) return FXP_ERR_WORKSPACE;
     if (ws && !aligned(ws, 256)) return FXP_ERR_ALIGN;
+    // a contraction beyond one int32 sum needs the slice area behind the transposed copies (nothing is enqueued otherwise)
+    if (K > kMaxContraction && (!fp32_out || !ws || ws_bytes < need + gemm_split_ws_bytes(M, N, K))) return FXP_ERR_OVERFLOW;
     int8_t* w = static_cast<int8_t*>(ws);
     int rc;
     if (transA && K > 0) {
@@ -1230,7 +1251,7 @@ extern "C" int fxp_gemm(int transA, int transB, int64_t M, int64_t N, int64_t K,
 extern "C" int fxp_gemm_unmap(int transA, int transB, int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda,
                               const int8_t* B, int64_t ldb, const int32_t* eA, int bitsA, const int32_t* eB, int bitsB,
                               float* C, int64_t ldc, void* ws, size_t ws_bytes, void* stream) {
-    int rc = fxp::check_gemm_args(M, N, K, A, lda, transA, B, ldb, transB, C, ldc);
+    int rc = fxp::check_gemm_args(M, N, K, A, lda, transA, B, ldb, transB, C, ldc, true);
     if (rc) return rc;
     if (!eA) return FXP_ERR_NULL;
     if (bitsA < 2 || bitsA > 8 || (eB && (bitsB < 2 || bitsB > 8))) return FXP_ERR_BITS;
@@ -1242,7 +1263,7 @@ extern "C" int fxp_gemm_unmap_absmax(int transA, int transB, int64_t M, int64_t 
                                      const int8_t* B, int64_t ldb, const int32_t* eA, int bitsA, const int32_t* eB,
                                      int bitsB, float* C, int64_t ldc, uint32_t* out_absmax, void* ws, size_t ws_bytes,
                                      void* stream) {
-    int rc = fxp::check_gemm_args(M, N, K, A, lda, transA, B, ldb, transB, C, ldc);
+    int rc = fxp::check_gemm_args(M, N, K, A, lda, transA, B, ldb, transB, C, ldc, true);
     if (rc) return rc;
     if (!eA || !out_absmax) return FXP_ERR_NULL;
     if (!fxp::aligned(out_absmax, 4)) return FXP_ERR_ALIGN;

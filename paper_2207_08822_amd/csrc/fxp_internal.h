@@ -12,7 +12,11 @@ namespace fxp {
 constexpr int kMaxPartials = 1024;        // per-block maxima of the scale reduction (uint32 each)
 constexpr int kScaleThreads = 256;
 constexpr size_t kScaleWsBytes = kMaxPartials * sizeof(uint32_t);
-constexpr int64_t kMaxContraction = 133144;   // 127^2 * K < 2^31
+constexpr int64_t kMaxContraction = 133144;   // 127^2 * K < 2^31: the longest contraction one int32 sum can hold
+// Longer contractions (a weight gradient over more rows than that) run as slices of at most kMaxSlice terms (a
+// multiple of every K step), each summed exactly in int32 into its workspace slice; the slices are added in 64
+// bits and the inverse mapping rounds that sum once.
+constexpr int64_t kMaxSlice = 133120;
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? FXP_OK : FXP_ERR_LAUNCH; }
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
@@ -68,6 +72,7 @@ struct ReduceRider {
     const int32_t* eB = nullptr;
     int bitsB = 8;
     uint32_t* amax = nullptr;
+    int wide = 0;            // the contraction is longer than kMaxContraction: the slices are added in 64 bits
     unsigned blocks = 0;
     unsigned tiles = 0;      // set by the launcher: workgroups of the host product
     bool front = false;      // set by the launcher: riders before the tiles
@@ -228,5 +233,9 @@ __device__ inline float unmap_value(int acc, int E) {
     }
     return static_cast<float>(ldexp(static_cast<double>(acc), E));
 }
+
+// the same for a sum of slices that needs more than 32 bits (|acc| < 2^53: the conversion to double is exact, and
+// so is the scaling; one rounding, double -> float)
+__device__ inline float unmap_value64(int64_t acc, int E) { return static_cast<float>(ldexp(static_cast<double>(acc), E)); }
 
 }  // namespace fxp

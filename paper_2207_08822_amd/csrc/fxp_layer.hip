@@ -40,7 +40,7 @@ extern "C" const char* fxp_strerror(int status) {
     }
 }
 
-extern "C" int fxp_version(void) { return 110; }
+extern "C" int fxp_version(void) { return 111; }
 
 extern "C" size_t fxp_workspace_bytes(int op, int64_t M, int64_t N, int64_t K) {
     if (M < 0 || N < 0 || K < 0) return 0;
@@ -64,7 +64,6 @@ extern "C" int fxp_linear_fwd(const float* X, const float* W, int64_t M, int64_t
     using namespace fxp;
     int rc = check_layer(M, K, N, rounding, bits, ws, ws_bytes, fxp_workspace_bytes(FXP_OP_LINEAR_FWD, M, N, K));
     if (rc) return rc;
-    if (K > kMaxContraction) return FXP_ERR_OVERFLOW;
     if (!X || !W || !Y || !saved || !saved->Xq || !saved->XqT || !saved->Wq || !saved->WqT || !saved->eX || !saved->eW)
         return FXP_ERR_NULL;
     if (!aligned(X, 4) || !aligned(W, 4) || !aligned(Y, 4) || !aligned(saved->eX, 4) || !aligned(saved->eW, 4))
@@ -86,7 +85,6 @@ extern "C" int fxp_linear_bwd(const float* dY, const fxp_saved* saved, int64_t M
     using namespace fxp;
     int rc = check_layer(M, K, N, rounding, bits, ws, ws_bytes, fxp_workspace_bytes(FXP_OP_LINEAR_BWD, M, N, K));
     if (rc) return rc;
-    if (N > kMaxContraction || M > kMaxContraction) return FXP_ERR_OVERFLOW;
     if (!dY || !saved || !saved->XqT || !saved->Wq || !saved->eX || !saved->eW || !dYq || !dYqT || !e_dY)
         return FXP_ERR_NULL;
     if (!aligned(dY, 4) || !aligned(dX, 4) || !aligned(dW, 4) || !aligned(e_dY, 4)) return FXP_ERR_ALIGN;

@@ -50,6 +50,11 @@ def test_host_only_entry_points_and_argument_errors():
     L.fxp_gemm.argtypes = [ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, i64, vp, sz, vp]
     assert L.fxp_gemm(0, 1, 4, 4, 200000, fake, 200000, fake, 200000, fake, 4, None, 0, None) == -8
     assert L.fxp_gemm(0, 1, 4, 4, 16, fake, 8, fake, 16, fake, 4, None, 0, None) == -2
+    # the fp32 variant takes such a contraction through 64-bit sums of workspace slices - not without the workspace
+    L.fxp_gemm_unmap.argtypes = [ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, ci, vp, ci, vp, i64, vp, sz, vp]
+    assert L.fxp_gemm_unmap(0, 1, 4, 4, 200000, fake, 200000, fake, 200000, fake, 8, fake, 8, fake, 4, None, 0, None) == -8
+    assert L.fxp_gemm_unmap(0, 1, 4, 4, 200000, fake, 200000, fake, 200000, fake, 8, fake, 8, fake, 4, fake, 256, None) == -8
+    assert L.fxp_workspace_bytes(1, 4, 4, 200000) >= 2 * 4 * 4 * 4          # FXP_OP_GEMM: two slices or more
     assert L.fxp_gemm(0, 0, 4, 4, 16, fake, 16, fake, 16, fake, 4, None, 0, None) == -4    # needs workspace
     L.fxp_scale.argtypes = [vp, sz, vp, vp, sz, vp]
     assert L.fxp_scale(fake, 16, fake, None, 0, None) == -4

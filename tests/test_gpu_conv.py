@@ -114,3 +114,16 @@ def test_conv_random_geometries(fxp):
         dY = rng.laplace(0, 1e-3, (N, Ho, Wo, Cout)).astype(np.float32)
         check_conv(fxp, X, Wt, dY, stride, pad, seed=done, step=done % 3)
         done += 1
+
+
+def test_conv_weight_gradient_over_more_pixels_than_one_int32_sum_holds(fxp):
+    """3 x 212 x 212 = 134 832 output pixels: the weight gradient sums over all of them (int32 slices added in 64
+    bits); channel 0 of X and of dY is at the top code everywhere, so those sums pass 2^31."""
+    rng = np.random.default_rng(77)
+    N, H, W, C, Cout = 3, 212, 212, 4, 8
+    X = np.maximum(rng.standard_normal((N, H, W, C)), 0).astype(np.float32).clip(0, 3.9)
+    Wt = (rng.standard_normal((Cout, 3, 3, C)) * 0.1).astype(np.float32)
+    dY = rng.uniform(-1e-3, 1e-3, (N, H, W, Cout)).astype(np.float32)
+    X[..., 0], dY[..., 0] = 127 / 32, 127 * 2.0 ** -16         # top code at every pixel (units 2^-5 and 2^-16)
+    say("conv with", N * H * W, "output pixels")
+    check_conv(fxp, X, Wt, dY, 1, 1)

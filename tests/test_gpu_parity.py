@@ -331,6 +331,71 @@ def layer_check_full(fxp, X, W, dY, seed, step, rounding=0, bits=8):
     return buf
 
 
+@pytest.mark.parametrize("K", [140032, 140016, 140001, 300000])
+def test_products_over_contractions_longer_than_one_int32_sum(fxp, K):
+    """Beyond 133144 terms an int32 sum could wrap: the product then runs as int32 slices added in 64 bits and
+    rounded once.  Extreme operands (sums of +-127^2 * K, past 2^31) and random ones, against the oracle's exact
+    int64 sums; K a multiple of 128, of 16 only, odd (element-wise loader), and long enough for three slices."""
+    say("long contraction", K)
+    rng = np.random.default_rng(K)
+    A, B = rand_i8(rng, (70, K)), rand_i8(rng, (130, K))
+    A[0], A[1], B[0], B[1] = 127, -127, 127, -127
+    want = oracle.gemm(A, B, transB=True)
+    assert want.dtype == np.int64 and int(want[0, 0]) == 16129 * K > 2**31 and int(want[0, 1]) == -16129 * K
+    e = dev(np.array([120, 131], np.int32))
+    assert same_bits(host(fxp.gemm_unmap(dev(A), dev(B), e[0:1], e[1:2], transB=True)), oracle.unmap(want, 120, 131))
+    # operands stored the other way round (transposed into the scratch area first), and the abs-max variant
+    AT, Bn = dev(np.ascontiguousarray(A.T)), dev(np.ascontiguousarray(B.T))
+    assert same_bits(host(fxp.gemm_unmap(AT, Bn, e[0:1], e[1:2], transA=True, transB=False)), oracle.unmap(want, 120, 131))
+    area = torch.zeros(fxp.ABSMAX_WORDS, dtype=torch.int32, device="cuda")
+    got = host(fxp.gemm_unmap_absmax(dev(A), dev(B), e[0:1], e[1:2], area, transB=True))
+    assert same_bits(got, oracle.unmap(want, 120, 131))
+    assert int(host(area).view(np.uint32).max()) == int(np.abs(got).max().view(np.uint32))
+    # no 64-bit path: int32 output, or no room for the slices
+    with pytest.raises(Exception):
+        fxp.gemm(dev(A), dev(B), transB=True)
+    with pytest.raises(Exception):
+        fxp.gemm_unmap(dev(A), dev(B), e[0:1], e[1:2], transB=True, ws=torch.empty(256, dtype=torch.uint8, device="cuda"))
+
+
+def test_long_contraction_forces_slices_on_a_large_output(fxp):
+    """2048 x 2048 outputs are not split along K for speed; past 133144 terms they are, for exactness (two slices of
+    256 x 256 tiles here).  Sampled rows against the oracle, rows of extremes included."""
+    M = N = 2048
+    K = 133248
+    say("long contraction, large output", (M, N, K))
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    A = torch.randint(-127, 128, (M, K), dtype=torch.int8, device="cuda", generator=gen)
+    B = torch.randint(-127, 128, (N, K), dtype=torch.int8, device="cuda", generator=gen)
+    A[7], B[3], B[2040] = 127, 127, -127
+    e = dev(np.array([133, 133], np.int32))                      # one unit = 2^0
+    assert fxp.workspace_bytes(fxp.OP_GEMM, M, N, K) >= 2 * M * N * 4
+    C = host(fxp.gemm_unmap(A, B, e[0:1], e[1:2], transB=True))
+    rows = [0, 7, 255, 256, 1000, 2047]
+    want = oracle.gemm(host(A[rows]), host(B), transB=True)
+    assert want.dtype == np.int64 and int(want[1, 3]) == 16129 * K > 2**31 and int(want[1, 2040]) == -16129 * K
+    assert same_bits(C[rows], oracle.unmap(want, 133, 133))
+
+
+def test_layer_over_more_rows_than_one_int32_sum_holds(fxp):
+    """A linear layer applied to 140 000 rows: the weight gradient contracts over all of them (its reduction rides
+    in the input-gradient launch); one column of X and of dY maps to +-127 in every row, so its sum passes 2^31."""
+    M, K, N = 140000, 64, 48
+    say("long-contraction layer", (M, K, N))
+    rng = np.random.default_rng(12)
+    X = rng.uniform(-1, 1, (M, K)).astype(np.float32)
+    W = (rng.standard_normal((K, N)) * 0.05).astype(np.float32)
+    dY = rng.uniform(-1e-3, 1e-3, (M, N)).astype(np.float32)
+    X[:, 0], dY[:, 0] = 127 / 64, -127 * 2.0 ** -16          # top code in every row (units 2^-6 and 2^-16)
+    X[:, 1], dY[:, 1] = -127 / 64, -127 * 2.0 ** -16
+    for rounding in (0, 1):
+        buf = layer_check_full(fxp, X, W, dY, seed=4, step=9, rounding=rounding)
+    only_dW = fxp.linear_bwd(dev(dY), buf, 4, 9, 1, 8, need_dX=False)[1]
+    assert same_bits(host(only_dW), oracle.linear_bwd(dY, oracle.linear_fwd(X, W, 4, 9, 1, 8)[1], 4, 9, 1, 8)[1])
+    E = int(host(buf.e)[0]) - 133 + int(host(buf.e)[2]) - 133
+    assert 16129 * M > 2**31 and float(host(only_dW)[0, 0]) == float(np.float32(np.ldexp(-16129.0 * M, E)))
+
+
 ABSMAX_SHAPES = [(2560, 2560, 256), (4096, 1536, 128), (300, 200, 160), (100, 90, 50), (256, 128, 8192), (17, 5, 7)]
 
 

@@ -53,6 +53,25 @@ def test_extreme_values_at_the_longest_contraction():
     assert 16129 * 133144 < 2**31 <= 16129 * 133145      # the documented bound on the contraction length
 
 
+def test_contractions_beyond_one_int32_sum_are_summed_exactly():
+    """Past 133144 terms an int32 could wrap; the oracle then returns the exact int64 sums (all operand forms,
+    against numpy's int64 matmul, with rows of +-127 whose sums do exceed 2^31)."""
+    K = oracle.INT32_TERMS + 6857
+    rng = np.random.default_rng(5)
+    A, B = rand_i8(rng, (5, K)), rand_i8(rng, (K, 4))
+    A[0], A[1], B[:, 0] = 127, -127, 127
+    want = A.astype(np.int64) @ B.astype(np.int64)
+    assert want[0, 0] == 16129 * K > 2**31 and want[1, 0] == -16129 * K
+    AT, BT = np.ascontiguousarray(A.T), np.ascontiguousarray(B.T)
+    for C in (oracle.gemm(A, B), oracle.gemm(AT, B, transA=True), oracle.gemm(A, BT, transB=True),
+              oracle.gemm(AT, BT, transA=True, transB=True), oracle.gemm64(A, B)):
+        assert C.dtype == np.int64 and np.array_equal(C, want)
+    # at the bound itself the int32 path is still taken, and the 64-bit one agrees with it
+    A, B = np.full((1, oracle.INT32_TERMS), 127, np.int8), np.full((oracle.INT32_TERMS, 1), 127, np.int8)
+    C = oracle.gemm(A, B)
+    assert C.dtype == np.int32 and int(C[0, 0]) == 16129 * oracle.INT32_TERMS == int(oracle.gemm64(A, B)[0, 0])
+
+
 def test_empty_contraction_gives_zeros():
     C = oracle.gemm(np.zeros((3, 0), np.int8), np.zeros((0, 4), np.int8))
     assert C.shape == (3, 4) and np.all(C == 0)

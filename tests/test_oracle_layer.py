@@ -83,3 +83,22 @@ def test_steps_and_tensors_use_independent_random_streams():
     eW = oracle.scale(W)
     assert not np.array_equal(oracle.map(W, eW, seed=5, stream_id=0), s0["Wq"])
     assert np.array_equal(oracle.map(W, eW, seed=5, stream_id=1), s0["Wq"])
+
+
+def test_weight_gradient_over_more_rows_than_an_int32_sum_holds():
+    """A layer applied to more than 133144 rows: the weight gradient is the exact integer sum (which passes 2^31
+    here: every mapped entry of one column pair is +-127) rounded once - checked against numpy's int64 product
+    and numpy's own double -> float conversion."""
+    M, K, N = oracle.INT32_TERMS + 5000, 3, 2
+    rng = np.random.default_rng(8)
+    X = rng.uniform(-1, 1, (M, K)).astype(np.float32)
+    dY = rng.uniform(-1, 1, (M, N)).astype(np.float32)
+    X[:, 0], dY[:, 0] = 127 / 64, -127 / 64              # mapped to +127 / -127 in every row
+    W = rng.uniform(-1, 1, (K, N)).astype(np.float32)
+    Y, saved = oracle.linear_fwd(X, W, seed=1, step=2, rounding=oracle.NEAREST)
+    dX, dW, aux = oracle.linear_bwd(dY, saved, seed=1, step=2, rounding=oracle.NEAREST)
+    acc = saved["Xq"].astype(np.int64).T @ aux["dYq"].astype(np.int64)
+    assert acc[0, 0] == -16129 * M < -2**31
+    E = (saved["eX"] - 133) + (aux["eG"] - 133)
+    assert np.array_equal(dW, np.ldexp(acc.astype(np.float64), E).astype(np.float32))
+    assert np.array_equal(dX.astype(np.float64), (aux["dYq"].astype(np.int64) @ saved["Wq"].astype(np.int64).T) * 2.0 ** (aux["eG"] - 133 + saved["eW"] - 133))

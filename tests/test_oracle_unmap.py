@@ -63,6 +63,24 @@ def test_single_rounding_ties_to_even_subnormals_and_overflow():
     assert oracle.unmap(np.array([0], np.int32), 254, 254).view(np.uint32)[0] == 0                  # +0.0
 
 
+def test_sums_wider_than_32_bits_are_rounded_once():
+    """int64 sums (contractions beyond 133144 terms): against the exact rational model, ties and all, from
+    sub-normal results to overflow; and equal to the int32 path wherever a value fits both."""
+    rng = np.random.default_rng(3)
+    acc = np.array([(1 << 40) + (1 << 16), (1 << 40) + 3 * (1 << 16), -(1 << 40) - (1 << 16), (1 << 33) + (1 << 9),
+                    (1 << 33) + (1 << 9) + 1, (1 << 33) + (1 << 9) - 1, 2**31, -2**31 - 1, 16129 * 2**31 - 1,
+                    -(16129 * 2**31 - 1), 1, -1, 0], dtype=np.int64)
+    acc = np.concatenate([acc, rng.integers(-2**46, 2**46, 400, dtype=np.int64), rng.integers(-2**33, 2**33, 100, dtype=np.int64)])
+    for eA, eB in [(1, 1), (1, 90), (10, 100), (60, 66), (133, 133), (200, 200), (254, 230), (254, 254)]:
+        E = (eA - 133) + (eB - 133)
+        want = [pymodel.round_to_f32(Fraction(int(a)) * pymodel.pow2(E)) for a in acc]
+        got = oracle.unmap(acc, eA, eB).view(np.uint32).tolist()
+        assert got == want, (eA, eB)
+    assert oracle.unmap(np.array([(1 << 40) + (1 << 16)], np.int64), 133, 133)[0] == float(1 << 40)        # tie -> even
+    small = rng.integers(-2**31, 2**31, 300, dtype=np.int64)
+    assert np.array_equal(oracle.unmap(small, 120, 131).view(np.uint32), oracle.unmap(small.astype(np.int32), 120, 131).view(np.uint32))
+
+
 def test_lower_bit_widths_change_only_the_unit():
     acc = np.array([5, -9], np.int32)
     for bits in (8, 7, 6, 5, 4):
