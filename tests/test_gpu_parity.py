@@ -396,6 +396,20 @@ def test_layer_over_more_rows_than_one_int32_sum_holds(fxp):
     assert 16129 * M > 2**31 and float(host(only_dW)[0, 0]) == float(np.float32(np.ldexp(-16129.0 * M, E)))
 
 
+def test_layer_with_more_input_features_than_one_int32_sum_holds(fxp):
+    """The forward product's contraction (K = 140 032 input features) beyond 133144 terms; one row of X and one
+    column of W at the top code, so that entry of Y passes 2^31 units."""
+    M, K, N = 64, 140032, 32
+    say("long-contraction forward", (M, K, N))
+    rng = np.random.default_rng(13)
+    X = rng.uniform(-1, 1, (M, K)).astype(np.float32)
+    W = rng.uniform(-1, 1, (K, N)).astype(np.float32)
+    dY = rng.uniform(-1, 1, (M, N)).astype(np.float32)
+    X[5], W[:, 7] = 127 / 64, -127 / 64
+    buf = layer_check_full(fxp, X, W, dY, seed=2, step=3)
+    assert float(host(buf.Y)[5, 7]) == float(np.float32(-16129.0 * K * 2.0 ** -12))
+
+
 ABSMAX_SHAPES = [(2560, 2560, 256), (4096, 1536, 128), (300, 200, 160), (100, 90, 50), (256, 128, 8192), (17, 5, 7)]
 
 
