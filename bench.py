@@ -62,6 +62,18 @@ def read_traffic(workload, kernel_class):
     return None
 
 
+def read_step_traffic(name):
+    """HBM bytes per whole step from profiles/<name>.txt (line `HBM bytes per step (...): <bytes>; ...`), or None."""
+    try:
+        with open(os.path.join(ROOT, "profiles", name + ".txt")) as f:
+            for line in f:
+                if line.startswith("HBM bytes per step"):
+                    return float(line.split("):", 1)[1].split(";")[0])
+    except (OSError, ValueError, IndexError):
+        pass
+    return None
+
+
 def repeat_to_target(run_once, target_seconds, most=64):
     """Run the (whole-workload) CPU sample once; when that is far below the target time, repeat it.  Returns
     (repetitions, total seconds)."""
@@ -129,7 +141,7 @@ def bench_conv(args, torch, fxp, synth, dev):
                    "rounding": "stochastic (Philox-4x32-10)", "bits": args.bits},
         "roofline": dict(bound="hbm", achieved=round(gbs, 1), peak=PEAK_HBM_GBS, unit="GB/s",
                          frac=round(gbs / PEAK_HBM_GBS, 4), kernel="whole step (7 launches, all HBM- or launch-bound)",
-                         algorithmic_per_launch=step_bytes, traffic=None),
+                         algorithmic_per_launch=step_bytes, traffic=read_step_traffic("layer_step_c2conv")),
         "cpu_baseline": cpu,
     }))
 
@@ -192,7 +204,7 @@ def bench_attn(args, torch, fxp, synth, dev):
                    "rounding": "stochastic (Philox-4x32-10)", "bits": args.bits},
         "roofline": dict(bound="hbm", achieved=round(gbs, 1), peak=PEAK_HBM_GBS, unit="GB/s",
                          frac=round(gbs / PEAK_HBM_GBS, 4), kernel="whole step (16 kernels, all HBM-bound)",
-                         algorithmic_per_launch=step_bytes, traffic=None),
+                         algorithmic_per_launch=step_bytes, traffic=read_step_traffic("layer_step_vitb_attn")),
         "cpu_baseline": cpu,
     }))
 
@@ -243,7 +255,7 @@ def bench_sgd(args, torch, fxp, synth, dev):
                    "rounding": "stochastic (Philox-4x32-10)", "bits": 16},
         "roofline": dict(bound="hbm", achieved=round(gbs, 1), peak=PEAK_HBM_GBS, unit="GB/s",
                          frac=round(gbs / PEAK_HBM_GBS, 4), kernel="whole step (3 x k_absmax_partials, 3 x k_axpy16)",
-                         algorithmic_per_launch=step_bytes, traffic=None),
+                         algorithmic_per_launch=step_bytes, traffic=read_step_traffic("sgd16_step")),
         "cpu_baseline": cpu,
     }))
 
