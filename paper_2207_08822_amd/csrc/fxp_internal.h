@@ -179,7 +179,7 @@ __device__ inline void transpose4x4(const uint32_t (&o)[4], uint32_t (&t)[4]) {
 // 32x32->64 multiplies with the Weyl key schedule.  Element i of a tensor stream uses word i % 4 of the
 // block with counter (i / 4, stream id) and key = seed.
 // a ^ b ^ c in one instruction (three-input bit operation with the parity truth table); the compiler
-// leaves two v_xor_b32 when one input is wave-uniform, and the map kernels are bound by VALU issue
+// leaves two v_xor_b32 when one input is wave-uniform, and the map kernels spend most of their VALU issue slots in these rounds
 __device__ inline uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) { return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96); }
 
 __device__ inline uint4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1) {
