@@ -9,7 +9,12 @@
 
 namespace fxp {
 
-constexpr int kMaxPartials = 1024;        // per-block maxima of the scale reduction (uint32 each)
+constexpr int kMaxPartials = 1024;        // capacity of a block-maxima scratch area (uint32 each)
+// Workgroups of a scale reduction: one per CU, four 16-byte loads in flight per thread.  More requests in flight
+// make the reduction slower, not faster (8192^3 layer, the step's two reductions over 805 MB: 147 us with 1024
+// workgroups, 124 with two loads per thread, 115-117 with 256 workgroups x 4 loads, 512 x 2 or 1024 x 1 = 6.9 TB/s;
+// 215 us with 256 x 1).
+constexpr int kScaleBlocks = 256;
 constexpr int kScaleThreads = 256;
 constexpr size_t kScaleWsBytes = kMaxPartials * sizeof(uint32_t);
 constexpr int64_t kMaxContraction = 133144;   // 127^2 * K < 2^31: the longest contraction one int32 sum can hold
@@ -28,7 +33,7 @@ int scale_partials(const float* x, size_t n, uint32_t* partials, int* n_partials
 int scale_partials2(const float* x0, size_t n0, uint32_t* partials0, int* n_partials0, const float* x1, size_t n1,
                     uint32_t* partials1, int* n_partials1, hipStream_t s);
 int scale_finish(const uint32_t* partials, int n_partials, int32_t* e_max, hipStream_t s);
-int scale_partial_count(size_t n);     // block maxima a reduction over n elements leaves (<= kMaxPartials)
+int scale_partial_count(size_t n);     // block maxima a reduction over n elements leaves (<= kScaleBlocks)
 
 // One tensor to map: x[rows, cols] fp32 -> q (row-major) and / or qT (transposed), either may be null.  The
 // scale comes from e_in (device) or, when partials is given, from the block maxima of a scale reduction, in

@@ -29,10 +29,10 @@ __global__ __launch_bounds__(kScaleThreads) void k_absmax_finish(const uint32_t*
     if (threadIdx.x == 0) e_max[0] = max(1, static_cast<int>(m >> 23));
 }
 
-// 16K elements or more per block (the map kernel re-reads every block maximum), at most kMaxPartials
+// 16K elements or more per block (the map kernel re-reads every block maximum), at most kScaleBlocks
 int scale_partial_count(size_t n) {
     const size_t want = (n + 16383) / 16384;
-    return static_cast<int>(want < 1 ? 1 : (want > kMaxPartials ? kMaxPartials : want));
+    return static_cast<int>(want < 1 ? 1 : (want > kScaleBlocks ? kScaleBlocks : want));
 }
 
 int scale_partials(const float* x, size_t n, uint32_t* partials, int* n_partials, hipStream_t s) {
