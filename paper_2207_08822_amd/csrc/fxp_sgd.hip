@@ -310,10 +310,14 @@ __global__ __launch_bounds__(kAxpyThreads) void k_axpy16_multi(const SgdJobs job
                                   line_step, bid, J.blocks, red);
 }
 
-// grid of one line over n elements: at most kMaxPartials blocks, so that pz fits a scale scratch area
+// grid of one line over n elements: at most kAxpyBlocks workgroups (three per CU: 0.1104 -> 0.1066 ms per step
+// of 11.7 M parameters against 1024; 512: 0.107, 384: 0.122 - the kernel is bound by VALU issue and needs the
+// waves, the memory system prefers fewer requests in flight); pz fits a scale scratch area (kMaxPartials words)
+constexpr int kAxpyBlocks = 768;
+static_assert(kAxpyBlocks <= kMaxPartials, "block maxima of z go to a scale scratch area");
 static int axpy_grid(uint64_t n) {
     const uint64_t want = (((n + 3) >> 2) + kAxpyThreads - 1) / kAxpyThreads;
-    return static_cast<int>(want < 1 ? 1 : (want > kMaxPartials ? kMaxPartials : want));
+    return static_cast<int>(want < 1 ? 1 : (want > kAxpyBlocks ? kAxpyBlocks : want));
 }
 
 // one line; px / py: block maxima of x / y (npx / npy of them); pz receives axpy_grid(n) block maxima of z
@@ -411,7 +415,8 @@ extern "C" int fxp_sgd16_step(float* w, const float* g, float* v, size_t n, floa
 }
 
 namespace fxp {
-// workgroups of one tensor in every launch of a multi-tensor step: eight quads or more per thread, at most 1024
+// workgroups of one tensor in every launch of a multi-tensor step: eight quads or more per thread (6: slower, 12 and
+// 16: the same, 24: slower), at most 1024
 static uint32_t multi_blocks(size_t n) {
     const uint64_t want = (((static_cast<uint64_t>(n) + 3) >> 2) + kAxpyThreads * 8 - 1) / (kAxpyThreads * 8);
     return static_cast<uint32_t>(want < 1 ? 1 : (want > 1024 ? 1024 : want));
