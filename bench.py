@@ -26,7 +26,8 @@ if ROOT not in sys.path:
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, published
 PEAK_INT8_TOPS = 5000.0      # MI355X dense int8 MFMA, published (5.0 POP/s)
 RIDGE_OPS_PER_BYTE = PEAK_INT8_TOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
-# ceilings measured on the box with plain kernels (profiles/ceilings.md): streaming copy of 4 GiB, register-only MFMA loop
+# ceilings measured on the box with plain kernels (profiles/ceilings.md): streaming copy beyond the Infinity Cache
+# (5.3-5.9 TB/s over sizes and runs), register-only MFMA loop
 MEASURED_HBM_GBS = 5766.0
 MEASURED_INT8_TOPS = 4877.5
 

@@ -109,23 +109,33 @@ int main() {
         CK(hipMalloc(&y, bytes));
         CK(hipMemset(x, 1, bytes));
         CK(hipMemset(y, 0, bytes));
-        k_read<<<16384, 256>>>(x, nvec, out);
-        CK(hipDeviceSynchronize());
-        CK(hipEventRecord(e0));
-        for (int r = 0; r < 10; ++r) k_read<<<16384, 256>>>(x, nvec, out);
-        CK(hipEventRecord(e1));
-        CK(hipEventSynchronize(e1));
-        CK(hipEventElapsedTime(&ms, e0, e1));
-        printf("hbm read  %5zu MiB: %7.1f GB/s\n", mb, bytes * 10.0 / (ms * 1e-3) / 1e9);
-        const int grid = static_cast<int>(nvec / 256 > 262144 ? 262144 : nvec / 256);
-        k_copy<<<grid, 256>>>(x, y, nvec);
-        CK(hipDeviceSynchronize());
-        CK(hipEventRecord(e0));
-        for (int r = 0; r < 10; ++r) k_copy<<<grid, 256>>>(x, y, nvec);
-        CK(hipEventRecord(e1));
-        CK(hipEventSynchronize(e1));
-        CK(hipEventElapsedTime(&ms, e0, e1));
-        printf("hbm copy  %5zu MiB: %7.1f GB/s (read + write)\n", mb, 2.0 * bytes * 10 / (ms * 1e-3) / 1e9);
+        // The rate depends on how many requests are in flight: sweep the grid (every thread keeps four 16-byte
+        // loads, or one load and one store, in flight) and report every point; the best one is the ceiling.
+        double best_r = 0, best_c = 0;
+        int best_rg = 0, best_cg = 0;
+        for (int grid : {256, 512, 1024, 4096, 16384}) {
+            k_read<<<grid, 256>>>(x, nvec, out);
+            CK(hipDeviceSynchronize());
+            CK(hipEventRecord(e0));
+            for (int r = 0; r < 10; ++r) k_read<<<grid, 256>>>(x, nvec, out);
+            CK(hipEventRecord(e1));
+            CK(hipEventSynchronize(e1));
+            CK(hipEventElapsedTime(&ms, e0, e1));
+            const double rd = bytes * 10.0 / (ms * 1e-3) / 1e9;
+            k_copy<<<grid, 256>>>(x, y, nvec);
+            CK(hipDeviceSynchronize());
+            CK(hipEventRecord(e0));
+            for (int r = 0; r < 10; ++r) k_copy<<<grid, 256>>>(x, y, nvec);
+            CK(hipEventRecord(e1));
+            CK(hipEventSynchronize(e1));
+            CK(hipEventElapsedTime(&ms, e0, e1));
+            const double cp = 2.0 * bytes * 10 / (ms * 1e-3) / 1e9;
+            printf("hbm %5zu MiB, %5d workgroups: read %7.1f GB/s   copy %7.1f GB/s (read + write)\n", mb, grid, rd, cp);
+            if (rd > best_r) { best_r = rd; best_rg = grid; }
+            if (cp > best_c) { best_c = cp; best_cg = grid; }
+        }
+        printf("hbm %5zu MiB best: read %7.1f GB/s (%d workgroups)   copy %7.1f GB/s (%d workgroups)\n", mb, best_r, best_rg,
+               best_c, best_cg);
         CK(hipFree(x));
         CK(hipFree(y));
     }
