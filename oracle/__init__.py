@@ -21,7 +21,10 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        path = _build.LIB if os.path.exists(_build.LIB) else _build.build()
+        if os.environ.get("FXP_REF_SANITIZE") == "1":      # the AddressSanitizer + UBSan build (tests only)
+            path = _build.build(force=False, sanitize=True)
+        else:
+            path = _build.LIB if os.path.exists(_build.LIB) else _build.build()
         L = ctypes.CDLL(path)
         c = ctypes
         vp, i32, i64, u64, u32 = c.c_void_p, c.c_int32, c.c_int64, c.c_uint64, c.c_uint32

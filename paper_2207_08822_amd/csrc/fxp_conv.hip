@@ -400,6 +400,10 @@ extern "C" int fxp_conv2d_bwd(const float* dY, const fxp_conv_saved* saved, cons
         return FXP_ERR_NULL;
     if (!ws || ws_bytes < conv_ws_bwd(g)) return FXP_ERR_WORKSPACE;
     if (!aligned(ws, 256) || !aligned(dY, 4) || !aligned(dX, 16) || !aligned(dW, 4)) return FXP_ERR_ALIGN;
+    // the patch, flip and product kernels of this call read and write these with 4- and 16-byte accesses
+    if (!aligned(saved->Xq, 16) || !aligned(saved->Wq, 16) || !aligned(saved->WqT, 16) || !aligned(saved->WqF, 16) ||
+        !aligned(dYq, 16) || !aligned(dYqT, 16) || !aligned(saved->eX, 4) || !aligned(saved->eW, 4) || !aligned(e_dY, 4))
+        return FXP_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint8_t* w8 = static_cast<uint8_t*>(ws);
     uint8_t* area = w8 + round_up(kScaleWsBytes, 256);

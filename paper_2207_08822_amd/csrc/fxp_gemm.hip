@@ -1009,9 +1009,13 @@ static GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K) {
     return long_contraction(p, K);
 }
 
+// elements between two workspace slices of an M x N product: a multiple of 4, so that every slice starts 16-byte
+// aligned and the reduction can read all of them in 16-byte pieces
+static int64_t slice_stride(int64_t M, int64_t N) { return (M * N + 3) / 4 * 4; }
+
 size_t gemm_split_ws_bytes(int64_t M, int64_t N, int64_t K) {
     const GemmPlan p = plan_gemm(M, N, K);
-    return p.splits > 1 ? round_up(static_cast<size_t>(p.splits) * M * N * sizeof(int32_t), 256) : 0;
+    return p.splits > 1 ? round_up(static_cast<size_t>(p.splits) * slice_stride(M, N) * sizeof(int32_t), 256) : 0;
 }
 
 // `batch` products of one shape in one launch (grid.z), never split along K.
@@ -1093,7 +1097,7 @@ int gemm_nt_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda
     const int first_mode = splits > 1 ? (to_ws ? kStoreI32 : kAtomicI32) : (fp32_out ? kStoreF32 : kStoreI32);
     void* dst = to_ws ? ws : C;
     const int64_t dst_ld = to_ws ? N : ldc;
-    const int64_t split_stride = to_ws ? M * N : 0;
+    const int64_t split_stride = to_ws ? slice_stride(M, N) : 0;
     // beyond kMaxContraction only the 64-bit sum of workspace slices is exact
     if (K > kMaxContraction && !(to_ws && fp32_out)) return FXP_ERR_OVERFLOW;
     int hr, hc;
@@ -1130,7 +1134,7 @@ int gemm_nt_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda
         ReduceRider r;
         r.parts = static_cast<const int32_t*>(ws);
         r.splits = slices;
-        r.stride = M * N;
+        r.stride = split_stride;
         r.M = static_cast<int>(M);
         r.N = static_cast<int>(N);
         r.C = C;

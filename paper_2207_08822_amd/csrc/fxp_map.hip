@@ -309,7 +309,8 @@ static MapPlan plan_map(const MapTensor& t) {
     auto count = [&](int64_t tile_rows) { return ((t.rows + tile_rows - 1) / tile_rows) * tiles_c; };
     p.passes = count(tall) >= 1024 ? 4 : (count(tall / 2) >= 1024 ? 2 : 1);
     p.tile_path = (t.cols % 4 == 0) && aligned(t.x, 16) && (!t.q || aligned(t.q, 16)) && (!t.qT || aligned(t.qT, 16)) &&
-                  t.rows > 0 && count(tall / 4) < (int64_t{1} << 30) && t.cols < (int64_t{1} << 22);   // 32-bit offsets inside a tile
+                  t.rows > 0 && count(tall / 4) < (int64_t{1} << 30) && t.cols < (int64_t{1} << 22) &&   // 32-bit offsets inside a tile
+                  t.rows < (int64_t{1} << 32);                        // and a 32-bit row count in the transposed copy's addressing
     return p;
 }
 

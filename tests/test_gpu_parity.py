@@ -260,7 +260,9 @@ def test_gemm_split_k_both_ways_and_deterministic(fxp):
     """Long contraction, small output: slices of K go to the workspace and are summed by a
     second pass; with no room for the slices they add into the output with int32 atomics."""
     rng = np.random.default_rng(1)
-    for (M, N, K) in [(256, 128, 8192), (512, 768, 6208)]:
+    # (33, 65, 4096) and (5, 3, 2064): M * N is odd, so the slices after the first start off a 16-byte boundary
+    # unless the slice stride is padded
+    for (M, N, K) in [(256, 128, 8192), (512, 768, 6208), (33, 65, 4096), (5, 3, 2064)]:
         Ah, Bh = rand_i8(rng, (M, K)), rand_i8(rng, (N, K))
         want = oracle.gemm(Ah, Bh, transB=True)
         A, B = dev(Ah), dev(Bh)
@@ -487,6 +489,7 @@ def test_layer_random_shapes(fxp):
             M, K, N = (max(16, v // 16 * 16) for v in (M, K, N))
         shapes.append((M, K, N))
     shapes += [(1040, 208, 464), (4112, 80, 1040), (272, 4240, 144)]      # several tiles, ragged, K tails, split-K
+    shapes += [(4096, 33, 65), (4112, 48, 17)]      # weight gradient split into slices of odd size, summed in the dX launch
     for (M, K, N) in shapes:
         say("layer random", (M, K, N))
         X = rng.standard_normal((M, K)).astype(np.float32)

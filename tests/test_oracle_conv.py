@@ -50,9 +50,43 @@ def test_gradients_are_the_exact_adjoints(N, H, W, C, Cout, KH, KW, stride, pad)
     dW = oracle.conv2d_bwd_weight_acc(Xq, Gq, Wq.shape, stride, pad).astype(np.int64)
     assert int((dX * Xq).sum()) == lhs
     assert int((dW * Wq).sum()) == lhs
-    # and element-wise against numpy: dW = col^T G, dX by finite "unit impulse" probing on a tiny case
+    # and element-wise against numpy: dW = col^T G
     col, _ = im2col_numpy(Xq, KH, KW, stride, pad)
     assert np.array_equal(dW.reshape(Cout, -1), Gq.reshape(-1, Cout).astype(np.int64).T @ col)
+
+
+def col2im_numpy(dcol, x_shape, KH, KW, stride, pad):
+    """Independent scatter: patch-gradient rows [N*Ho*Wo, KH*KW*C] added back onto the zero-padded image, one
+    filter tap at a time with strided slices; the padding rim is cut off at the end."""
+    N, H, W, C = x_shape
+    Ho, Wo = (H + 2 * pad - KH) // stride + 1, (W + 2 * pad - KW) // stride + 1
+    P = np.zeros((N, H + 2 * pad, W + 2 * pad, C), dtype=np.int64)
+    d = dcol.reshape(N, Ho, Wo, KH, KW, C)
+    for kh in range(KH):
+        for kw in range(KW):
+            P[:, kh:kh + stride * Ho:stride, kw:kw + stride * Wo:stride, :] += d[:, :, :, kh, kw, :]
+    return P[:, pad:pad + H, pad:pad + W, :]
+
+
+@pytest.mark.parametrize("N,H,W,C,Cout,KH,KW,stride,pad", CASES)
+def test_input_gradient_element_by_element(N, H, W, C, Cout, KH, KW, stride, pad):
+    """dX against a numpy construction that shares nothing with the oracle's loops: the patch gradient
+    G[M, Cout] . W[Cout, KH*KW*C] by matmul, scattered back by col2im; and, for every input element of the
+    smallest cases, against the definition dX[x] = d<conv(X, W), G>/dX[x] taken with a unit impulse."""
+    rng = np.random.default_rng(11 + N + 3 * H + 5 * KH)
+    Wq = rand_i8(rng, (Cout, KH, KW, C))
+    Ho, Wo = (H + 2 * pad - KH) // stride + 1, (W + 2 * pad - KW) // stride + 1
+    Gq = rand_i8(rng, (N, Ho, Wo, Cout))
+    got = oracle.conv2d_bwd_input_acc(Gq, Wq, (N, H, W, C), stride, pad).astype(np.int64)
+    dcol = Gq.reshape(-1, Cout).astype(np.int64) @ Wq.reshape(Cout, -1).astype(np.int64)
+    want = col2im_numpy(dcol, (N, H, W, C), KH, KW, stride, pad)
+    assert got.shape == want.shape and np.array_equal(got, want)
+    if N * H * W * C <= 200:
+        for idx in np.ndindex(N, H, W, C):
+            impulse = np.zeros((N, H, W, C), np.int8)
+            impulse[idx] = 1
+            y = oracle.conv2d_fwd_acc(impulse, Wq, stride, pad).astype(np.int64)
+            assert int((y * Gq).sum()) == got[idx], idx
 
 
 def test_special_kernels():
