@@ -195,6 +195,22 @@ typedef struct fxp_saved {
 int fxp_linear_fwd(const float* X, const float* W, int64_t M, int64_t K, int64_t N, float* Y, const fxp_saved* saved,
                    uint64_t seed, uint64_t step, int rounding, int bits, void* ws, size_t ws_bytes, void* stream);
 
+/* fxp_linear_fwd for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation.  Same arguments without ws, same results bit
+ * for bit; the call allocates and frees nothing.  Its scratch (block maxima of the two scale reductions, int32
+ * slices of a product that is split along its contraction) is a device array of FXP_STATIC_SCRATCH_BYTES bytes
+ * inside the library, one copy per GPU, held until the process ends.  A layer that needs more -
+ * fxp_workspace_bytes(FXP_OP_LINEAR_FWD, M, N, K) > FXP_STATIC_SCRATCH_BYTES, which only long contractions into
+ * small outputs reach - returns FXP_ERR_WORKSPACE and enqueues nothing.  All calls on one GPU share that GPU's
+ * array: two calls whose work overlaps in time on one GPU (different streams, or different threads) race;
+ * calls on one stream are ordered and safe.  The array's previous contents never matter (every word read was
+ * written by the same call).  The first call on a device looks the array's address up (no allocation), so make
+ * one call per device before a capture begins. */
+#define FXP_STATIC_SCRATCH_BYTES (32u << 20)
+size_t fxp_static_scratch_bytes(void);
+int fxp_linear_fwd_static(const float* X, const float* W, int64_t M, int64_t K, int64_t N, float* Y, const fxp_saved* saved,
+                          uint64_t seed, uint64_t step, int rounding, int bits, void* stream);
+
 /* Backward of the same layer (App. A.2: dL/dW = X_hat^T G_hat; chain rule for
  * dL/dX = G_hat W_hat^T): scale + map dY ONCE (FXP_TAG_DY; both GEMMs use the
  * same rounded gradient), then dX[M,K] and dW[K,N] as fp32.  dX or dW may be

@@ -7,6 +7,7 @@
 //   Y  = Xq  [M,K] x WqT [N,K]^T      dX = dYq [M,N] x Wq [K,N]^T
 //   dW = XqT [K,M] x dYqT[N,M]^T
 #include <algorithm>
+#include <mutex>
 
 #include "fxp_internal.h"
 
@@ -58,25 +59,95 @@ extern "C" size_t fxp_workspace_bytes(int op, int64_t M, int64_t N, int64_t K) {
     }
 }
 
+namespace fxp {
+
+// argument checks of the forward call that need no workspace
+static int check_linear_fwd(const float* X, const float* W, int64_t M, int64_t K, int64_t N, const float* Y,
+                            const fxp_saved* saved, int rounding, int bits) {
+    if (M <= 0 || K <= 0 || N <= 0) return FXP_ERR_DIMS;
+    if (M >= (int64_t{1} << 31) || N >= (int64_t{1} << 31) || K >= (int64_t{1} << 31)) return FXP_ERR_DIMS;
+    if (rounding != FXP_ROUND_STOCHASTIC && rounding != FXP_ROUND_NEAREST) return FXP_ERR_ROUNDING;
+    if (bits < 2 || bits > 8) return FXP_ERR_BITS;
+    if (!X || !W || !Y || !saved || !saved->Xq || !saved->XqT || !saved->Wq || !saved->WqT || !saved->eX || !saved->eW)
+        return FXP_ERR_NULL;
+    if (!aligned(X, 4) || !aligned(W, 4) || !aligned(Y, 4) || !aligned(saved->eX, 4) || !aligned(saved->eW, 4))
+        return FXP_ERR_ALIGN;
+    return FXP_OK;
+}
+
+// the forward pass itself: arguments validated, ws of fxp_workspace_bytes(FXP_OP_LINEAR_FWD) bytes or more
+static int linear_fwd_run(const float* X, const float* W, int64_t M, int64_t K, int64_t N, float* Y, const fxp_saved* saved,
+                          uint64_t seed, uint64_t step, int rounding, int bits, void* ws, size_t ws_bytes, hipStream_t s) {
+    uint32_t* pX = static_cast<uint32_t*>(ws);
+    uint32_t* pW = pX + round_up(kScaleWsBytes, 256) / sizeof(uint32_t);
+    const MapTensor tX{X, M, K, nullptr, pX, 0, saved->eX, saved->Xq, saved->XqT, (step << 8) | FXP_TAG_X};
+    const MapTensor tW{W, K, N, nullptr, pW, 0, saved->eW, saved->Wq, saved->WqT, (step << 8) | FXP_TAG_W};
+    int rc = scale_and_map2(tX, tW, seed, rounding, bits, s);
+    if (rc) return rc;
+    uint8_t* rest = static_cast<uint8_t*>(ws) + 2 * round_up(kScaleWsBytes, 256);
+    return gemm_nt_launch(M, N, K, saved->Xq, K, saved->WqT, K, Y, N, true, saved->eX, bits, saved->eW, bits, rest,
+                          ws_bytes - 2 * round_up(kScaleWsBytes, 256), s);
+}
+
+}  // namespace fxp
+
 extern "C" int fxp_linear_fwd(const float* X, const float* W, int64_t M, int64_t K, int64_t N, float* Y,
                               const fxp_saved* saved, uint64_t seed, uint64_t step, int rounding, int bits, void* ws,
                               size_t ws_bytes, void* stream) {
     using namespace fxp;
     int rc = check_layer(M, K, N, rounding, bits, ws, ws_bytes, fxp_workspace_bytes(FXP_OP_LINEAR_FWD, M, N, K));
     if (rc) return rc;
-    if (!X || !W || !Y || !saved || !saved->Xq || !saved->XqT || !saved->Wq || !saved->WqT || !saved->eX || !saved->eW)
-        return FXP_ERR_NULL;
-    if (!aligned(X, 4) || !aligned(W, 4) || !aligned(Y, 4) || !aligned(saved->eX, 4) || !aligned(saved->eW, 4))
-        return FXP_ERR_ALIGN;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    uint32_t* pX = static_cast<uint32_t*>(ws);
-    uint32_t* pW = pX + round_up(kScaleWsBytes, 256) / sizeof(uint32_t);
-    const MapTensor tX{X, M, K, nullptr, pX, 0, saved->eX, saved->Xq, saved->XqT, (step << 8) | FXP_TAG_X};
-    const MapTensor tW{W, K, N, nullptr, pW, 0, saved->eW, saved->Wq, saved->WqT, (step << 8) | FXP_TAG_W};
-    if ((rc = scale_and_map2(tX, tW, seed, rounding, bits, s))) return rc;
-    uint8_t* rest = static_cast<uint8_t*>(ws) + 2 * round_up(kScaleWsBytes, 256);
-    return gemm_nt_launch(M, N, K, saved->Xq, K, saved->WqT, K, Y, N, true, saved->eX, bits, saved->eW, bits, rest,
-                          ws_bytes - 2 * round_up(kScaleWsBytes, 256), s);
+    if ((rc = check_linear_fwd(X, W, M, K, N, Y, saved, rounding, bits))) return rc;
+    return linear_fwd_run(X, W, M, K, N, Y, saved, seed, step, rounding, bits, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+// ---- the forward pass for callers that cannot allocate -------------------------------------------------------
+// The scratch of fxp_linear_fwd (two areas of block maxima, and the int32 slices of a product that is split along
+// its contraction) lives in this device array instead of a caller's workspace.  Every GPU the library runs on
+// holds its own copy of the array at its own address until the process ends; the array's name is only a
+// host-side handle, so its device address is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[FXP_STATIC_SCRATCH_BYTES];
+
+namespace fxp {
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];     // device address of `scratch` on each device, null until looked up
+static std::mutex g_scratch_lock;
+
+// the current device's copy of the array (looked up on the first call on that device), or null on failure
+static void* static_scratch() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
+
+}  // namespace fxp
+
+extern "C" size_t fxp_static_scratch_bytes(void) { return FXP_STATIC_SCRATCH_BYTES; }
+
+extern "C" int fxp_linear_fwd_static(const float* X, const float* W, int64_t M, int64_t K, int64_t N, float* Y,
+                                     const fxp_saved* saved, uint64_t seed, uint64_t step, int rounding, int bits,
+                                     void* stream) {
+    using namespace fxp;
+    int rc = check_linear_fwd(X, W, M, K, N, Y, saved, rounding, bits);
+    if (rc) return rc;
+    // a layer whose scratch does not fit the array is refused before anything touches the device
+    if (fxp_workspace_bytes(FXP_OP_LINEAR_FWD, M, N, K) > FXP_STATIC_SCRATCH_BYTES) return FXP_ERR_WORKSPACE;
+    void* ws = static_scratch();
+    if (ws == nullptr) return FXP_ERR_LAUNCH;
+    // nothing in the array has to start at zero: the reduction writes every block maximum the map kernel reads,
+    // and every slice element is stored by the product before the sum of the slices reads it
+    return linear_fwd_run(X, W, M, K, N, Y, saved, seed, step, rounding, bits, ws, FXP_STATIC_SCRATCH_BYTES,
+                          static_cast<hipStream_t>(stream));
 }
 
 extern "C" int fxp_linear_bwd(const float* dY, const fxp_saved* saved, int64_t M, int64_t K, int64_t N, float* dX,

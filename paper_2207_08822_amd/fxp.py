@@ -76,6 +76,10 @@ def lib():
     L.fxp_map_absmax.argtypes = [vp, i64, i64, vp, vp, vp, vp, u64, u64, ci, ci, vp]
     L.fxp_linear_fwd.argtypes = [vp, vp, i64, i64, i64, vp, c.POINTER(_Saved), u64, u64, ci, ci, vp, sz, vp]
     L.fxp_linear_bwd.argtypes = [vp, c.POINTER(_Saved), i64, i64, i64, vp, vp, vp, vp, vp, u64, u64, ci, ci, vp, sz, vp]
+    L.fxp_linear_fwd_static.argtypes = [vp, vp, i64, i64, i64, vp, c.POINTER(_Saved), u64, u64, ci, ci, vp]
+    L.fxp_linear_fwd_static.restype = ci
+    L.fxp_static_scratch_bytes.restype = sz
+    L.fxp_static_scratch_bytes.argtypes = []
     L.fxp_conv2d_workspace_bytes.restype = sz
     L.fxp_conv2d_workspace_bytes.argtypes = [c.POINTER(_ConvShape), ci]
     L.fxp_conv2d_fwd.argtypes = [vp, vp, c.POINTER(_ConvShape), vp, c.POINTER(_ConvSaved), u64, u64, ci, ci, vp, sz, vp]
@@ -285,6 +289,17 @@ def linear_fwd(X, W, buf, seed=0, step=0, rounding=STOCHASTIC, bits=8):
         raise FxpError("shapes do not match the layer buffers")
     _check(lib().fxp_linear_fwd(_p(X), _p(W), M, K, buf.N, _p(buf.Y), ctypes.byref(buf.saved), seed, step, rounding,
                                 bits, _p(buf.ws), buf.ws.numel(), _stream()), "fxp_linear_fwd")
+    return buf.Y
+
+
+def linear_fwd_static(X, W, buf, seed=0, step=0, rounding=STOCHASTIC, bits=8):
+    """linear_fwd through the entry point that takes no workspace (its scratch is a device array inside the library)."""
+    X, W = _dev(X, torch.float32, "X"), _dev(W, torch.float32, "W")
+    M, K = X.shape
+    if W.shape[0] != K or (M, K, W.shape[1]) != (buf.M, buf.K, buf.N):
+        raise FxpError("shapes do not match the layer buffers")
+    _check(lib().fxp_linear_fwd_static(_p(X), _p(W), M, K, buf.N, _p(buf.Y), ctypes.byref(buf.saved), seed, step, rounding,
+                                       bits, _stream()), "fxp_linear_fwd_static")
     return buf.Y
 
 
