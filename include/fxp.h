@@ -346,6 +346,14 @@ int fxp_conv2d_bwd(const float* dY, const fxp_conv_saved* saved, const fxp_conv2
                    int8_t* dYq, int8_t* dYqT, int32_t* e_dY, uint64_t seed, uint64_t step, int rounding, int bits,
                    void* ws, size_t ws_bytes, void* stream);
 
+/* ---- measurement helper (not a step of the method) ----
+ * Core clock while other work runs: enqueues one wave on `stream` (use a stream of its own, next to the kernels
+ * under test) that stays alive for `microseconds` (1 .. 1000000) of the constant 100 MHz counter and then writes
+ * out[0] = ticks of that counter, out[1] = core clock cycles in the same interval (device, 2 x uint64, 8-byte
+ * aligned): core clock in MHz = 100 * out[1] / out[0].  The compute-bound products of Sec. 3.3 run the chip
+ * into its power limit, so their rate is reported next to the clock they ran at. */
+int fxp_clock_probe(uint64_t* out, uint32_t microseconds, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

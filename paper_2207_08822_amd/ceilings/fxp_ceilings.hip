@@ -11,8 +11,12 @@
 // Build: python -m paper_2207_08822_amd.build --ceilings ; run: paper_2207_08822_amd/ceilings/fxp_ceilings
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+#include <cmath>
 #include <cstdint>
 #include <cstdio>
+#include <random>
+#include <vector>
 
 #define CK(x)                                                                        \
     do {                                                                             \
@@ -63,6 +67,55 @@ __global__ __launch_bounds__(256) void k_mfma(int* out, int iters, int seed) {
     for (int n = 0; n < 8; ++n)
         for (int r = 0; r < 16; ++r) s += acc[n][r];
     if (s == 0x7fffffff) out[0] = s;
+}
+
+// The same loop with operands that change with every instruction, as in a real product: every lane holds eight A
+// and eight B fragments (loaded once from memory) and walks through the pairings.  With all-equal operand words
+// the matrix cores toggle few bits; with the int8 values a mapped tensor holds they draw enough power to pull the
+// core clock down, which is the ceiling a product kernel on such data can at best reach.
+template <bool SHAPE16>
+__global__ __launch_bounds__(256) void k_mfma_data(const v4i* __restrict__ ops, int* out, int iters) {
+    const v4i* mine = ops + (static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x) * 16;
+    v4i a[8], b[8];
+    for (int n = 0; n < 8; ++n) { a[n] = mine[n]; b[n] = mine[8 + n]; }
+    int s = 0;
+    if (SHAPE16) {
+        v4i acc[8];
+        for (int n = 0; n < 8; ++n) acc[n] = v4i{0, 0, 0, 0};
+        for (int i = 0; i < iters; ++i) {
+#pragma unroll
+            for (int r = 0; r < 8; ++r)
+#pragma unroll
+                for (int n = 0; n < 8; ++n) acc[n] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[(n + r) & 7], b[n], acc[n], 0, 0, 0);
+        }
+        for (int n = 0; n < 8; ++n)
+            for (int r = 0; r < 4; ++r) s += acc[n][r];
+    } else {
+        v16i acc[8];
+        for (int n = 0; n < 8; ++n)
+            for (int r = 0; r < 16; ++r) acc[n][r] = 0;
+        for (int i = 0; i < iters; ++i) {
+#pragma unroll
+            for (int r = 0; r < 8; ++r)
+#pragma unroll
+                for (int n = 0; n < 8; ++n) acc[n] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[(n + r) & 7], b[n], acc[n], 0, 0, 0);
+        }
+        for (int n = 0; n < 8; ++n)
+            for (int r = 0; r < 16; ++r) s += acc[n][r];
+    }
+    if (s == 0x7fffffff) out[0] = s;
+}
+
+// one wave counts core-clock cycles against the constant 100 MHz counter for `ticks` of the latter
+__global__ void k_clock(unsigned long long* out, unsigned long long ticks) {
+    const unsigned long long t0 = wall_clock64(), c0 = clock64();
+    unsigned long long t1 = t0;
+    for (int i = 0; i < (1 << 22) && t1 - t0 < ticks; ++i) {
+        __builtin_amdgcn_s_sleep(32);
+        t1 = wall_clock64();
+    }
+    out[0] = t1 - t0;
+    out[1] = clock64() - c0;
 }
 
 // every block walks a panel of `rows` rows x K bytes (row stride ld), BK bytes per row per step;
@@ -150,6 +203,55 @@ int main() {
     CK(hipEventElapsedTime(&ms, e0, e1));
     printf("int8 mfma 32x32x32 from registers, 2 waves/SIMD, %.0f ms: %7.1f TOP/s\n", ms,
            20.0 * 512 * 4 * iters * 8 * 65536.0 / (ms * 1e-3) / 1e12);
+
+    {
+        // operand bits: all bytes equal; the int8 values of a mapped N(0,1) tensor whose largest magnitude is near
+        // 5.7 (one unit = 1/16, so the values are N(0,16) rounded); uniform over [-127, 127]
+        const size_t nops = static_cast<size_t>(512) * 256 * 16;
+        std::vector<int8_t> h(nops * 16);
+        v4i* ops;
+        unsigned long long* clk;
+        hipStream_t side;
+        CK(hipMalloc(&ops, nops * 16));
+        CK(hipMalloc(&clk, 16));
+        CK(hipStreamCreateWithFlags(&side, hipStreamNonBlocking));
+        std::mt19937_64 rng(12345);
+        std::normal_distribution<double> gauss(0.0, 16.0);
+        std::uniform_int_distribution<int> uni(-127, 127);
+        const char* names[3] = {"all bytes equal", "mapped N(0,1) tensor", "uniform int8"};
+        for (int kind = 0; kind < 3; ++kind) {
+            for (auto& v : h) {
+                if (kind == 0) v = 1;
+                else if (kind == 1) v = static_cast<int8_t>(std::max(-127.0, std::min(127.0, std::nearbyint(gauss(rng)))));
+                else v = static_cast<int8_t>(uni(rng));
+            }
+            CK(hipMemcpy(ops, h.data(), nops * 16, hipMemcpyHostToDevice));
+            for (int shape16 = 0; shape16 < 2; ++shape16) {
+                const int it = shape16 ? 4 * 2500 : 2500;        // 64 instructions per iteration
+                auto launch = [&] {
+                    if (shape16) k_mfma_data<true><<<512, 256>>>(ops, reinterpret_cast<int*>(out), it);
+                    else k_mfma_data<false><<<512, 256>>>(ops, reinterpret_cast<int*>(out), it);
+                };
+                launch();
+                CK(hipDeviceSynchronize());
+                for (int r = 0; r < 5; ++r) launch();               // lead-in: the clock settles under load
+                CK(hipEventRecord(e0));
+                k_clock<<<1, 64, 0, side>>>(clk, 2000 * 100ull);     // 2 ms
+                for (int r = 0; r < 20; ++r) launch();
+                CK(hipEventRecord(e1));
+                CK(hipDeviceSynchronize());
+                CK(hipEventElapsedTime(&ms, e0, e1));
+                unsigned long long hc[2];
+                CK(hipMemcpy(hc, clk, 16, hipMemcpyDeviceToHost));
+                const double ops_per_inst = shape16 ? 32768.0 : 65536.0;
+                printf("int8 mfma %s from registers, operands change per instruction, %-22s: %7.1f TOP/s at %4.0f MHz\n",
+                       shape16 ? "16x16x64" : "32x32x32", names[kind], 20.0 * 512 * 4 * it * 64 * ops_per_inst / (ms * 1e-3) / 1e12,
+                       100.0 * hc[1] / hc[0]);
+            }
+        }
+        CK(hipFree(ops));
+        CK(hipFree(clk));
+    }
 
     {
         const size_t ld = 8192;

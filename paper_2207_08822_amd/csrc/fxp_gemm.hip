@@ -1013,6 +1013,16 @@ static GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K) {
 // aligned and the reduction can read all of them in 16-byte pieces
 static int64_t slice_stride(int64_t M, int64_t N) { return (M * N + 3) / 4 * 4; }
 
+// Output elements the busiest CU computes with 256 x 256 tiles (one workgroup per CU) and with 160 x 128 tiles
+// (tiles dealt round-robin, two resident per CU): the smaller tiles win when they cut that by a quarter or more,
+// i.e. when the large tiles leave many CUs idle or a last round nearly empty.
+static bool fits_160x128(int64_t M, int64_t N) {
+    const int64_t num_cu = 256;
+    const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256), t160 = ((M + 159) / 160) * ((N + 127) / 128);
+    const int64_t work256 = (t256 + num_cu - 1) / num_cu * (256 * 256), work160 = (t160 + num_cu - 1) / num_cu * (160 * 128);
+    return 4 * work160 <= 3 * work256;
+}
+
 size_t gemm_split_ws_bytes(int64_t M, int64_t N, int64_t K) {
     const GemmPlan p = plan_gemm(M, N, K);
     return p.splits > 1 ? round_up(static_cast<size_t>(p.splits) * slice_stride(M, N) * sizeof(int32_t), 256) : 0;
@@ -1119,6 +1129,11 @@ int gemm_nt_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda
         rc = launch_dma<128, 128, 128, 64, 64, 2>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, 1, eA, bitsA, eB, bitsB, s, 0, nullptr, one, amax1, ride);
     else if (use256 && splits == 1 && stream_out)
         rc = launch_dma<128, 256, 64, 64, 64, 3>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, 1, eA, bitsA, eB, bitsB, s, 0, nullptr, one, amax1, ride);
+    else if (use256 && K % 128 == 0 && splits == 1 && fits_160x128(M, N))
+        // too few 256 x 256 tiles for the 256 CUs: 160 x 128 tiles, two workgroups resident per CU (one is at its
+        // barrier or in its epilogue while the other multiplies).  ViT-B, 12608 x 768 outputs = 150 tiles of 256 x 256
+        // against 474 of these: contraction 3072: 39.9 -> 35.2 us, 2304: 32.4 -> 28.1, 768: 16.8 -> 14.7
+        rc = launch_dma<160, 128, 128, 160, 32, 2>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, 1, eA, bitsA, eB, bitsB, s, 0, nullptr, one, amax1, ride);
     else if (use256 && K % 128 == 0 && splits == 1)
         rc = launch_ring<64, 128>(M, N, K, A, lda, B, ldb, dst, dst_ld, first_mode, 1, eA, bitsA, eB, bitsB, s, 0, nullptr, one, amax1, ride);
     else if (plan.tall)

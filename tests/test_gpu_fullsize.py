@@ -1,8 +1,11 @@
 """GPU parity at the full sizes of the benchmark workloads, in the launch
 configuration bench.py times (the layer calls): scales and all mapped int8 tensors
-are compared in full with the oracle; GEMM outputs are compared exactly on sampled
-rows the oracle computes one by one and through exact int64 identities that hold at
-any size (C v = A (B v); sum C = colsum(A) . rowsum(B))."""
+are compared in full with the oracle.  Product outputs: every element against the
+oracle for the ResNet layer, the ViT layers and the 8192^3 layer at sigma = 1
+(n_rows = None); for the other three sigmas of the 8192^3 layer the oracle computes 32
+rows of every 256-row band of the output (1024 rows per product: every tile row of
+the launch, every 8-row group of a tile), and exact int64 identities that hold at any
+size cover the rest (C v = A (B v); sum C = colsum(A) . rowsum(B))."""
 import numpy as np
 import pytest
 
@@ -68,8 +71,19 @@ def run_layer_fullsize(fxp, workload, layer_index, sigma, n_rows):
     # --- GEMM outputs
     rng = np.random.default_rng(99)
     WqT, XqT, GqT = (np.ascontiguousarray(a.T) for a in (Wq, Xq, Gq))
-    rows_m = np.sort(rng.choice(M, size=min(n_rows, M), replace=False))
-    rows_k = np.sort(rng.choice(K, size=min(n_rows, K), replace=False))
+    if n_rows is None:
+        # every element of every product
+        assert same_bits(Y, oracle.unmap(oracle.gemm(Xq, WqT, transB=True), eX, eW)), "Y"
+        assert same_bits(dX, oracle.unmap(oracle.gemm(Gq, Wq, transB=True), eG, eW)), "dX"
+        assert same_bits(dW, oracle.unmap(oracle.gemm(XqT, GqT, transB=True), eX, eG)), "dW"
+        return
+    if n_rows == "bands":
+        band = lambda n: np.array([256 * t + 8 * j + (3 * j + t) % 8 for t in range((n + 255) // 256) for j in range(32)
+                                   if 256 * t + 8 * j + (3 * j + t) % 8 < n])
+        rows_m, rows_k = band(M), band(K)
+    else:
+        rows_m = np.sort(rng.choice(M, size=min(n_rows, M), replace=False))
+        rows_k = np.sort(rng.choice(K, size=min(n_rows, K), replace=False))
     sampled_rows_check(Y, lambda r: Xq[r], WqT, eX, eW, rows_m, "Y rows")
     sampled_rows_check(dX, lambda r: Gq[r], Wq, eG, eW, rows_m, "dX rows")
     sampled_rows_check(dW, lambda r: XqT[r], GqT, eX, eG, rows_k, "dW rows")
@@ -79,21 +93,22 @@ def run_layer_fullsize(fxp, workload, layer_index, sigma, n_rows):
 
 
 def test_c2_resnet_conv_fullsize(fxp):
-    run_layer_fullsize(fxp, "c2", 0, 1.0, 128)
+    run_layer_fullsize(fxp, "c2", 0, 1.0, None)
 
 
 def test_c3_vit_fc1_fullsize(fxp):
-    run_layer_fullsize(fxp, "c3", 0, 1.0, 96)
+    run_layer_fullsize(fxp, "c3", 0, 1.0, None)
 
 
 @pytest.mark.parametrize("layer_index", [0, 1, 3])
 def test_c4_vit_block_other_linears_fullsize(fxp, layer_index):
-    run_layer_fullsize(fxp, "c4", layer_index, 1.0, 64)
+    run_layer_fullsize(fxp, "c4", layer_index, 1.0, None)
 
 
 @pytest.mark.parametrize("sigma", synth.C5_SIGMAS)
 def test_c5_square_fullsize(fxp, sigma):
-    run_layer_fullsize(fxp, "c5", 0, sigma, 32)
+    # sigma = 1 in full (about a minute of oracle time); the other sigmas on 32 rows of every 256-row band
+    run_layer_fullsize(fxp, "c5", 0, sigma, None if sigma == 1.0 else "bands")
 
 
 # --------------------------------------------------------------------------- beyond 32-bit element counts

@@ -302,7 +302,8 @@ def test_unmap_all_exponent_ranges(fxp):
 
 
 @pytest.mark.parametrize("M,N,K", [(300, 200, 160), (128, 128, 4096), (512, 768, 256), (1024, 1280, 64),
-                                   (2560, 2560, 256), (2560, 2600, 192), (1024, 1024, 4160), (100, 90, 50)])
+                                   (2560, 2560, 256), (2560, 2600, 192), (1024, 1024, 4160), (100, 90, 50),
+                                   (2500, 2570, 384), (3100, 2304, 128)])      # 160 x 128 tiles, ragged in both directions
 def test_gemm_unmap_fused(fxp, M, N, K):
     rng = np.random.default_rng(M + N + K)
     A, B = rand_i8(rng, (M, K)), rand_i8(rng, (N, K))
