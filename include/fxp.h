@@ -354,6 +354,19 @@ int fxp_conv2d_bwd(const float* dY, const fxp_conv_saved* saved, const fxp_conv2
  * into its power limit, so their rate is reported next to the clock they ran at. */
 int fxp_clock_probe(uint64_t* out, uint32_t microseconds, void* stream);
 
+/* Time stamps inside the linear-layer calls.  After fxp_timeline_begin(capacity) (host call; creates `capacity`
+ * HIP events, 1 .. 2^20) every fxp_linear_fwd / fxp_linear_bwd records one event on its stream at its entry
+ * (FXP_TL_ENTRY) and one after each of its launches, tagged with what the launch was, until the events are used
+ * up.  fxp_timeline_end waits for the last recorded event and returns, for every pair of consecutive events, the
+ * elapsed microseconds and the tag of the later one (so an interval is the in-stream duration of that launch
+ * behind the launch that really precedes it in the step; an FXP_TL_ENTRY interval is the idle time between two
+ * calls); *count receives the number of intervals written (at most `capacity`).  Then the events are destroyed.
+ * One timeline per process; not to be begun or ended while layer calls are running in other threads. */
+enum { FXP_TL_ENTRY = 0, FXP_TL_SCALE = 1, FXP_TL_MAP = 2, FXP_TL_GEMM_FWD = 3, FXP_TL_GEMM_DW = 4, FXP_TL_GEMM_DX = 5,
+       FXP_TL_REDUCE = 6 };
+int fxp_timeline_begin(int capacity);
+int fxp_timeline_end(float* microseconds, int* tags, int capacity, int* count);
+
 #ifdef __cplusplus
 }
 #endif

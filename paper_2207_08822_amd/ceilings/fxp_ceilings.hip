@@ -73,7 +73,7 @@ __global__ __launch_bounds__(256) void k_mfma(int* out, int iters, int seed) {
 // and eight B fragments (loaded once from memory) and walks through the pairings.  With all-equal operand words
 // the matrix cores toggle few bits; with the int8 values a mapped tensor holds they draw enough power to pull the
 // core clock down, which is the ceiling a product kernel on such data can at best reach.
-template <bool SHAPE16>
+template <bool SHAPE16, bool HOLD_A = false>
 __global__ __launch_bounds__(256) void k_mfma_data(const v4i* __restrict__ ops, int* out, int iters) {
     const v4i* mine = ops + (static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x) * 16;
     v4i a[8], b[8];
@@ -86,7 +86,7 @@ __global__ __launch_bounds__(256) void k_mfma_data(const v4i* __restrict__ ops, 
 #pragma unroll
             for (int r = 0; r < 8; ++r)
 #pragma unroll
-                for (int n = 0; n < 8; ++n) acc[n] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[(n + r) & 7], b[n], acc[n], 0, 0, 0);
+                for (int n = 0; n < 8; ++n) acc[n] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[HOLD_A ? r : (n + r) & 7], b[n], acc[n], 0, 0, 0);
         }
         for (int n = 0; n < 8; ++n)
             for (int r = 0; r < 4; ++r) s += acc[n][r];
@@ -98,7 +98,7 @@ __global__ __launch_bounds__(256) void k_mfma_data(const v4i* __restrict__ ops, 
 #pragma unroll
             for (int r = 0; r < 8; ++r)
 #pragma unroll
-                for (int n = 0; n < 8; ++n) acc[n] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[(n + r) & 7], b[n], acc[n], 0, 0, 0);
+                for (int n = 0; n < 8; ++n) acc[n] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[HOLD_A ? r : (n + r) & 7], b[n], acc[n], 0, 0, 0);
         }
         for (int n = 0; n < 8; ++n)
             for (int r = 0; r < 16; ++r) s += acc[n][r];
@@ -226,10 +226,14 @@ int main() {
                 else v = static_cast<int8_t>(uni(rng));
             }
             CK(hipMemcpy(ops, h.data(), nops * 16, hipMemcpyHostToDevice));
-            for (int shape16 = 0; shape16 < 2; ++shape16) {
+            for (int variant = 0; variant < 4; ++variant) {
+                const int shape16 = variant & 1, hold = variant >> 1;
+                if (hold && kind == 0) continue;
                 const int it = shape16 ? 4 * 2500 : 2500;        // 64 instructions per iteration
                 auto launch = [&] {
-                    if (shape16) k_mfma_data<true><<<512, 256>>>(ops, reinterpret_cast<int*>(out), it);
+                    if (shape16 && hold) k_mfma_data<true, true><<<512, 256>>>(ops, reinterpret_cast<int*>(out), it);
+                    else if (shape16) k_mfma_data<true><<<512, 256>>>(ops, reinterpret_cast<int*>(out), it);
+                    else if (hold) k_mfma_data<false, true><<<512, 256>>>(ops, reinterpret_cast<int*>(out), it);
                     else k_mfma_data<false><<<512, 256>>>(ops, reinterpret_cast<int*>(out), it);
                 };
                 launch();
@@ -244,8 +248,9 @@ int main() {
                 unsigned long long hc[2];
                 CK(hipMemcpy(hc, clk, 16, hipMemcpyDeviceToHost));
                 const double ops_per_inst = shape16 ? 32768.0 : 65536.0;
-                printf("int8 mfma %s from registers, operands change per instruction, %-22s: %7.1f TOP/s at %4.0f MHz\n",
-                       shape16 ? "16x16x64" : "32x32x32", names[kind], 20.0 * 512 * 4 * it * 64 * ops_per_inst / (ms * 1e-3) / 1e12,
+                printf("int8 mfma %s from registers, %s, %-22s: %7.1f TOP/s at %4.0f MHz\n",
+                       shape16 ? "16x16x64" : "32x32x32",
+                       hold ? "one operand held for 8 instructions  " : "both operands change per instruction", names[kind], 20.0 * 512 * 4 * it * 64 * ops_per_inst / (ms * 1e-3) / 1e12,
                        100.0 * hc[1] / hc[0]);
             }
         }

@@ -8,10 +8,32 @@
 //   dW = XqT [K,M] x dYqT[N,M]^T
 #include <algorithm>
 #include <mutex>
+#include <vector>
 
 #include "fxp_internal.h"
 
 namespace fxp {
+
+// Measurement helper (fxp_timeline_begin / _end): HIP events recorded on the caller's stream at the entry of a
+// linear-layer call and after each of its launches, so that a benchmark reads the duration every kernel has
+// INSIDE a step (behind the kernel that really precedes it, with what that kernel left in the caches) instead of
+// timing it in a loop of its own.  Off unless a timeline has been begun; one timeline per process.
+struct Timeline {
+    std::vector<hipEvent_t> events;
+    std::vector<int> tags;
+    size_t used = 0;
+    bool on = false;
+};
+static Timeline g_timeline;
+static std::mutex g_timeline_lock;
+
+static void timeline_mark(hipStream_t s, int tag) {
+    if (!g_timeline.on) return;                       // (read without the lock: begin / end are not called concurrently with layer calls)
+    std::lock_guard<std::mutex> hold(g_timeline_lock);
+    if (g_timeline.used >= g_timeline.events.size()) return;
+    if (hipEventRecord(g_timeline.events[g_timeline.used], s) != hipSuccess) { (void)hipGetLastError(); return; }
+    g_timeline.tags[g_timeline.used++] = tag;
+}
 
 static int check_layer(int64_t M, int64_t K, int64_t N, int rounding, int bits, const void* ws, size_t ws_bytes,
                        size_t need) {
@@ -80,13 +102,20 @@ static int linear_fwd_run(const float* X, const float* W, int64_t M, int64_t K, 
                           uint64_t seed, uint64_t step, int rounding, int bits, void* ws, size_t ws_bytes, hipStream_t s) {
     uint32_t* pX = static_cast<uint32_t*>(ws);
     uint32_t* pW = pX + round_up(kScaleWsBytes, 256) / sizeof(uint32_t);
-    const MapTensor tX{X, M, K, nullptr, pX, 0, saved->eX, saved->Xq, saved->XqT, (step << 8) | FXP_TAG_X};
-    const MapTensor tW{W, K, N, nullptr, pW, 0, saved->eW, saved->Wq, saved->WqT, (step << 8) | FXP_TAG_W};
-    int rc = scale_and_map2(tX, tW, seed, rounding, bits, s);
+    MapTensor tX{X, M, K, nullptr, pX, 0, saved->eX, saved->Xq, saved->XqT, (step << 8) | FXP_TAG_X};
+    MapTensor tW{W, K, N, nullptr, pW, 0, saved->eW, saved->Wq, saved->WqT, (step << 8) | FXP_TAG_W};
+    timeline_mark(s, FXP_TL_ENTRY);
+    // scale + map of both operands in two launches: one reduction launch and one map launch cover both tensors
+    int rc = scale_partials2(X, static_cast<size_t>(M * K), pX, &tX.n_partials, W, static_cast<size_t>(K * N), pW, &tW.n_partials, s);
     if (rc) return rc;
+    timeline_mark(s, FXP_TL_SCALE);
+    if ((rc = map_launch2(tX, tW, seed, rounding, bits, s))) return rc;
+    timeline_mark(s, FXP_TL_MAP);
     uint8_t* rest = static_cast<uint8_t*>(ws) + 2 * round_up(kScaleWsBytes, 256);
-    return gemm_nt_launch(M, N, K, saved->Xq, K, saved->WqT, K, Y, N, true, saved->eX, bits, saved->eW, bits, rest,
-                          ws_bytes - 2 * round_up(kScaleWsBytes, 256), s);
+    rc = gemm_nt_launch(M, N, K, saved->Xq, K, saved->WqT, K, Y, N, true, saved->eX, bits, saved->eW, bits, rest,
+                        ws_bytes - 2 * round_up(kScaleWsBytes, 256), s);
+    timeline_mark(s, FXP_TL_GEMM_FWD);
+    return rc;
 }
 
 }  // namespace fxp
@@ -160,9 +189,15 @@ extern "C" int fxp_linear_bwd(const float* dY, const fxp_saved* saved, int64_t M
         return FXP_ERR_NULL;
     if (!aligned(dY, 4) || !aligned(dX, 4) || !aligned(dW, 4) || !aligned(e_dY, 4)) return FXP_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if ((rc = scale_and_map(dY, M, N, e_dY, dYq, dYqT, seed, (step << 8) | FXP_TAG_DY, rounding, bits,
-                            static_cast<uint32_t*>(ws), s)))
-        return rc;
+    timeline_mark(s, FXP_TL_ENTRY);
+    {
+        int np = 0;
+        if ((rc = scale_partials(dY, static_cast<size_t>(M * N), static_cast<uint32_t*>(ws), &np, s))) return rc;
+        timeline_mark(s, FXP_TL_SCALE);
+        const MapTensor t{dY, M, N, nullptr, static_cast<uint32_t*>(ws), np, e_dY, dYq, dYqT, (step << 8) | FXP_TAG_DY};
+        if ((rc = map_launch(t, seed, rounding, bits, s))) return rc;
+        timeline_mark(s, FXP_TL_MAP);
+    }
     uint8_t* rest = static_cast<uint8_t*>(ws) + round_up(kScaleWsBytes, 256);
     const size_t rest_bytes = ws_bytes - round_up(kScaleWsBytes, 256);
     // The weight gradient first: when it is split along K, the sum of its slices does not get a launch of its own
@@ -173,11 +208,60 @@ extern "C" int fxp_linear_bwd(const float* dY, const fxp_saved* saved, int64_t M
     if (dW && (rc = gemm_nt_launch(K, N, M, saved->XqT, M, dYqT, M, dW, N, true, saved->eX, bits, e_dY, bits, rest,
                                    rest_bytes, s, nullptr, nullptr, rides ? &pending : nullptr)))
         return rc;
+    if (dW) timeline_mark(s, FXP_TL_GEMM_DW);
     if (dX && (rc = gemm_nt_launch(M, K, N, dYq, N, saved->Wq, N, dX, K, true, e_dY, bits, saved->eW, bits, rest,
                                    rest_bytes, s, nullptr, &pending, nullptr)))
         return rc;
-    if (pending.blocks != 0) return splitk_reduce_launch(pending, s);      // nobody took it along
+    if (dX) timeline_mark(s, FXP_TL_GEMM_DX);
+    if (pending.blocks != 0) {                                             // nobody took it along
+        rc = splitk_reduce_launch(pending, s);
+        timeline_mark(s, FXP_TL_REDUCE);
+        return rc;
+    }
     return FXP_OK;
+}
+
+extern "C" int fxp_timeline_begin(int capacity) {
+    using namespace fxp;
+    if (capacity <= 0 || capacity > (1 << 20)) return FXP_ERR_DIMS;
+    std::lock_guard<std::mutex> hold(g_timeline_lock);
+    if (g_timeline.on) return FXP_ERR_DIMS;                       // one timeline at a time
+    g_timeline.events.assign(static_cast<size_t>(capacity), nullptr);
+    g_timeline.tags.assign(static_cast<size_t>(capacity), 0);
+    g_timeline.used = 0;
+    for (auto& e : g_timeline.events)
+        if (hipEventCreate(&e) != hipSuccess) {
+            (void)hipGetLastError();
+            for (auto& d : g_timeline.events)
+                if (d) (void)hipEventDestroy(d);
+            g_timeline.events.clear();
+            return FXP_ERR_LAUNCH;
+        }
+    g_timeline.on = true;
+    return FXP_OK;
+}
+
+extern "C" int fxp_timeline_end(float* microseconds, int* tags, int capacity, int* count) {
+    using namespace fxp;
+    std::lock_guard<std::mutex> hold(g_timeline_lock);
+    if (!g_timeline.on) return FXP_ERR_DIMS;
+    g_timeline.on = false;
+    int rc = FXP_OK, n = 0;
+    if (g_timeline.used > 0 && hipEventSynchronize(g_timeline.events[g_timeline.used - 1]) != hipSuccess) rc = FXP_ERR_LAUNCH;
+    for (size_t i = 1; rc == FXP_OK && i < g_timeline.used && n < capacity; ++i) {
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, g_timeline.events[i - 1], g_timeline.events[i]) != hipSuccess) { rc = FXP_ERR_LAUNCH; break; }
+        if (microseconds) microseconds[n] = ms * 1000.0f;
+        if (tags) tags[n] = g_timeline.tags[i];
+        ++n;
+    }
+    if (rc != FXP_OK) (void)hipGetLastError();
+    if (count) *count = n;
+    for (auto& e : g_timeline.events) (void)hipEventDestroy(e);
+    g_timeline.events.clear();
+    g_timeline.tags.clear();
+    g_timeline.used = 0;
+    return rc;
 }
 
 

@@ -82,6 +82,10 @@ def lib():
     L.fxp_static_scratch_bytes.argtypes = []
     L.fxp_clock_probe.argtypes = [vp, c.c_uint32, vp]
     L.fxp_clock_probe.restype = ci
+    L.fxp_timeline_begin.argtypes = [ci]
+    L.fxp_timeline_begin.restype = ci
+    L.fxp_timeline_end.argtypes = [vp, vp, ci, vp]
+    L.fxp_timeline_end.restype = ci
     L.fxp_conv2d_workspace_bytes.restype = sz
     L.fxp_conv2d_workspace_bytes.argtypes = [c.POINTER(_ConvShape), ci]
     L.fxp_conv2d_fwd.argtypes = [vp, vp, c.POINTER(_ConvShape), vp, c.POINTER(_ConvSaved), u64, u64, ci, ci, vp, sz, vp]
