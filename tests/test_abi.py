@@ -152,3 +152,35 @@ def test_argument_errors_of_the_multi_tensor_update():
     assert L.fxp_sgd16_step_multi(tab, 3, 0.1, 0.0, 0.0, 0, 1 << 32, 0, ws, need, None) == -2
     assert L.fxp_sgd16_step_multi(tab, 3, 0.1, 0.0, 0.0, 0, 0, 5, ws, need, None) == -5
     assert L.fxp_sgd16_step_multi(None, 0, 0.1, 0.0, 0.0, 0, 0, 0, None, 0, None) == 0       # nothing to do
+
+
+def test_argument_errors_of_the_measurement_helpers_and_the_workspace_free_forward():
+    """Clock probe, timeline and fxp_linear_fwd_static validate on the host before touching a device."""
+    L = load()
+    vp, i64, u64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_uint64, ctypes.c_int
+    fake = ctypes.c_void_p(1 << 20)
+    L.fxp_clock_probe.argtypes = [vp, ctypes.c_uint32, vp]
+    assert L.fxp_clock_probe(None, 100, None) == -1
+    assert L.fxp_clock_probe(ctypes.c_void_p((1 << 20) + 4), 100, None) == -3
+    assert L.fxp_clock_probe(fake, 0, None) == -2 and L.fxp_clock_probe(fake, 2_000_000, None) == -2
+    L.fxp_timeline_begin.argtypes = [ci]
+    L.fxp_timeline_end.argtypes = [vp, vp, ci, vp]
+    assert L.fxp_timeline_begin(0) == -2 and L.fxp_timeline_begin(-5) == -2
+    n = ctypes.c_int(7)
+    assert L.fxp_timeline_end(None, None, 0, ctypes.byref(n)) == -2       # nothing was begun
+    L.fxp_static_scratch_bytes.restype = ctypes.c_size_t
+    assert L.fxp_static_scratch_bytes() == 32 << 20
+
+    class Saved(ctypes.Structure):
+        _fields_ = [(k, vp) for k in ("Xq", "XqT", "Wq", "WqT", "eX", "eW")]
+
+    L.fxp_linear_fwd_static.argtypes = [vp, vp, i64, i64, i64, vp, ctypes.POINTER(Saved), u64, u64, ci, ci, vp]
+    ok = Saved(*([1 << 20] * 6))
+    assert L.fxp_linear_fwd_static(fake, fake, 0, 4, 4, fake, ctypes.byref(ok), 0, 0, 0, 8, None) == -2
+    assert L.fxp_linear_fwd_static(None, fake, 4, 4, 4, fake, ctypes.byref(ok), 0, 0, 0, 8, None) == -1
+    assert L.fxp_linear_fwd_static(fake, fake, 4, 4, 4, fake, ctypes.byref(Saved()), 0, 0, 0, 8, None) == -1
+    assert L.fxp_linear_fwd_static(fake, fake, 4, 4, 4, fake, ctypes.byref(ok), 0, 0, 3, 8, None) == -5
+    assert L.fxp_linear_fwd_static(fake, fake, 4, 4, 4, fake, ctypes.byref(ok), 0, 0, 0, 1, None) == -6
+    assert L.fxp_linear_fwd_static(ctypes.c_void_p((1 << 20) + 2), fake, 4, 4, 4, fake, ctypes.byref(ok), 0, 0, 0, 8, None) == -3
+    # a layer whose split forward product needs more than the static array holds
+    assert L.fxp_linear_fwd_static(fake, fake, 2048, 1 << 16, 1024, fake, ctypes.byref(ok), 0, 0, 0, 8, None) == -4

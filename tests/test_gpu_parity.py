@@ -575,3 +575,39 @@ def test_empty_operands_are_no_ops(fxp):
     assert L.fxp_axpy16(p(x), p(x), 0.5, 0, p(x), None, 0, 0, 0, p(ws), ws.numel(), None) == 0
     torch.cuda.synchronize()
     assert bool((guard == 7).all()) and bool((x == 0).all())
+
+
+def test_timeline_and_clock_probe_measure_without_changing_results(fxp):
+    """The measurement helpers: the events recorded inside the layer calls come back as one interval per launch,
+    in launch order, and the outputs are the ones an undisturbed call gives; the clock probe reports a plausible
+    core clock."""
+    import ctypes
+    say("timeline / clock probe")
+    L = fxp.lib()
+    X, W, dY = synth.layer_tensors("c2", scale_down=8)
+    M, K = X.shape
+    N = W.shape[1]
+    buf0, buf1 = fxp.LayerBuffers(M, K, N), fxp.LayerBuffers(M, K, N)
+    Xd, Wd, Gd = dev(X), dev(W), dev(dY)
+    fxp.linear_fwd(Xd, Wd, buf0, 5, 2)
+    fxp.linear_bwd(Gd, buf0, 5, 2)
+    torch.cuda.synchronize()
+    assert L.fxp_timeline_begin(64) == 0
+    assert L.fxp_timeline_begin(64) == -2                      # one timeline at a time
+    for _ in range(2):
+        fxp.linear_fwd(Xd, Wd, buf1, 5, 2)
+        fxp.linear_bwd(Gd, buf1, 5, 2)
+    us, tags, n = (ctypes.c_float * 64)(), (ctypes.c_int * 64)(), ctypes.c_int(0)
+    assert L.fxp_timeline_end(us, tags, 64, ctypes.byref(n)) == 0
+    got = [tags[i] for i in range(n.value)]
+    one = [1, 2, 3, 0, 1, 2, 4, 5]                             # scale, map, product; entry, scale, map, dW, dX
+    assert got in (one + [0] + one, one + [6, 0] + one + [6]), got     # (a stand-alone slice sum would add a 6)
+    assert all(us[i] > 0.0 for i in range(n.value)) and sum(us[i] for i in range(n.value)) < 1e6
+    assert L.fxp_timeline_end(us, tags, 64, ctypes.byref(n)) == -2
+    for a, b in ((buf0.Y, buf1.Y), (buf0.dX, buf1.dX), (buf0.dW, buf1.dW)):
+        assert same_bits(host(a), host(b))
+    out = torch.zeros(2, dtype=torch.int64, device="cuda")
+    assert L.fxp_clock_probe(out.data_ptr(), 300, torch.cuda.current_stream().cuda_stream) == 0
+    torch.cuda.synchronize()
+    ticks, cycles = host(out).tolist()
+    assert 30000 <= ticks < 60000 and 300.0 < 100.0 * cycles / ticks < 3500.0, (ticks, cycles)
