@@ -222,6 +222,21 @@ int fxp_linear_bwd(const float* dY, const fxp_saved* saved, int64_t M, int64_t K
                    int8_t* dYq, int8_t* dYqT, int32_t* e_dY, uint64_t seed, uint64_t step, int rounding, int bits,
                    void* ws, size_t ws_bytes, void* stream);
 
+/* The same two calls for a training loop, where a tensor's scale seldom moves from one step to the next (Sec. 3.1:
+ * the scale is the largest exponent of the tensor).  saved->eX, saved->eW and e_dY are read on entry as GUESSES of
+ * the scales (what the previous step's call left there; any other content is harmless).  Each large tensor is then
+ * read ONCE: a single pass maps it with the guess and finds its true largest magnitude, and a second, short launch
+ * verifies - if the guess was the scale, the mapped tensor is already what fxp_linear_fwd / _bwd would have
+ * written; if not (the maximum crossed a power of two, first call, garbage in the word), that launch maps the
+ * tensor again with the true scale.  Results are bit for bit those of fxp_linear_fwd / fxp_linear_bwd in every
+ * case; a hit saves the reduction's pass over the tensor (4 of 10 bytes per element), a miss costs one map pass
+ * more.  Tensors below 2^22 elements and tensors off the fast path of fxp_map take the two-pass path as before. */
+int fxp_linear_fwd_guess(const float* X, const float* W, int64_t M, int64_t K, int64_t N, float* Y, const fxp_saved* saved,
+                         uint64_t seed, uint64_t step, int rounding, int bits, void* ws, size_t ws_bytes, void* stream);
+int fxp_linear_bwd_guess(const float* dY, const fxp_saved* saved, int64_t M, int64_t K, int64_t N, float* dX, float* dW,
+                         int8_t* dYq, int8_t* dYqT, int32_t* e_dY, uint64_t seed, uint64_t step, int rounding, int bits,
+                         void* ws, size_t ws_bytes, void* stream);
+
 /* Batched integer GEMM for the attention products (the paper runs Q K^T and A V as int8 matmuls with the
  * softmax in floating point, Sec. 5 / ViT): `batch` (<= 65535) independent products in the native form
  * C_b[M,N] = A_b[M,K] * B_b[N,K]^T, matrix b of an operand starting b * stride elements after matrix 0.

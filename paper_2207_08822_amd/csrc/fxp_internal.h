@@ -50,6 +50,12 @@ struct MapTensor {
     uint64_t stream_id;
 };
 int map_launch(const MapTensor& t, uint64_t seed, int rounding, int bits, hipStream_t s);
+// scale + map in one pass with the previous scale as a guess (fxp_map.hip)
+constexpr unsigned kGuessBlocks = 1008;            // workgroups of a guessing launch: their maxima and the guess fit one scratch area
+constexpr int64_t kGuessMinElements = int64_t{1} << 22;
+constexpr int kNoGuessPath = 2;
+int scale_map_guess_launch(const MapTensor& a, const MapTensor* b, uint32_t* area_a, uint32_t* area_b, uint64_t seed,
+                           int rounding, int bits, hipStream_t s);
 int map_launch2(const MapTensor& a, const MapTensor& b, uint64_t seed, int rounding, int bits, hipStream_t s);
 int gemm_nt_batched_launch(int64_t M, int64_t N, int64_t K, const int8_t* A, int64_t lda, int64_t strideA,
                            const int8_t* B, int64_t ldb, int64_t strideB, void* C, int64_t ldc, int64_t strideC,

@@ -99,17 +99,23 @@ static int check_linear_fwd(const float* X, const float* W, int64_t M, int64_t K
 
 // the forward pass itself: arguments validated, ws of fxp_workspace_bytes(FXP_OP_LINEAR_FWD) bytes or more
 static int linear_fwd_run(const float* X, const float* W, int64_t M, int64_t K, int64_t N, float* Y, const fxp_saved* saved,
-                          uint64_t seed, uint64_t step, int rounding, int bits, void* ws, size_t ws_bytes, hipStream_t s) {
+                          uint64_t seed, uint64_t step, int rounding, int bits, void* ws, size_t ws_bytes, hipStream_t s,
+                          bool guess = false) {
     uint32_t* pX = static_cast<uint32_t*>(ws);
     uint32_t* pW = pX + round_up(kScaleWsBytes, 256) / sizeof(uint32_t);
     MapTensor tX{X, M, K, nullptr, pX, 0, saved->eX, saved->Xq, saved->XqT, (step << 8) | FXP_TAG_X};
     MapTensor tW{W, K, N, nullptr, pW, 0, saved->eW, saved->Wq, saved->WqT, (step << 8) | FXP_TAG_W};
     timeline_mark(s, FXP_TL_ENTRY);
-    // scale + map of both operands in two launches: one reduction launch and one map launch cover both tensors
-    int rc = scale_partials2(X, static_cast<size_t>(M * K), pX, &tX.n_partials, W, static_cast<size_t>(K * N), pW, &tW.n_partials, s);
+    // with the scales of the last step as guesses: one pass that maps and finds the maxima, one launch that verifies
+    int rc = guess ? scale_map_guess_launch(tX, &tW, pX, pW, seed, rounding, bits, s) : kNoGuessPath;
+    if (rc == kNoGuessPath) {
+        // scale + map of both operands in two launches: one reduction launch and one map launch cover both tensors
+        rc = scale_partials2(X, static_cast<size_t>(M * K), pX, &tX.n_partials, W, static_cast<size_t>(K * N), pW, &tW.n_partials, s);
+        if (rc) return rc;
+        timeline_mark(s, FXP_TL_SCALE);
+        rc = map_launch2(tX, tW, seed, rounding, bits, s);
+    }
     if (rc) return rc;
-    timeline_mark(s, FXP_TL_SCALE);
-    if ((rc = map_launch2(tX, tW, seed, rounding, bits, s))) return rc;
     timeline_mark(s, FXP_TL_MAP);
     uint8_t* rest = static_cast<uint8_t*>(ws) + 2 * round_up(kScaleWsBytes, 256);
     rc = gemm_nt_launch(M, N, K, saved->Xq, K, saved->WqT, K, Y, N, true, saved->eX, bits, saved->eW, bits, rest,
@@ -179,10 +185,10 @@ extern "C" int fxp_linear_fwd_static(const float* X, const float* W, int64_t M, 
                           static_cast<hipStream_t>(stream));
 }
 
-extern "C" int fxp_linear_bwd(const float* dY, const fxp_saved* saved, int64_t M, int64_t K, int64_t N, float* dX,
-                              float* dW, int8_t* dYq, int8_t* dYqT, int32_t* e_dY, uint64_t seed, uint64_t step,
-                              int rounding, int bits, void* ws, size_t ws_bytes, void* stream) {
-    using namespace fxp;
+namespace fxp {
+static int linear_bwd_impl(const float* dY, const fxp_saved* saved, int64_t M, int64_t K, int64_t N, float* dX,
+                           float* dW, int8_t* dYq, int8_t* dYqT, int32_t* e_dY, uint64_t seed, uint64_t step,
+                           int rounding, int bits, void* ws, size_t ws_bytes, void* stream, bool guess) {
     int rc = check_layer(M, K, N, rounding, bits, ws, ws_bytes, fxp_workspace_bytes(FXP_OP_LINEAR_BWD, M, N, K));
     if (rc) return rc;
     if (!dY || !saved || !saved->XqT || !saved->Wq || !saved->eX || !saved->eW || !dYq || !dYqT || !e_dY)
@@ -191,11 +197,14 @@ extern "C" int fxp_linear_bwd(const float* dY, const fxp_saved* saved, int64_t M
     hipStream_t s = static_cast<hipStream_t>(stream);
     timeline_mark(s, FXP_TL_ENTRY);
     {
-        int np = 0;
-        if ((rc = scale_partials(dY, static_cast<size_t>(M * N), static_cast<uint32_t*>(ws), &np, s))) return rc;
-        timeline_mark(s, FXP_TL_SCALE);
-        const MapTensor t{dY, M, N, nullptr, static_cast<uint32_t*>(ws), np, e_dY, dYq, dYqT, (step << 8) | FXP_TAG_DY};
-        if ((rc = map_launch(t, seed, rounding, bits, s))) return rc;
+        MapTensor t{dY, M, N, nullptr, static_cast<uint32_t*>(ws), 0, e_dY, dYq, dYqT, (step << 8) | FXP_TAG_DY};
+        rc = guess ? scale_map_guess_launch(t, nullptr, static_cast<uint32_t*>(ws), nullptr, seed, rounding, bits, s) : kNoGuessPath;
+        if (rc == kNoGuessPath) {
+            if ((rc = scale_partials(dY, static_cast<size_t>(M * N), static_cast<uint32_t*>(ws), &t.n_partials, s))) return rc;
+            timeline_mark(s, FXP_TL_SCALE);
+            rc = map_launch(t, seed, rounding, bits, s);
+        }
+        if (rc) return rc;
         timeline_mark(s, FXP_TL_MAP);
     }
     uint8_t* rest = static_cast<uint8_t*>(ws) + round_up(kScaleWsBytes, 256);
@@ -219,6 +228,29 @@ extern "C" int fxp_linear_bwd(const float* dY, const fxp_saved* saved, int64_t M
         return rc;
     }
     return FXP_OK;
+}
+}  // namespace fxp
+
+extern "C" int fxp_linear_bwd(const float* dY, const fxp_saved* saved, int64_t M, int64_t K, int64_t N, float* dX,
+                              float* dW, int8_t* dYq, int8_t* dYqT, int32_t* e_dY, uint64_t seed, uint64_t step,
+                              int rounding, int bits, void* ws, size_t ws_bytes, void* stream) {
+    return fxp::linear_bwd_impl(dY, saved, M, K, N, dX, dW, dYq, dYqT, e_dY, seed, step, rounding, bits, ws, ws_bytes, stream, false);
+}
+
+extern "C" int fxp_linear_fwd_guess(const float* X, const float* W, int64_t M, int64_t K, int64_t N, float* Y,
+                                    const fxp_saved* saved, uint64_t seed, uint64_t step, int rounding, int bits, void* ws,
+                                    size_t ws_bytes, void* stream) {
+    using namespace fxp;
+    int rc = check_layer(M, K, N, rounding, bits, ws, ws_bytes, fxp_workspace_bytes(FXP_OP_LINEAR_FWD, M, N, K));
+    if (rc) return rc;
+    if ((rc = check_linear_fwd(X, W, M, K, N, Y, saved, rounding, bits))) return rc;
+    return linear_fwd_run(X, W, M, K, N, Y, saved, seed, step, rounding, bits, ws, ws_bytes, static_cast<hipStream_t>(stream), true);
+}
+
+extern "C" int fxp_linear_bwd_guess(const float* dY, const fxp_saved* saved, int64_t M, int64_t K, int64_t N, float* dX,
+                                    float* dW, int8_t* dYq, int8_t* dYqT, int32_t* e_dY, uint64_t seed, uint64_t step,
+                                    int rounding, int bits, void* ws, size_t ws_bytes, void* stream) {
+    return fxp::linear_bwd_impl(dY, saved, M, K, N, dX, dW, dYq, dYqT, e_dY, seed, step, rounding, bits, ws, ws_bytes, stream, true);
 }
 
 extern "C" int fxp_timeline_begin(int capacity) {

@@ -16,6 +16,8 @@
 //     folded in, which saves a launch per tensor.
 // The random word of element i is word (i mod 4) of Philox-4x32-10 with key = seed
 // and counter = (i / 4, stream_id): nothing depends on the launch geometry.
+#include <algorithm>
+
 #include "fxp_internal.h"
 
 namespace fxp {
@@ -104,6 +106,11 @@ struct MapJob {
     uint32_t sid0, sid1;
     int tiles_c;
     unsigned blocks;
+    // scale taken as a guess (see k_map_tile_guess): where the guess comes from, where the workgroup maxima of
+    // the guessing launch go, and the word that records which guess the tensor was mapped with (0 = none)
+    const int32_t* e_guess;
+    uint32_t* guess_partials;
+    int32_t* guess_used;
 };
 struct MapJobs {
     MapJob j[2];
@@ -128,11 +135,14 @@ __device__ inline int resolve_scale(const int32_t* e_in, const uint32_t* partial
 // to fill the chip with the taller tiles.  EDGE = the tile sticks out of the tensor: loads are clamped to valid
 // addresses and stores are predicated; interior tiles carry no bounds code at all.  All
 // per-thread addressing is a 32-bit element offset from the tile's (wave-uniform) origin.
-template <bool STOCH, bool EDGE, int PASSES, int TC>
+// GUESS: the scale is not resolved from block maxima but given (e_given; do_map = false: there is none, only the
+// maximum is wanted), and the largest magnitude bits of the tile are accumulated into tile_max (clamped loads
+// of an edge tile repeat elements of the tensor, which a maximum does not mind).
+template <bool STOCH, bool EDGE, int PASSES, int TC, bool GUESS = false>
 __device__ inline void map_tile_body(const uint32_t* __restrict__ x, int64_t rows, int64_t cols, const MapJob& J, int bits,
                                      bool publish, uint32_t* red, int8_t* __restrict__ q, int8_t* __restrict__ qT,
                                      uint32_t key0, uint32_t key1, uint32_t sid0, uint32_t sid1, int64_t r0, int64_t c0,
-                                     uint32_t* stage) {
+                                     uint32_t* stage, int e_given = 0, bool do_map = true, uint32_t* tile_max = nullptr) {
     constexpr int CG = TC / 4;                    // groups of 4 columns
     constexpr int RGP = kMapThreads / CG;         // groups of 4 rows per pass
     constexpr int TR = 4 * RGP * PASSES;          // rows of the tile
@@ -163,14 +173,24 @@ __device__ inline void map_tile_body(const uint32_t* __restrict__ x, int64_t row
     uint4 cur[4], nxt[4];
     load_pass(0, cur);
     // the scale is resolved (block maxima re-read and reduced) while the first loads are in flight
-    const MapCfg cfg = make_cfg(resolve_scale(J.e_in, J.partials, J.n_partials, J.e_out, red, publish), bits);
+    const MapCfg cfg = make_cfg(GUESS ? e_given : resolve_scale(J.e_in, J.partials, J.n_partials, J.e_out, red, publish), bits);
     const bool scale_ok = cfg.e_max >= 25 && cfg.e_max < 255;
     const uint32_t over_bits = ~cfg.sat;          // a fast-path result with any of these set needs saturation
+    uint32_t seen = 0;                             // GUESS: largest magnitude bits this thread has loaded
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
         const int rg = p * RGP + rgl;              // group of 4 rows
         const int lrow = 4 * rg;
         if (p + 1 < PASSES) load_pass(p + 1, nxt);
+        if (GUESS) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) seen = max(seen, absmax4(cur[k]));
+            if (!do_map) {                         // workgroup-uniform: no scale to map with, the maximum is all
+#pragma unroll
+                for (int k = 0; k < 4; ++k) cur[k] = nxt[k];
+                continue;
+            }
+        }
         auto words_of = [&](int k) {
             const uint32_t off = static_cast<uint32_t>(lrow + k) * ucols + 4 * cg;   // element offset in the tile
             const uint64_t blk = blk0 + (off >> 2);
@@ -213,7 +233,8 @@ __device__ inline void map_tile_body(const uint32_t* __restrict__ x, int64_t row
 #pragma unroll
         for (int k = 0; k < 4; ++k) cur[k] = nxt[k];
     }
-    if (qT == nullptr) return;
+    if (GUESS) *tile_max = max(*tile_max, seen);
+    if (qT == nullptr || (GUESS && !do_map)) return;
     __syncthreads();
     int8_t* qTt = qT + c0 * rows + r0;             // element [c0][r0] of the transposed copy
     const uint32_t urows = static_cast<uint32_t>(rows);
@@ -249,6 +270,12 @@ __global__ __launch_bounds__(kMapThreads) void k_map_tile(const MapJobs jobs, ui
     const bool second = blockIdx.x >= jobs.j[0].blocks;            // workgroup-uniform
     const MapJob& J = jobs.j[second ? 1 : 0];
     const unsigned bid = blockIdx.x - (second ? jobs.j[0].blocks : 0u);
+    if (J.guess_used != nullptr) {
+        // this launch follows k_map_tile_guess: the tensor is already mapped if the guess was its scale - then
+        // the scale is published and nothing else is left to do; otherwise the tile is mapped now
+        const int e = resolve_scale(nullptr, J.partials, J.n_partials, J.e_out, red, bid == 0);
+        if (J.guess_used[0] == e) return;
+    }
     const uint32_t* __restrict__ x = J.x;
     int8_t* __restrict__ q = J.q;
     int8_t* __restrict__ qT = J.qT;
@@ -259,6 +286,53 @@ __global__ __launch_bounds__(kMapThreads) void k_map_tile(const MapJobs jobs, ui
         map_tile_body<STOCH, false, PASSES, TC>(x, rows, cols, J, bits, bid == 0, red, q, qT, key0, key1, J.sid0, J.sid1, r0, c0, stage);
     else
         map_tile_body<STOCH, true, PASSES, TC>(x, rows, cols, J, bits, bid == 0, red, q, qT, key0, key1, J.sid0, J.sid1, r0, c0, stage);
+}
+
+// Scale and map in ONE pass over the tensor, for a caller that has a guess of the scale (the tensor's scale of
+// the previous training step: the largest exponent of a weight, an activation or a gradient tensor seldom moves
+// from one step to the next).  Every workgroup maps its tiles with the guess and keeps the largest magnitude it
+// saw; the launch leaves one maximum per workgroup (at most kGuessBlocks, so that the launch that follows can
+// reduce them like block maxima) and the guess it used.  The launch that follows (k_map_tile with guess_used
+// set) computes the true scale from the maxima: equal to the guess - the bytes written here are exactly what the
+// two-pass path writes, and that launch ends at once; different, or no usable guess (outside 1 .. 255) - it
+// maps the tensor again with the true scale.  4 B read + 2 B written per element instead of 8 + 2 on a hit.
+template <bool STOCH, int PASSES, int TC>
+__global__ __launch_bounds__(kMapThreads) void k_map_tile_guess(const MapJobs jobs, uint32_t key0, uint32_t key1, int bits) {
+    constexpr int RGP = kMapThreads / (TC / 4);
+    constexpr int TR = 4 * RGP * PASSES;
+    __shared__ uint32_t stage[TC * (RGP * PASSES + 1)];
+    __shared__ uint32_t red[kMapThreads / 64];
+    int guess[2];
+    uint32_t seen[2] = {0u, 0u};
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        guess[j] = jobs.j[j].blocks != 0 ? jobs.j[j].e_guess[0] : 0;
+        if (guess[j] < 1 || guess[j] > 255) guess[j] = 0;
+        if (jobs.j[j].blocks != 0 && blockIdx.x == 0 && threadIdx.x == 0) jobs.j[j].guess_used[0] = guess[j];
+    }
+    const unsigned total = jobs.j[0].blocks + jobs.j[1].blocks;
+    for (unsigned tile = blockIdx.x; tile < total; tile += gridDim.x) {
+        const int which = tile >= jobs.j[0].blocks ? 1 : 0;       // workgroup-uniform
+        const MapJob& J = jobs.j[which];
+        const unsigned bid = tile - (which ? jobs.j[0].blocks : 0u);
+        const int64_t r0 = static_cast<int64_t>(bid / J.tiles_c) * TR;
+        const int64_t c0 = static_cast<int64_t>(bid % J.tiles_c) * TC;
+        uint32_t m = 0;
+        if (r0 + TR <= J.rows && c0 + TC <= J.cols)
+            map_tile_body<STOCH, false, PASSES, TC, true>(J.x, J.rows, J.cols, J, bits, false, red, J.q, J.qT, key0, key1, J.sid0,
+                                                          J.sid1, r0, c0, stage, guess[which], guess[which] != 0, &m);
+        else
+            map_tile_body<STOCH, true, PASSES, TC, true>(J.x, J.rows, J.cols, J, bits, false, red, J.q, J.qT, key0, key1, J.sid0,
+                                                         J.sid1, r0, c0, stage, guess[which], guess[which] != 0, &m);
+        seen[which] = max(seen[which], m);
+        __syncthreads();      // the staging area is read by other threads than those that fill it for the next tile
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        if (jobs.j[j].blocks == 0) continue;
+        const uint32_t m = block_max(seen[j], red);
+        if (threadIdx.x == 0) jobs.j[j].guess_partials[blockIdx.x] = m;
+    }
 }
 
 // One element per thread, any shape and alignment.
@@ -330,6 +404,9 @@ static MapJob make_job(const MapTensor& t, int tc, int passes) {
     j.sid1 = static_cast<uint32_t>(t.stream_id >> 32);
     j.tiles_c = static_cast<int>((t.cols + tc - 1) / tc);
     j.blocks = static_cast<unsigned>(((t.rows + tr - 1) / tr) * j.tiles_c);
+    j.e_guess = nullptr;
+    j.guess_partials = nullptr;
+    j.guess_used = nullptr;
     return j;
 }
 
@@ -352,6 +429,72 @@ static void launch_tiles(const MapJobs& jobs, int tc, int passes, bool stoch, ui
     else { FXP_MAP_PICK(64); }
 #undef FXP_MAP_PICK
 #undef FXP_MAP_LAUNCH
+}
+
+static void launch_tiles_guess(const MapJobs& jobs, unsigned grid_x, int tc, int passes, bool stoch, uint32_t k0, uint32_t k1,
+                               int bits, hipStream_t s) {
+    const dim3 grid(grid_x), block(kMapThreads);
+#define FXP_MAP_LAUNCH(STOCH, PASSES, TC) \
+    hipLaunchKernelGGL((k_map_tile_guess<STOCH, PASSES, TC>), grid, block, 0, s, jobs, k0, k1, bits)
+#define FXP_MAP_PICK(TC)                                   \
+    if (stoch) {                                           \
+        if (passes == 4) FXP_MAP_LAUNCH(true, 4, TC);      \
+        else if (passes == 2) FXP_MAP_LAUNCH(true, 2, TC); \
+        else FXP_MAP_LAUNCH(true, 1, TC);                  \
+    } else {                                               \
+        if (passes == 4) FXP_MAP_LAUNCH(false, 4, TC);     \
+        else if (passes == 2) FXP_MAP_LAUNCH(false, 2, TC);\
+        else FXP_MAP_LAUNCH(false, 1, TC);                 \
+    }
+    if (tc == 128) { FXP_MAP_PICK(128); }
+    else { FXP_MAP_PICK(64); }
+#undef FXP_MAP_PICK
+#undef FXP_MAP_LAUNCH
+}
+
+// Scale + map of one or two tensors (b may be null) with the scales their e_out words hold on entry taken as
+// guesses: one pass over the tensors and a launch that verifies (and repairs, should a guess be off).  area_a /
+// area_b: kMaxPartials words of scratch each.  Returns kNoGuessPath when the tensors do not take the tiled
+// kernel together or are too small for the guess to pay (the caller then takes the two-pass path).
+int scale_map_guess_launch(const MapTensor& a, const MapTensor* b, uint32_t* area_a, uint32_t* area_b, uint64_t seed,
+                           int rounding, int bits, hipStream_t s) {
+    const MapPlan pa = plan_map(a);
+    const MapPlan pb = b ? plan_map(*b) : pa;
+    if (!pa.tile_path || !pb.tile_path || pa.tc != pb.tc) return kNoGuessPath;
+    const int64_t na = a.rows * a.cols, nb = b ? b->rows * b->cols : 0;
+    // below a few million elements a scale reduction costs what the verifying launch costs
+    if (std::max(na, nb) < kGuessMinElements) return kNoGuessPath;
+    const int passes = na >= nb ? pa.passes : pb.passes;
+    MapJobs jobs;
+    jobs.j[0] = make_job(a, pa.tc, passes);
+    if (b) jobs.j[1] = make_job(*b, pa.tc, passes);
+    else { jobs.j[1] = jobs.j[0]; jobs.j[1].blocks = 0; }
+    const uint64_t total = static_cast<uint64_t>(jobs.j[0].blocks) + jobs.j[1].blocks;
+    if (total >= (uint64_t{1} << 31)) return kNoGuessPath;
+    const unsigned grid = static_cast<unsigned>(std::min<uint64_t>(total, kGuessBlocks));
+    uint32_t* areas[2] = {area_a, area_b};
+    const MapTensor* ts[2] = {&a, b};
+    for (int j = 0; j < 2; ++j) {
+        if (jobs.j[j].blocks == 0) continue;
+        jobs.j[j].e_guess = ts[j]->e_out;                                   // last step's scale, if the caller kept it
+        jobs.j[j].guess_partials = areas[j];
+        jobs.j[j].guess_used = reinterpret_cast<int32_t*>(areas[j] + kGuessBlocks);
+        jobs.j[j].e_in = nullptr;
+        jobs.j[j].partials = nullptr;
+    }
+    const bool stoch = rounding == FXP_ROUND_STOCHASTIC;
+    const uint32_t k0 = static_cast<uint32_t>(seed), k1 = static_cast<uint32_t>(seed >> 32);
+    launch_tiles_guess(jobs, grid, pa.tc, passes, stoch, k0, k1, bits, s);
+    int rc = launch_status();
+    if (rc) return rc;
+    // the launch that verifies: an ordinary map launch that takes the workgroup maxima as block maxima
+    for (int j = 0; j < 2; ++j) {
+        if (jobs.j[j].blocks == 0) continue;
+        jobs.j[j].partials = areas[j];
+        jobs.j[j].n_partials = static_cast<int>(grid);
+    }
+    launch_tiles(jobs, pa.tc, passes, stoch, k0, k1, bits, s);
+    return launch_status();
 }
 
 int map_launch(const MapTensor& t, uint64_t seed, int rounding, int bits, hipStream_t s) {

@@ -76,6 +76,10 @@ def lib():
     L.fxp_map_absmax.argtypes = [vp, i64, i64, vp, vp, vp, vp, u64, u64, ci, ci, vp]
     L.fxp_linear_fwd.argtypes = [vp, vp, i64, i64, i64, vp, c.POINTER(_Saved), u64, u64, ci, ci, vp, sz, vp]
     L.fxp_linear_bwd.argtypes = [vp, c.POINTER(_Saved), i64, i64, i64, vp, vp, vp, vp, vp, u64, u64, ci, ci, vp, sz, vp]
+    L.fxp_linear_fwd_guess.argtypes = L.fxp_linear_fwd.argtypes
+    L.fxp_linear_bwd_guess.argtypes = L.fxp_linear_bwd.argtypes
+    L.fxp_linear_fwd_guess.restype = ci
+    L.fxp_linear_bwd_guess.restype = ci
     L.fxp_linear_fwd_static.argtypes = [vp, vp, i64, i64, i64, vp, c.POINTER(_Saved), u64, u64, ci, ci, vp]
     L.fxp_linear_fwd_static.restype = ci
     L.fxp_static_scratch_bytes.restype = sz
@@ -287,13 +291,15 @@ class LayerBuffers:
         return self.e[2:3]
 
 
-def linear_fwd(X, W, buf, seed=0, step=0, rounding=STOCHASTIC, bits=8):
-    """Y = unmap(map(X) map(W)); fills buf.Xq/XqT/Wq/WqT/eX/eW and returns buf.Y."""
+def linear_fwd(X, W, buf, seed=0, step=0, rounding=STOCHASTIC, bits=8, guess=False):
+    """Y = unmap(map(X) map(W)); fills buf.Xq/XqT/Wq/WqT/eX/eW and returns buf.Y.  guess: the scales buf.e holds
+    from the previous call are taken as guesses (fxp_linear_fwd_guess)."""
     X, W = _dev(X, torch.float32, "X"), _dev(W, torch.float32, "W")
     M, K = X.shape
     if W.shape[0] != K or (M, K, W.shape[1]) != (buf.M, buf.K, buf.N):
         raise FxpError("shapes do not match the layer buffers")
-    _check(lib().fxp_linear_fwd(_p(X), _p(W), M, K, buf.N, _p(buf.Y), ctypes.byref(buf.saved), seed, step, rounding,
+    fn = lib().fxp_linear_fwd_guess if guess else lib().fxp_linear_fwd
+    _check(fn(_p(X), _p(W), M, K, buf.N, _p(buf.Y), ctypes.byref(buf.saved), seed, step, rounding,
                                 bits, _p(buf.ws), buf.ws.numel(), _stream()), "fxp_linear_fwd")
     return buf.Y
 
@@ -309,14 +315,15 @@ def linear_fwd_static(X, W, buf, seed=0, step=0, rounding=STOCHASTIC, bits=8):
     return buf.Y
 
 
-def linear_bwd(dY, buf, seed=0, step=0, rounding=STOCHASTIC, bits=8, need_dX=True, need_dW=True):
+def linear_bwd(dY, buf, seed=0, step=0, rounding=STOCHASTIC, bits=8, need_dX=True, need_dW=True, guess=False):
     """(dX, dW) from the upstream gradient and the operands the forward call saved."""
     dY = _dev(dY, torch.float32, "dY")
     if tuple(dY.shape) != (buf.M, buf.N):
         raise FxpError("shapes do not match the layer buffers")
     dX = buf.dX if need_dX else None
     dW = buf.dW if need_dW else None
-    _check(lib().fxp_linear_bwd(_p(dY), ctypes.byref(buf.saved), buf.M, buf.K, buf.N, _p(dX), _p(dW), _p(buf.dYq),
+    fn = lib().fxp_linear_bwd_guess if guess else lib().fxp_linear_bwd
+    _check(fn(_p(dY), ctypes.byref(buf.saved), buf.M, buf.K, buf.N, _p(dX), _p(dW), _p(buf.dYq),
                                 _p(buf.dYqT), buf.e[2:3].data_ptr(), seed, step, rounding, bits, _p(buf.ws),
                                 buf.ws.numel(), _stream()), "fxp_linear_bwd")
     return dX, dW
