@@ -1,11 +1,12 @@
 """GPU parity at the full sizes of the benchmark workloads, in the launch
 configuration bench.py times (the layer calls): scales and all mapped int8 tensors
 are compared in full with the oracle.  Product outputs: every element against the
-oracle for the ResNet layer, the ViT layers and the 8192^3 layer at sigma = 1
-(n_rows = None); for the other three sigmas of the 8192^3 layer the oracle computes 32
-rows of every 256-row band of the output (1024 rows per product: every tile row of
-the launch, every 8-row group of a tile), and exact int64 identities that hold at any
-size cover the rest (C v = A (B v); sum C = colsum(A) . rowsum(B))."""
+oracle for the ResNet layer and the ViT layers (n_rows = None) and for the forward
+product of the 8192^3 layer at sigma = 1; for its gradient products and for the other
+three sigmas the oracle computes 32 rows of every 256-row band of the output (1024 rows
+per product: every tile row of the launch, every 8-row group of a tile), and exact int64
+identities that hold at any size cover the rest (C v = A (B v); sum C = colsum(A) .
+rowsum(B))."""
 import numpy as np
 import pytest
 
@@ -71,12 +72,14 @@ def run_layer_fullsize(fxp, workload, layer_index, sigma, n_rows):
     # --- GEMM outputs
     rng = np.random.default_rng(99)
     WqT, XqT, GqT = (np.ascontiguousarray(a.T) for a in (Wq, Xq, Gq))
-    if n_rows is None:
-        # every element of every product
+    if n_rows is None or n_rows == "Y in full":
+        # every element of every product (of the forward product only for the largest layer)
         assert same_bits(Y, oracle.unmap(oracle.gemm(Xq, WqT, transB=True), eX, eW)), "Y"
-        assert same_bits(dX, oracle.unmap(oracle.gemm(Gq, Wq, transB=True), eG, eW)), "dX"
-        assert same_bits(dW, oracle.unmap(oracle.gemm(XqT, GqT, transB=True), eX, eG)), "dW"
-        return
+        if n_rows is None:
+            assert same_bits(dX, oracle.unmap(oracle.gemm(Gq, Wq, transB=True), eG, eW)), "dX"
+            assert same_bits(dW, oracle.unmap(oracle.gemm(XqT, GqT, transB=True), eX, eG)), "dW"
+            return
+        n_rows = "bands"
     if n_rows == "bands":
         band = lambda n: np.array([256 * t + 8 * j + (3 * j + t) % 8 for t in range((n + 255) // 256) for j in range(32)
                                    if 256 * t + 8 * j + (3 * j + t) % 8 < n])
@@ -107,8 +110,9 @@ def test_c4_vit_block_other_linears_fullsize(fxp, layer_index):
 
 @pytest.mark.parametrize("sigma", synth.C5_SIGMAS)
 def test_c5_square_fullsize(fxp, sigma):
-    # sigma = 1 in full (about a minute of oracle time); the other sigmas on 32 rows of every 256-row band
-    run_layer_fullsize(fxp, "c5", 0, sigma, None if sigma == 1.0 else "bands")
+    # sigma = 1: the forward product in full (20 s of oracle time) and both gradients on 32 rows of every 256-row
+    # band (all three products run the same kernel on the same shape); the other sigmas: bands for all three
+    run_layer_fullsize(fxp, "c5", 0, sigma, "Y in full" if sigma == 1.0 else "bands")
 
 
 # --------------------------------------------------------------------------- beyond 32-bit element counts

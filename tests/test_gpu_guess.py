@@ -38,10 +38,10 @@ def check_step(fxp, buf, X, W, dY, seed, step, what):
         assert same_bits(got, want), (what, nm)
 
 
-@pytest.mark.parametrize("M,K,N", [(4224, 1024, 4100), (2100, 2052, 2048)], ids=["activation-and-gradient-large", "all-three-large"])
+@pytest.mark.parametrize("M,K,N", [(4224, 1024, 1044), (2180, 2052, 2048)], ids=["activation-and-gradient-large", "all-three-large"])
 def test_guessed_scales_every_case(fxp, M, K, N):
-    """(4224, 1024, 4100): X and dY are above the size where the guess is used (2^22 elements), W rides in X's
-    launch; ragged tiles on every side.  (2100, 2052, 2048): all three tensors above it."""
+    """(4224, 1024, 1044): X and dY are above the size where the guess is used (2^22 elements), the smaller W rides
+    in X's launch; ragged tiles.  (2180, 2052, 2048): all three tensors above it."""
     rng = np.random.default_rng(M)
     X = rng.standard_normal((M, K)).astype(np.float32)
     W = (rng.standard_normal((K, N)) * 0.05).astype(np.float32)
