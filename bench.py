@@ -205,6 +205,22 @@ def bench_attn(args, torch, fxp, synth, dev):
     ops = 2 * 3 * 2.0 * b * S * S * d
     nq, ns = b * S * d, b * S * S
 
+    # the same steps with every tensor's previous scale as its (right) guess: one pass for scale + map
+    def step_guess(i):
+        fxp.bmm_fwd(td["Q"], td["K"], qk, seed=0, step=i, bits=args.bits, guess=True)
+        fxp.bmm_bwd(td["dS"], qk, seed=0, step=i, bits=args.bits, guess=True)
+        fxp.bmm_fwd(td["P"], td["V"], pv, seed=0, step=i, bits=args.bits, guess=True)
+        fxp.bmm_bwd(td["dO"], pv, seed=0, step=i, bits=args.bits, guess=True)
+
+    for i in range(args.warmup):
+        step_guess(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step_guess(args.warmup + i)
+    torch.cuda.synchronize()
+    ms_guess = (time.perf_counter() - t0) * 1e3 / args.steps
+
     def layer_bytes(na, nb, ny):   # three tensors scaled + mapped to both orientations, three products
         return 10 * (na + nb + ny) + (na + nb + 4 * ny) + (ny + nb + 4 * na) + (na + ny + 4 * nb)
 
@@ -235,6 +251,8 @@ def bench_attn(args, torch, fxp, synth, dev):
                                f"S={g['S_real']} padded to {S}, d={d}: Q K^T and P V, forward + backward",
                    "pass": "per product: scale+map 3 tensors (both orientations), 3 batched int8 GEMMs with fused inverse map",
                    "rounding": "stochastic (Philox-4x32-10)", "bits": args.bits},
+        "with_scale_guesses": {"ms_per_step": round(ms_guess, 4), "value": round(ops / (ms_guess * 1e-3) / 1e12, 3),
+                               "note": "fxp_bmm_fwd_guess / _bwd_guess, every guess right (same inputs every step)"},
         "roofline": dict(bound="hbm", achieved=round(gbs, 1), peak=PEAK_HBM_GBS, unit="GB/s",
                          frac=round(gbs / PEAK_HBM_GBS, 4), kernel="whole step (16 kernels, all HBM-bound)",
                          algorithmic_per_launch=step_bytes, traffic=read_step_traffic("layer_step_vitb_attn")),

@@ -282,6 +282,15 @@ int fxp_bmm_bwd(const float* dY, const fxp_bmm_saved* saved, int64_t batch, int6
                 int transB, float* dA, float* dBm, int8_t* dYq, int8_t* dYqT, int32_t* e_dY, uint64_t seed,
                 uint64_t step, int rounding, int bits, void* ws, size_t ws_bytes, void* stream);
 
+/* fxp_bmm_fwd / fxp_bmm_bwd with the scales saved->eA, saved->eB and e_dY hold on entry taken as guesses: see
+ * fxp_linear_fwd_guess.  Same results bit for bit. */
+int fxp_bmm_fwd_guess(const float* A, const float* Bm, int64_t batch, int64_t M, int64_t K, int64_t N, int transB, float* Y,
+                      const fxp_bmm_saved* saved, uint64_t seed, uint64_t step, int rounding, int bits, void* ws,
+                      size_t ws_bytes, void* stream);
+int fxp_bmm_bwd_guess(const float* dY, const fxp_bmm_saved* saved, int64_t batch, int64_t M, int64_t K, int64_t N,
+                      int transB, float* dA, float* dBm, int8_t* dYq, int8_t* dYqT, int32_t* e_dY, uint64_t seed,
+                      uint64_t step, int rounding, int bits, void* ws, size_t ws_bytes, void* stream);
+
 /* ---- int16 weight update (Remark 5, App. A.4: w_hat_{k+1} = w_hat_k + alpha_hat_k * g_hat, every term in fixed
  * point with stochastic rounding; the paper's runs use "int16 SGD", Sec. 5) ----
  * fxp_axpy16: z = x_hat + SR(a_hat * y_hat) over n elements.  x_hat, y_hat, a_hat are the 16-bit instance of

@@ -54,6 +54,7 @@ int map_launch(const MapTensor& t, uint64_t seed, int rounding, int bits, hipStr
 constexpr unsigned kGuessBlocks = 1008;            // workgroups of a guessing launch: their maxima and the guess fit one scratch area
 constexpr int64_t kGuessMinElements = int64_t{1} << 22;
 constexpr int kNoGuessPath = 2;
+constexpr int kGuessOneByOne = 3;
 int scale_map_guess_launch(const MapTensor& a, const MapTensor* b, uint32_t* area_a, uint32_t* area_b, uint64_t seed,
                            int rounding, int bits, hipStream_t s);
 int map_launch2(const MapTensor& a, const MapTensor& b, uint64_t seed, int rounding, int bits, hipStream_t s);

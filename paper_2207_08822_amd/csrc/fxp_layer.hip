@@ -35,6 +35,25 @@ static void timeline_mark(hipStream_t s, int tag) {
     g_timeline.tags[g_timeline.used++] = tag;
 }
 
+// scale + map of the two operands of a forward pass: with guesses where that path applies (both in one pair of
+// launches, or each tensor by itself when their tile widths differ), else two launches for both
+static int scale_map_operands(const MapTensor& a, const MapTensor& b, uint32_t* area_a, uint32_t* area_b, uint64_t seed,
+                              int rounding, int bits, hipStream_t s, bool guess) {
+    int rc = guess ? scale_map_guess_launch(a, &b, area_a, area_b, seed, rounding, bits, s) : kNoGuessPath;
+    if (rc == kNoGuessPath) return scale_and_map2(a, b, seed, rounding, bits, s);
+    if (rc != kGuessOneByOne) return rc;
+    const MapTensor* ts[2] = {&a, &b};
+    uint32_t* areas[2] = {area_a, area_b};
+    for (int j = 0; j < 2; ++j) {
+        const MapTensor& t = *ts[j];
+        rc = scale_map_guess_launch(t, nullptr, areas[j], nullptr, seed, rounding, bits, s);
+        if (rc == kNoGuessPath)
+            rc = scale_and_map(t.x, t.rows, t.cols, t.e_out, t.q, t.qT, seed, t.stream_id, rounding, bits, areas[j], s);
+        if (rc) return rc;
+    }
+    return FXP_OK;
+}
+
 static int check_layer(int64_t M, int64_t K, int64_t N, int rounding, int bits, const void* ws, size_t ws_bytes,
                        size_t need) {
     if (M <= 0 || K <= 0 || N <= 0) return FXP_ERR_DIMS;
@@ -108,6 +127,7 @@ static int linear_fwd_run(const float* X, const float* W, int64_t M, int64_t K, 
     timeline_mark(s, FXP_TL_ENTRY);
     // with the scales of the last step as guesses: one pass that maps and finds the maxima, one launch that verifies
     int rc = guess ? scale_map_guess_launch(tX, &tW, pX, pW, seed, rounding, bits, s) : kNoGuessPath;
+    if (rc == kGuessOneByOne) rc = scale_map_operands(tX, tW, pX, pW, seed, rounding, bits, s, true);
     if (rc == kNoGuessPath) {
         // scale + map of both operands in two launches: one reduction launch and one map launch cover both tensors
         rc = scale_partials2(X, static_cast<size_t>(M * K), pX, &tX.n_partials, W, static_cast<size_t>(K * N), pW, &tW.n_partials, s);
@@ -316,10 +336,10 @@ static int check_bmm(int64_t batch, int64_t M, int64_t K, int64_t N, int roundin
 }
 }  // namespace fxp
 
-extern "C" int fxp_bmm_fwd(const float* A, const float* Bm, int64_t batch, int64_t M, int64_t K, int64_t N, int transB,
-                           float* Y, const fxp_bmm_saved* saved, uint64_t seed, uint64_t step, int rounding, int bits,
-                           void* ws, size_t ws_bytes, void* stream) {
-    using namespace fxp;
+namespace fxp {
+static int bmm_fwd_impl(const float* A, const float* Bm, int64_t batch, int64_t M, int64_t K, int64_t N, int transB,
+                        float* Y, const fxp_bmm_saved* saved, uint64_t seed, uint64_t step, int rounding, int bits,
+                        void* ws, size_t ws_bytes, void* stream, bool guess) {
     int rc = check_bmm(batch, M, K, N, rounding, bits, ws, ws_bytes, fxp_workspace_bytes(FXP_OP_BMM_FWD, M, N, K));
     if (rc) return rc;
     if (K > kMaxContraction) return FXP_ERR_OVERFLOW;
@@ -333,17 +353,30 @@ extern "C" int fxp_bmm_fwd(const float* A, const float* Bm, int64_t batch, int64
     const int64_t b_rows = transB ? N : K, b_cols = transB ? K : N;
     const MapTensor tA{A, batch * M, K, nullptr, pA, 0, saved->eA, saved->Aq, saved->AqT, (step << 8) | FXP_TAG_X};
     const MapTensor tB{Bm, batch * b_rows, b_cols, nullptr, pB, 0, saved->eB, saved->Bq, saved->BqT, (step << 8) | FXP_TAG_W};
-    if ((rc = scale_and_map2(tA, tB, seed, rounding, bits, s))) return rc;
+    if ((rc = scale_map_operands(tA, tB, pA, pB, seed, rounding, bits, s, guess))) return rc;
     const int8_t* Bop = transB ? saved->Bq : saved->BqT;
     const int64_t ldb = transB ? K : batch * K, strideB = transB ? N * K : K;
     return gemm_nt_batched_launch(M, N, K, saved->Aq, K, M * K, Bop, ldb, strideB, Y, N, M * N, batch, true, saved->eA, bits,
                                   saved->eB, bits, s);
 }
+}  // namespace fxp
 
-extern "C" int fxp_bmm_bwd(const float* dY, const fxp_bmm_saved* saved, int64_t batch, int64_t M, int64_t K, int64_t N,
-                           int transB, float* dA, float* dBm, int8_t* dYq, int8_t* dYqT, int32_t* e_dY, uint64_t seed,
-                           uint64_t step, int rounding, int bits, void* ws, size_t ws_bytes, void* stream) {
-    using namespace fxp;
+extern "C" int fxp_bmm_fwd(const float* A, const float* Bm, int64_t batch, int64_t M, int64_t K, int64_t N, int transB,
+                           float* Y, const fxp_bmm_saved* saved, uint64_t seed, uint64_t step, int rounding, int bits,
+                           void* ws, size_t ws_bytes, void* stream) {
+    return fxp::bmm_fwd_impl(A, Bm, batch, M, K, N, transB, Y, saved, seed, step, rounding, bits, ws, ws_bytes, stream, false);
+}
+
+extern "C" int fxp_bmm_fwd_guess(const float* A, const float* Bm, int64_t batch, int64_t M, int64_t K, int64_t N, int transB,
+                                 float* Y, const fxp_bmm_saved* saved, uint64_t seed, uint64_t step, int rounding, int bits,
+                                 void* ws, size_t ws_bytes, void* stream) {
+    return fxp::bmm_fwd_impl(A, Bm, batch, M, K, N, transB, Y, saved, seed, step, rounding, bits, ws, ws_bytes, stream, true);
+}
+
+namespace fxp {
+static int bmm_bwd_impl(const float* dY, const fxp_bmm_saved* saved, int64_t batch, int64_t M, int64_t K, int64_t N,
+                        int transB, float* dA, float* dBm, int8_t* dYq, int8_t* dYqT, int32_t* e_dY, uint64_t seed,
+                        uint64_t step, int rounding, int bits, void* ws, size_t ws_bytes, void* stream, bool guess) {
     int rc = check_bmm(batch, M, K, N, rounding, bits, ws, ws_bytes, fxp_workspace_bytes(FXP_OP_BMM_BWD, M, N, K));
     if (rc) return rc;
     if (N > kMaxContraction || M > kMaxContraction) return FXP_ERR_OVERFLOW;
@@ -351,9 +384,14 @@ extern "C" int fxp_bmm_bwd(const float* dY, const fxp_bmm_saved* saved, int64_t 
         return FXP_ERR_NULL;
     if (!aligned(dY, 4) || !aligned(dA, 4) || !aligned(dBm, 4) || !aligned(e_dY, 4)) return FXP_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if ((rc = scale_and_map(dY, batch * M, N, e_dY, dYq, dYqT, seed, (step << 8) | FXP_TAG_DY, rounding, bits,
-                            static_cast<uint32_t*>(ws), s)))
-        return rc;
+    {
+        const MapTensor t{dY, batch * M, N, nullptr, static_cast<uint32_t*>(ws), 0, e_dY, dYq, dYqT, (step << 8) | FXP_TAG_DY};
+        rc = guess ? scale_map_guess_launch(t, nullptr, static_cast<uint32_t*>(ws), nullptr, seed, rounding, bits, s) : kNoGuessPath;
+        if (rc == kNoGuessPath)
+            rc = scale_and_map(dY, batch * M, N, e_dY, dYq, dYqT, seed, (step << 8) | FXP_TAG_DY, rounding, bits,
+                               static_cast<uint32_t*>(ws), s);
+        if (rc) return rc;
+    }
     if (dA) {
         const int8_t* Bop = transB ? saved->BqT : saved->Bq;      // [K,N] per matrix, N contiguous
         const int64_t ldb = transB ? batch * N : N, strideB = transB ? N : K * N;
@@ -372,4 +410,19 @@ extern "C" int fxp_bmm_bwd(const float* dY, const fxp_bmm_saved* saved, int64_t 
         if (rc) return rc;
     }
     return FXP_OK;
+}
+}  // namespace fxp
+
+extern "C" int fxp_bmm_bwd(const float* dY, const fxp_bmm_saved* saved, int64_t batch, int64_t M, int64_t K, int64_t N,
+                           int transB, float* dA, float* dBm, int8_t* dYq, int8_t* dYqT, int32_t* e_dY, uint64_t seed,
+                           uint64_t step, int rounding, int bits, void* ws, size_t ws_bytes, void* stream) {
+    return fxp::bmm_bwd_impl(dY, saved, batch, M, K, N, transB, dA, dBm, dYq, dYqT, e_dY, seed, step, rounding, bits, ws, ws_bytes,
+                             stream, false);
+}
+
+extern "C" int fxp_bmm_bwd_guess(const float* dY, const fxp_bmm_saved* saved, int64_t batch, int64_t M, int64_t K, int64_t N,
+                                 int transB, float* dA, float* dBm, int8_t* dYq, int8_t* dYqT, int32_t* e_dY, uint64_t seed,
+                                 uint64_t step, int rounding, int bits, void* ws, size_t ws_bytes, void* stream) {
+    return fxp::bmm_bwd_impl(dY, saved, batch, M, K, N, transB, dA, dBm, dYq, dYqT, e_dY, seed, step, rounding, bits, ws, ws_bytes,
+                             stream, true);
 }

@@ -460,10 +460,11 @@ int scale_map_guess_launch(const MapTensor& a, const MapTensor* b, uint32_t* are
                            int rounding, int bits, hipStream_t s) {
     const MapPlan pa = plan_map(a);
     const MapPlan pb = b ? plan_map(*b) : pa;
-    if (!pa.tile_path || !pb.tile_path || pa.tc != pb.tc) return kNoGuessPath;
     const int64_t na = a.rows * a.cols, nb = b ? b->rows * b->cols : 0;
     // below a few million elements a scale reduction costs what the verifying launch costs
     if (std::max(na, nb) < kGuessMinElements) return kNoGuessPath;
+    if (!pa.tile_path || !pb.tile_path) return kNoGuessPath;
+    if (pa.tc != pb.tc) return kGuessOneByOne;        // different tile widths: no common launch, but each may guess alone
     const int passes = na >= nb ? pa.passes : pb.passes;
     MapJobs jobs;
     jobs.j[0] = make_job(a, pa.tc, passes);

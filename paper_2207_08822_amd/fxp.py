@@ -102,6 +102,10 @@ def lib():
     L.fxp_bmm_fwd.argtypes = [vp, vp, i64, i64, i64, i64, ci, vp, c.POINTER(_Saved), u64, u64, ci, ci, vp, sz, vp]
     L.fxp_bmm_bwd.argtypes = [vp, c.POINTER(_Saved), i64, i64, i64, i64, ci, vp, vp, vp, vp, vp, u64, u64, ci, ci, vp, sz,
                               vp]
+    L.fxp_bmm_fwd_guess.argtypes = L.fxp_bmm_fwd.argtypes
+    L.fxp_bmm_bwd_guess.argtypes = L.fxp_bmm_bwd.argtypes
+    L.fxp_bmm_fwd_guess.restype = ci
+    L.fxp_bmm_bwd_guess.restype = ci
     L.fxp_map2.argtypes = [c.POINTER(_MapDesc), c.POINTER(_MapDesc), u64, ci, ci, vp]
     L.fxp_scale_map2.argtypes = [c.POINTER(_MapDesc), c.POINTER(_MapDesc), u64, ci, ci, vp, sz, vp]
     L.fxp_map2.restype = ci
@@ -369,25 +373,25 @@ class BmmBuffers:
                             self.e[1:2].data_ptr())
 
 
-def bmm_fwd(A, Bm, buf, seed=0, step=0, rounding=STOCHASTIC, bits=8):
+def bmm_fwd(A, Bm, buf, seed=0, step=0, rounding=STOCHASTIC, bits=8, guess=False):
     """Y_b = unmap(map(A)_b op(map(Bm)_b)); fills buf.Aq/AqT/Bq/BqT/e[0:2] and returns buf.Y."""
     A, Bm = _dev(A, torch.float32, "A"), _dev(Bm, torch.float32, "Bm")
     if tuple(A.shape) != tuple(buf.Aq.shape) or tuple(Bm.shape) != tuple(buf.Bq.shape):
         raise FxpError("shapes do not match the layer buffers")
-    _check(lib().fxp_bmm_fwd(_p(A), _p(Bm), buf.batch, buf.M, buf.K, buf.N, int(buf.transB), _p(buf.Y),
+    _check((lib().fxp_bmm_fwd_guess if guess else lib().fxp_bmm_fwd)(_p(A), _p(Bm), buf.batch, buf.M, buf.K, buf.N, int(buf.transB), _p(buf.Y),
                              ctypes.byref(buf.saved), seed, step, rounding, bits, _p(buf.ws), buf.ws.numel(), _stream()),
            "fxp_bmm_fwd")
     return buf.Y
 
 
-def bmm_bwd(dY, buf, seed=0, step=0, rounding=STOCHASTIC, bits=8, need_dA=True, need_dB=True):
+def bmm_bwd(dY, buf, seed=0, step=0, rounding=STOCHASTIC, bits=8, need_dA=True, need_dB=True, guess=False):
     """(dA, dBm) from the upstream gradient and the operands the forward call saved."""
     dY = _dev(dY, torch.float32, "dY")
     if tuple(dY.shape) != (buf.batch, buf.M, buf.N):
         raise FxpError("shapes do not match the layer buffers")
     dA = buf.dA if need_dA else None
     dB = buf.dB if need_dB else None
-    _check(lib().fxp_bmm_bwd(_p(dY), ctypes.byref(buf.saved), buf.batch, buf.M, buf.K, buf.N, int(buf.transB), _p(dA),
+    _check((lib().fxp_bmm_bwd_guess if guess else lib().fxp_bmm_bwd)(_p(dY), ctypes.byref(buf.saved), buf.batch, buf.M, buf.K, buf.N, int(buf.transB), _p(dA),
                              _p(dB), _p(buf.dYq), _p(buf.dYqT), buf.e[2:3].data_ptr(), seed, step, rounding, bits,
                              _p(buf.ws), buf.ws.numel(), _stream()), "fxp_bmm_bwd")
     return dA, dB

@@ -81,3 +81,33 @@ def test_guessed_scales_small_layer_takes_the_two_pass_path(fxp):
     buf = fxp.LayerBuffers(300, 200, 100)
     for step in range(2):
         check_step(fxp, buf, X, W, dY, 1, step, "small")
+
+
+def test_guessed_scales_batched_products(fxp):
+    """fxp_bmm_fwd_guess / _bwd_guess on attention-shaped products large enough for the guess to be used: scores
+    (A and Bm of equal tile width: one pair of launches) and context (P 208 wide, V 64 wide: different tile widths,
+    each tensor guesses by itself); first call, hit, and a miss in every tensor."""
+    rng = np.random.default_rng(5)
+    batch, S, d = 340, 208, 64                                   # 340 * 208 * 64 = 4.5 M elements per Q / K / V
+    Q = rng.standard_normal((batch, S, d)).astype(np.float32)
+    Kt = rng.standard_normal((batch, S, d)).astype(np.float32)
+    dS = (rng.standard_normal((batch, S, S)) * 1e-3).astype(np.float32)
+    P = np.abs(rng.standard_normal((batch, S, S))).astype(np.float32)
+    V = rng.standard_normal((batch, S, d)).astype(np.float32)
+    dO = (rng.standard_normal((batch, S, d)) * 1e-3).astype(np.float32)
+    for name, A, Bm, dY, transB in (("scores", Q, Kt, dS, True), ("context", P, V, dO, False)):
+        M, K = A.shape[1:]
+        N = dY.shape[2]
+        buf = fxp.BmmBuffers(batch, M, K, N, transB)
+        for step, (fa, fb, fg) in enumerate([(1, 1, 1), (1, 1, 1), (32, 1, 1 / 64), (32, 1 / 16, 1 / 64), (1, 1, 1)]):
+            say("bmm guess", name, step, (fa, fb, fg))
+            a, b, g = A * np.float32(fa), Bm * np.float32(fb), dY * np.float32(fg)
+            Y = host(fxp.bmm_fwd(dev(a), dev(b), buf, 2, step, guess=True))
+            dA, dB = fxp.bmm_bwd(dev(g), buf, 2, step, guess=True)
+            Yo, sv = oracle.bmm_fwd(a, b, transB, 2, step)
+            dAo, dBo, aux = oracle.bmm_bwd(g, sv, 2, step)
+            assert host(buf.e).tolist() == [sv["eA"], sv["eB"], aux["eG"]], (name, step)
+            assert np.array_equal(host(buf.Aq), sv["Aq"]) and np.array_equal(host(buf.Bq), sv["Bq"]), (name, step)
+            assert np.array_equal(host(buf.AqT), sv["Aq"].reshape(batch * M, K).T), (name, step)
+            assert np.array_equal(host(buf.dYq), aux["dYq"]), (name, step)
+            assert same_bits(Y, Yo) and same_bits(host(dA), dAo) and same_bits(host(dB), dBo), (name, step)
