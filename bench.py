@@ -91,7 +91,7 @@ def read_step_traffic(name):
         with open(os.path.join(ROOT, "profiles", name + ".txt")) as f:
             for line in f:
                 if line.startswith("HBM bytes per step"):
-                    return float(line.split("):", 1)[1].split(";")[0])
+                    return float(line.split(":", 1)[1].split(";")[0])
     except (OSError, ValueError, IndexError):
         pass
     return None
@@ -120,6 +120,16 @@ def copy_calibration(torch, dev):
     torch.cuda.synchronize()
 
 
+def step_only_line(args, torch, dev, metric, unit, value, ms, dtype, workload):
+    """--step-only: nothing but the steps has run (what a profiler should see); print the bare line and stop."""
+    if args.copy_calibration:
+        copy_calibration(torch, dev)
+    print(json.dumps({"metric": metric, "value": round(value, 3), "unit": unit, "n_gpus": 1, "steps": args.steps,
+                      "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
+                      "vs_baseline": None, "dtype": dtype, "data": "synthetic", "config": {"workload": workload},
+                      "roofline": None, "cpu_baseline": None}))
+
+
 def bench_conv(args, torch, fxp, synth, dev):
     """The c2 layer given as a convolution (channels-last): map the activation once, int8 im2col, GEMMs,
     gather col2im.  Same integer work as c2 (3 x 2*M*K*Cout), far fewer fp32 bytes."""
@@ -141,6 +151,9 @@ def bench_conv(args, torch, fxp, synth, dev):
     ms = (time.perf_counter() - t0) * 1e3 / args.steps
     M, K, Cout = g["N"] * buf.Ho * buf.Wo, g["KH"] * g["KW"] * g["C"], g["Cout"]
     ops = 3 * 2.0 * M * K * Cout
+    if args.step_only:
+        return step_only_line(args, torch, dev, "int8 fixed-point layer fwd+bwd TOPS", "TOPS", ops / (ms * 1e-3) / 1e12, ms,
+                              "int8", "c2conv")
     nx, nw, ny = X.size, Wt.size, dY.size
     # algorithmic HBM bytes of every kernel of the step: scale + map of X (one
     # copy), W and dY (both copies); forward GEMM reading the image and the weights; transposed patches of X and the
@@ -204,6 +217,9 @@ def bench_attn(args, torch, fxp, synth, dev):
     ms = (time.perf_counter() - t0) * 1e3 / args.steps
     ops = 2 * 3 * 2.0 * b * S * S * d
     nq, ns = b * S * d, b * S * S
+    if args.step_only:
+        return step_only_line(args, torch, dev, "int8 fixed-point layer fwd+bwd TOPS", "TOPS", ops / (ms * 1e-3) / 1e12, ms,
+                              "int8", "vitb_attn")
 
     # the same steps with every tensor's previous scale as its (right) guess: one pass for scale + map
     def step_guess(i):
@@ -254,7 +270,7 @@ def bench_attn(args, torch, fxp, synth, dev):
         "with_scale_guesses": {"ms_per_step": round(ms_guess, 4), "value": round(ops / (ms_guess * 1e-3) / 1e12, 3),
                                "note": "fxp_bmm_fwd_guess / _bwd_guess, every guess right (same inputs every step)"},
         "roofline": dict(bound="hbm", achieved=round(gbs, 1), peak=PEAK_HBM_GBS, unit="GB/s",
-                         frac=round(gbs / PEAK_HBM_GBS, 4), kernel="whole step (16 kernels, all HBM-bound)",
+                         frac=round(gbs / PEAK_HBM_GBS, 4), kernel="whole step (15 kernels, all HBM-bound)",
                          algorithmic_per_launch=step_bytes, traffic=read_step_traffic("layer_step_vitb_attn")),
         "cpu_baseline": cpu,
     }))
@@ -279,6 +295,9 @@ def bench_sgd(args, torch, fxp, synth, dev):
         step(args.warmup + i)
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    if args.step_only:
+        return step_only_line(args, torch, dev, "int16 SGD step (weight decay + momentum) G elements/s", "G elements/s",
+                              n / (ms * 1e-3) / 1e9, ms, "int16", "sgd16")
     # scales of w, g, v (4 B each) + three lines of 8 B read, 4 B written
     step_bytes = 48 * n
     gbs = step_bytes / (ms * 1e-3) / 1e9
@@ -338,6 +357,9 @@ def bench_sgd_multi(args, torch, fxp, synth, dev):
         return (time.perf_counter() - t0) * 1e3 / steps
 
     ms = run(step, args.steps)
+    if args.step_only:
+        return step_only_line(args, torch, dev, "int16 SGD step (weight decay + momentum) G elements/s", "G elements/s",
+                              n / (ms * 1e-3) / 1e9, ms, "int16", "sgd16_multi")
     ms_loop = run(step_per_tensor, max(3, args.steps // 5))
     step_bytes = 48 * n
     gbs = step_bytes / (ms * 1e-3) / 1e9

@@ -106,6 +106,7 @@ struct MapJob {
     uint32_t sid0, sid1;
     int tiles_c;
     unsigned blocks;
+    unsigned xcd_blocks;    // leading workgroups whose tiles are numbered per XCD (see tile_of_workgroup)
     // scale taken as a guess (see k_map_tile_guess): where the guess comes from, where the workgroup maxima of
     // the guessing launch go, and the word that records which guess the tensor was mapped with (0 = none)
     const int32_t* e_guess;
@@ -115,6 +116,25 @@ struct MapJob {
 struct MapJobs {
     MapJob j[2];
 };
+
+// Row block and column block of workgroup `bid` of a tensor.  Plain numbering walks the column tiles of a row
+// block first.  Where a row is not a whole number of 128-byte lines, neighbouring column tiles share the lines
+// their boundary falls into, and workgroups are dealt to the eight XCDs in turn, each with an L2 of its own: such a
+// tensor numbers its tiles so that the column tiles of one row block are eight workgroups apart - the same XCD,
+// one after the other - and the shared lines come from that L2 the second time (row blocks beyond the last
+// whole group of eight keep the plain numbering).
+__device__ inline void tile_of_workgroup(const MapJob& J, unsigned bid, unsigned* rb, unsigned* cb) {
+    const unsigned tc = static_cast<unsigned>(J.tiles_c);
+    if (bid < J.xcd_blocks) {
+        const unsigned group = bid / (8u * tc), local = bid % (8u * tc);
+        *rb = group * 8u + (local & 7u);
+        *cb = local >> 3;
+    } else {
+        const unsigned i = bid - J.xcd_blocks;
+        *rb = J.xcd_blocks / tc + i / tc;
+        *cb = i % tc;
+    }
+}
 
 // scale of the tensor: either given, or the max of the per-block maxima (and then
 // block 0 publishes it)
@@ -280,8 +300,10 @@ __global__ __launch_bounds__(kMapThreads) void k_map_tile(const MapJobs jobs, ui
     int8_t* __restrict__ q = J.q;
     int8_t* __restrict__ qT = J.qT;
     const int64_t rows = J.rows, cols = J.cols;
-    const int64_t r0 = static_cast<int64_t>(bid / J.tiles_c) * TR;
-    const int64_t c0 = static_cast<int64_t>(bid % J.tiles_c) * TC;
+    unsigned rb, cb;
+    tile_of_workgroup(J, bid, &rb, &cb);
+    const int64_t r0 = static_cast<int64_t>(rb) * TR;
+    const int64_t c0 = static_cast<int64_t>(cb) * TC;
     if (r0 + TR <= rows && c0 + TC <= cols)
         map_tile_body<STOCH, false, PASSES, TC>(x, rows, cols, J, bits, bid == 0, red, q, qT, key0, key1, J.sid0, J.sid1, r0, c0, stage);
     else
@@ -315,8 +337,10 @@ __global__ __launch_bounds__(kMapThreads) void k_map_tile_guess(const MapJobs jo
         const int which = tile >= jobs.j[0].blocks ? 1 : 0;       // workgroup-uniform
         const MapJob& J = jobs.j[which];
         const unsigned bid = tile - (which ? jobs.j[0].blocks : 0u);
-        const int64_t r0 = static_cast<int64_t>(bid / J.tiles_c) * TR;
-        const int64_t c0 = static_cast<int64_t>(bid % J.tiles_c) * TC;
+        unsigned rb, cb;
+        tile_of_workgroup(J, bid, &rb, &cb);
+        const int64_t r0 = static_cast<int64_t>(rb) * TR;
+        const int64_t c0 = static_cast<int64_t>(cb) * TC;
         uint32_t m = 0;
         if (r0 + TR <= J.rows && c0 + TC <= J.cols)
             map_tile_body<STOCH, false, PASSES, TC, true>(J.x, J.rows, J.cols, J, bits, false, red, J.q, J.qT, key0, key1, J.sid0,
@@ -404,6 +428,8 @@ static MapJob make_job(const MapTensor& t, int tc, int passes) {
     j.sid1 = static_cast<uint32_t>(t.stream_id >> 32);
     j.tiles_c = static_cast<int>((t.cols + tc - 1) / tc);
     j.blocks = static_cast<unsigned>(((t.rows + tr - 1) / tr) * j.tiles_c);
+    const bool shared_lines = j.tiles_c > 1 && t.cols % 128 != 0;
+    j.xcd_blocks = shared_lines ? static_cast<unsigned>((t.rows + tr - 1) / tr / 8 * 8 * j.tiles_c) : 0u;
     j.e_guess = nullptr;
     j.guess_partials = nullptr;
     j.guess_used = nullptr;

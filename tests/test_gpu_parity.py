@@ -63,7 +63,8 @@ def check_map(fxp, x, e_max=None, seed=3, sid=(7 << 8) | 1, rounding=0, bits=8):
 
 
 @pytest.mark.parametrize("shape", [(128, 128), (256, 384), (1, 4), (5, 8), (130, 132), (16, 1000), (333, 260),
-                                   (1000, 16), (48, 4096), (7, 13), (129, 3), (64, 130), (1, 1)])
+                                   (1000, 16), (48, 4096), (7, 13), (129, 3), (64, 130), (1, 1),
+                                   (1100, 208), (2300, 400)])   # rows of partial lines: tiles numbered per XCD
 def test_map_shapes(fxp, shape):
     say("map shape", shape)
     rng = np.random.default_rng(shape[0] * 7919 + shape[1])
