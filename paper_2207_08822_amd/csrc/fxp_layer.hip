@@ -7,6 +7,7 @@
 //   Y  = Xq  [M,K] x WqT [N,K]^T      dX = dYq [M,N] x Wq [K,N]^T
 //   dW = XqT [K,M] x dYqT[N,M]^T
 #include <algorithm>
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -22,13 +23,13 @@ struct Timeline {
     std::vector<hipEvent_t> events;
     std::vector<int> tags;
     size_t used = 0;
-    bool on = false;
+    std::atomic<bool> on{false};
 };
 static Timeline g_timeline;
 static std::mutex g_timeline_lock;
 
 static void timeline_mark(hipStream_t s, int tag) {
-    if (!g_timeline.on) return;                       // (read without the lock: begin / end are not called concurrently with layer calls)
+    if (!g_timeline.on.load(std::memory_order_acquire)) return;     // off: no lock taken on the layer calls' path
     std::lock_guard<std::mutex> hold(g_timeline_lock);
     if (g_timeline.used >= g_timeline.events.size()) return;
     if (hipEventRecord(g_timeline.events[g_timeline.used], s) != hipSuccess) { (void)hipGetLastError(); return; }
